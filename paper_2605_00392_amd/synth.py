@@ -1,0 +1,248 @@
+"""Seeded synthetic visual-token batches shaped like DeepSeek-OCR encoder output.
+
+This module only *draws data*: token tensors, ragged offsets and per-image
+textual-density scalars for the five benchmark workloads, plus the bf16
+storage encoding of those tensors.  It contains none of the pruning method's
+arithmetic, so both the CPU oracle's tests and the HIP path's harness may feed
+from it without sharing any computation.
+
+Shapes follow the encoder's resolution modes (64 / 100 / 256 / 400 tokens of
+width 1280; tiled pages = n tiles x 100 tokens + 256 global-view tokens, see the
+paper's Appendix "Model Architecture of DeepSeek-OCR").  Values are stand-ins
+for real page embeddings, which are not available offline:
+
+* workload 1: unit Gaussian directions times a lognormal(0, 0.5) norm;
+* workloads 2-4: a mixture of unit-norm cluster centres plus isotropic noise of
+  total norm about 0.2 (per-coordinate sigma 0.2/sqrt(D)), so that tokens of a
+  cluster are near-duplicates (cosine about 0.96);
+* workload 5: the same mixture for 70 % of the tokens and 30 % near-copies
+  (cosine about 0.995) of other tokens;
+* everywhere, floor(0.1 N) tokens are scaled x4 as high-norm outliers.
+
+Every image has its own generator seeded by ``1000 * workload + image_index``
+(workload 1 uses seed 0), so any subset of a batch can be regenerated alone.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+D_MODEL = 1280
+
+# Hyper-parameter defaults: z, alpha from Algorithm 1's input line, T from
+# Appendix C; eps and the retention clamp come with the benchmark definition.
+DEFAULT_PARAMS: Dict[str, float] = dict(
+    z=0.2, alpha=0.1, eps=0.05, iters=50, dynamic=0, ratio=0.84,
+    ratio_min=0.6, ratio_max=1.0, phi_lo=0.0, phi_hi=1.0,
+)
+
+
+@dataclass
+class Workload:
+    """Static description of one benchmark workload."""
+    cfg: int
+    name: str
+    batch: int
+    dtype: str                      # "f32" or "bf16"
+    params: Dict[str, float] = field(default_factory=dict)
+    fixed_tokens: Optional[int] = None   # tokens per image, None when ragged
+
+
+def _params(**kw) -> Dict[str, float]:
+    p = dict(DEFAULT_PARAMS)
+    p.update(kw)
+    return p
+
+
+WORKLOADS: Dict[int, Workload] = {
+    1: Workload(1, "c1_single_64tok_f32", 1, "f32", _params(iters=50), 64),
+    2: Workload(2, "c2_b32_256tok_bf16", 32, "bf16", _params(iters=50), 256),
+    3: Workload(3, "c3_b64_400tok_bf16_dyn", 64, "bf16",
+                _params(iters=50, dynamic=1), 400),
+    4: Workload(4, "c4_b128_ragged_bf16_dyn", 128, "bf16",
+                _params(iters=50, dynamic=1), None),
+    5: Workload(5, "c5_b1024_400tok_bf16_dyn_T100", 1024, "bf16",
+                _params(iters=100, dynamic=1), 400),
+}
+
+
+# ---------------------------------------------------------------------------
+# bf16 storage encoding (round-to-nearest-even), as raw uint16 bit patterns
+# ---------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to bfloat16 (RNE) and return the uint16 patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    r = (u + 0x7FFF + lsb) >> 16
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns (uint16) to float32 exactly."""
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+# ---------------------------------------------------------------------------
+# per-image generators
+# ---------------------------------------------------------------------------
+def _rng(cfg: int, image: int) -> np.random.Generator:
+    return np.random.default_rng(0 if cfg == 1 else 1000 * cfg + image)
+
+
+def _scale_outliers(rng: np.random.Generator, x: np.ndarray) -> None:
+    n = x.shape[0]
+    k = n // 10
+    if k:
+        idx = rng.choice(n, size=k, replace=False)
+        x[idx] *= 4.0
+
+
+def _mixture(rng: np.random.Generator, n: int, d: int, k: int) -> np.ndarray:
+    centres = rng.standard_normal((k, d))
+    centres /= np.linalg.norm(centres, axis=1, keepdims=True)
+    labels = rng.integers(0, k, size=n)
+    noise = rng.standard_normal((n, d)) * (0.2 / np.sqrt(d))
+    return centres[labels] + noise
+
+
+def image_token_count(cfg: int, image: int) -> int:
+    """Number of visual tokens of one image of a workload."""
+    w = WORKLOADS[cfg]
+    if w.fixed_tokens is not None:
+        return w.fixed_tokens
+    rng = _rng(cfg, image)
+    tiles = int(rng.integers(2, 10))          # uniform in {2..9}
+    return 100 * tiles + 256
+
+
+def gen_image(cfg: int, image: int, d: int = D_MODEL):
+    """Return ``(tokens_f32 [N, d], density)`` for one image of a workload."""
+    w = WORKLOADS[cfg]
+    rng = _rng(cfg, image)
+    if cfg == 1:
+        n = w.fixed_tokens
+        g = rng.standard_normal((n, d))
+        g /= np.linalg.norm(g, axis=1, keepdims=True)
+        x = g * rng.lognormal(0.0, 0.5, size=(n, 1))
+        _scale_outliers(rng, x)
+        return x.astype(np.float32), np.float32(0.5)
+    if cfg == 2:
+        n = w.fixed_tokens
+        x = _mixture(rng, n, d, 16)
+        _scale_outliers(rng, x)
+        return x.astype(np.float32), np.float32(0.5)
+    if cfg in (3, 4):
+        if cfg == 4:
+            tiles = int(rng.integers(2, 10))
+            n = 100 * tiles + 256
+        else:
+            n = w.fixed_tokens
+        k = int(rng.integers(8, 65))
+        x = _mixture(rng, n, d, k)
+        _scale_outliers(rng, x)
+        rho = rng.uniform(0.1, 0.9)
+        return x.astype(np.float32), np.float32(rho)
+    if cfg == 5:
+        n = w.fixed_tokens
+        n_copy = (3 * n) // 10
+        n_base = n - n_copy
+        k = int(rng.integers(8, 65))
+        base = _mixture(rng, n_base, d, k)
+        src = base[rng.integers(0, n_base, size=n_copy)]
+        e = rng.standard_normal((n_copy, d))
+        e *= (0.1 * np.linalg.norm(src, axis=1, keepdims=True)
+              / np.linalg.norm(e, axis=1, keepdims=True))
+        x = np.concatenate([base, src + e], axis=0)
+        x = x[rng.permutation(n)]
+        _scale_outliers(rng, x)
+        rho = rng.uniform(0.1, 0.9)
+        return x.astype(np.float32), np.float32(rho)
+    raise ValueError(f"unknown workload {cfg}")
+
+
+@dataclass
+class Batch:
+    """A packed ragged batch, as both the oracle and the device harness take it.
+
+    ``tokens`` is float32 ``[total, D]`` for dtype "f32" and uint16 bf16 bit
+    patterns ``[total, D]`` for dtype "bf16"; ``offsets`` is the int32
+    exclusive prefix sum of per-image token counts (``B + 1`` entries).
+    """
+    cfg: int
+    dtype: str
+    tokens: np.ndarray
+    offsets: np.ndarray
+    density: np.ndarray
+    params: Dict[str, float]
+    images: List[int]
+
+    @property
+    def batch(self) -> int:
+        return len(self.offsets) - 1
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self.offsets[-1])
+
+    @property
+    def max_tokens(self) -> int:
+        c = np.diff(self.offsets)
+        return int(c.max()) if len(c) else 0
+
+    def tokens_f32(self) -> np.ndarray:
+        """The exact values the device sees, widened to float32."""
+        if self.dtype == "bf16":
+            return bf16_bits_to_f32(self.tokens)
+        return self.tokens
+
+
+def pack(cfg: int, dtype: str, images_f32: Sequence[np.ndarray],
+         density: Sequence[float], params: Dict[str, float],
+         image_ids: Optional[Sequence[int]] = None) -> Batch:
+    """Pack per-image float32 arrays into a :class:`Batch` of the given dtype."""
+    counts = [int(x.shape[0]) for x in images_f32]
+    offsets = np.zeros(len(counts) + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    d = images_f32[0].shape[1] if images_f32 else D_MODEL
+    if images_f32:
+        flat = np.concatenate(list(images_f32), axis=0).astype(np.float32)
+    else:
+        flat = np.zeros((0, d), dtype=np.float32)
+    tokens = f32_to_bf16_bits(flat) if dtype == "bf16" else flat
+    return Batch(cfg, dtype, tokens, offsets,
+                 np.asarray(density, dtype=np.float32), dict(params),
+                 list(image_ids) if image_ids is not None else list(range(len(counts))))
+
+
+def gen_batch(cfg: int, images: Optional[Sequence[int]] = None,
+              d: int = D_MODEL) -> Batch:
+    """Generate workload ``cfg`` (all images, or the listed image indices)."""
+    w = WORKLOADS[cfg]
+    ids = list(range(w.batch)) if images is None else list(images)
+    xs, rho = [], []
+    for i in ids:
+        x, r = gen_image(cfg, i, d)
+        xs.append(x)
+        rho.append(r)
+    return pack(cfg, w.dtype, xs, rho, w.params, ids)
+
+
+def subset(batch: Batch, picks: Sequence[int]) -> Batch:
+    """Re-pack the listed images (positions within ``batch``) as a new batch."""
+    rows, rho, ids = [], [], []
+    for p in picks:
+        lo, hi = int(batch.offsets[p]), int(batch.offsets[p + 1])
+        rows.append(batch.tokens[lo:hi])
+        rho.append(batch.density[p])
+        ids.append(batch.images[p])
+    counts = [r.shape[0] for r in rows]
+    offsets = np.zeros(len(counts) + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    tokens = (np.concatenate(rows, axis=0) if rows
+              else batch.tokens[:0].copy())
+    return Batch(batch.cfg, batch.dtype, tokens, offsets,
+                 np.asarray(rho, dtype=np.float32), dict(batch.params), ids)
