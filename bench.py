@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused RTPrune operator on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 5]
+
+A step is one pass of the whole hot path (``rtprune_prune``: norms, ratio,
+selection, scores, Sinkhorn, pairing, merge + compaction) over one synthetic
+batch that is already resident in HBM.  Prints ONE JSON line: whole-job
+throughput in images/s (tokens/s alongside), the roofline position of the
+kernel that dominates the step (timed with HIP events inside the timed
+region), and the CPU oracle timed on a bounded sample of the same workload as
+a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP64_VECTOR_TFLOPS = 78.6      # 256 CU x 2.4 GHz x 128 flop/clk
+FP32_VECTOR_TFLOPS = 157.3
+BF16_MFMA_TFLOPS = 2500.0
+
+
+def _gen_one(args):
+    from paper_2605_00392_amd import synth
+    cfg, i = args
+    x, rho = synth.gen_image(cfg, i)
+    return synth.f32_to_bf16_bits(x) if synth.WORKLOADS[cfg].dtype == "bf16" else x, float(rho)
+
+
+def generate(cfg: int):
+    """Draw the workload on the host (a process pool only speeds the drawing up)."""
+    from paper_2605_00392_amd import synth
+    w = synth.WORKLOADS[cfg]
+    if w.batch < 64:
+        return synth.gen_batch(cfg)
+    import multiprocessing as mp
+    workers = max(1, min(16, (os.cpu_count() or 1)))
+    with mp.get_context("fork").Pool(workers) as pool:
+        parts = pool.map(_gen_one, [(cfg, i) for i in range(w.batch)], chunksize=8)
+    counts = [p[0].shape[0] for p in parts]
+    offsets = np.zeros(len(counts) + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    tokens = np.concatenate([p[0] for p in parts], axis=0)
+    dens = np.asarray([p[1] for p in parts], dtype=np.float32)
+    return synth.Batch(cfg, w.dtype, tokens, offsets, dens, dict(w.params), list(range(w.batch)))
+
+
+def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, iters: int):
+    """Algorithmic work of one launch of a kernel over the batch: (bound, amount, unit, peak).
+
+    Bytes are the unavoidable HBM traffic of the step the kernel performs
+    (inputs read once, outputs written once); flops count useful arithmetic.
+    """
+    r = n - m
+    tok_bytes = float(n.sum()) * d * elt
+    if kernel == "k_norms":
+        # every token row read once; 4-byte score + 8-byte squared norm written
+        return "hbm", tok_bytes + 12.0 * n.sum(), "GB/s", HBM_PEAK_GBS
+    if kernel == "k_merge":
+        # kept and pruned rows read once, merged kept rows written once, plan read
+        return "hbm", tok_bytes + float(m.sum()) * d * elt + 4.0 * float((m * r).sum()), "GB/s", HBM_PEAK_GBS
+    if kernel == "k_scores":
+        # fp64 vector arithmetic: one multiply-add per (kept, pruned, d)
+        return "alu", 2.0 * float((m * r).sum()) * d, "TFLOP/s", FP64_VECTOR_TFLOPS
+    if kernel == "k_sinkhorn":
+        # two sweeps of multiply-adds over the augmented matrix per iteration
+        return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
+    return "hbm", 0.0, "GB/s", HBM_PEAK_GBS
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..5 (5 = 1024 x 400 tokens)")
+    ap.add_argument("--cpu-images", type=int, default=192, help="images the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this operator runs on ONE GPU (images are independent; there is no "
+              "multi-GPU path in this build). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    from paper_2605_00392_amd import rtprune as rt
+    from paper_2605_00392_amd import synth
+
+    t0 = time.time()
+    batch = generate(args.workload)          # before the GPU is touched (fork)
+    gen_s = time.time() - t0
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    rt.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    p = rt.make_params(batch.params)
+    db = rt.upload(batch, dev)
+    ws = rt.alloc_workspace(db)
+    B, total, D = db.B, db.total_tokens, db.D
+    out = torch.empty((total, D), dtype=db.tokens.dtype, device=dev)
+    out_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    keep = torch.empty(B, dtype=torch.int32, device=dev)
+    sel = torch.empty(total, dtype=torch.int32, device=dev)
+    pair = torch.empty(total, dtype=torch.int32, device=dev)
+    ratio = torch.empty(B, dtype=torch.float32, device=dev)
+    dens = torch.from_numpy(batch.density).to(dev)
+
+    def step():
+        rt.check(rt.rtprune_prune(db, dens, p, out, out_off, keep, sel, pair, ratio, ws))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rt.rtprune_profile_enable(1)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    rc, prof = rt.rtprune_profile_summary()
+    rt.rtprune_profile_enable(0)
+    rt.check(rc)
+    status = int(ws[:4].view(torch.int32).item())
+    assert status == 0, f"device status {status}"
+
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    images_per_s = B / (ms_per_step * 1e-3)
+    tokens_per_s = total / (ms_per_step * 1e-3)
+    keep_h = keep.cpu().numpy().astype(np.int64)
+    n_h = np.diff(batch.offsets).astype(np.int64)
+    elt = 2 if batch.dtype == "bf16" else 4
+
+    kernels = {}
+    for rec in prof:
+        kernels[rec["kernel"]] = rec["total_ms"] / max(1, rec["launches"])
+    dominant = max(kernels, key=kernels.get) if kernels else None
+    roofline = None
+    if dominant:
+        bound, amount, unit, peak = kernel_work(dominant, n_h, keep_h, D, elt, int(batch.params["iters"]))
+        dur_s = kernels[dominant] * 1e-3
+        achieved = amount / dur_s / (1e9 if unit == "GB/s" else 1e12)
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                traffic = json.load(open(tpath)).get(w.name, {}).get(dominant)
+            except Exception:
+                traffic = None
+        roofline = dict(kernel=dominant, bound=bound, achieved=round(achieved, 3), peak=peak, unit=unit,
+                        frac=round(achieved / peak, 5), traffic=traffic,
+                        avg_launch_ms=round(kernels[dominant], 5),
+                        algorithmic_per_launch=amount)
+    # whole-step HBM floor: every token read once, every kept token written once
+    floor_bytes = float(n_h.sum()) * D * elt + float(keep_h.sum()) * D * elt
+    step_hbm_frac = floor_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import rtprune_oracle as orc
+        from tests import harness
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        k = min(args.cpu_images, B)
+        sub = synth.subset(batch, list(range(k)))
+        op = orc.Params.from_dict(batch.params)
+        c0 = time.perf_counter()
+        res = orc.prune_batch(sub.tokens, sub.dtype, sub.offsets, sub.density, op)
+        c1 = time.perf_counter()
+        # the timed oracle results double as a parity check of the timed device outputs
+        gpu = dict(keep=keep_h, out_offsets=out_off.cpu().numpy(), sel=sel.cpu().numpy(),
+                   pair=pair.cpu().numpy(), ratio=ratio.cpu().numpy(), out=harness._np(out))
+        rep = harness.compare_batch(batch, gpu, images=list(range(0, k, max(1, k // 24))))
+        cpu = dict(value=round(k / (c1 - c0), 3), unit="images/s", cores=int(cores), kind="oracle",
+                   sample=f"first {k} images of {w.name}, float64 numpy oracle, {c1 - c0:.2f} s",
+                   parity_checked_images=rep.images,
+                   near_ties=rep.selection_near_ties + rep.pairing_near_ties)
+        del res
+
+    line = {
+        "metric": "images/s pruned (fused rtprune_prune, 400-token 1280-d bf16 pages)",
+        "value": round(images_per_s, 2),
+        "unit": "images/s",
+        "tokens_per_s": round(tokens_per_s, 1),
+        "kept_tokens": int(keep_h.sum()),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": batch.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "images": B, "total_tokens": int(total), "D": D,
+                   "iters": int(batch.params["iters"]), "eps": batch.params["eps"],
+                   "dynamic": int(batch.params["dynamic"]), "gen_s": round(gen_s, 1)},
+        "kernels_ms": {k_: round(v, 5) for k_, v in kernels.items()},
+        "step_hbm_floor_frac": round(step_hbm_frac, 5),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,202 @@
+/*
+ * rtprune.h - C ABI of the RTPrune batched visual-token reduction operator
+ * for AMD MI355X (gfx950).
+ *
+ * The operator is the training-free step RTPrune places between DeepSeek-OCR's
+ * vision encoder and the language model's prefill (paper: Sec. 3.3, Algorithm 1):
+ *
+ *   stage 1  keep the M tokens of largest l2 norm (Eq. 1, M = N(1-r));
+ *   stage 2  score kept x pruned pairs by cosine similarity (Eq. 3), add a
+ *            dustbin row and column of score z (Eq. 4-5), run T log-domain
+ *            Sinkhorn iterations (Appendix C) to get the transport plan P;
+ *   merge    T_i <- T_i + alpha * sum_j P_ij T_j for every kept token (Eq. 6);
+ *   ratio    optionally choose r per image from the mean pairwise cosine phi
+ *            (Eq. 7) and a textual-density scalar rho: r = f(phi)(1-rho) (Eq. 9).
+ *
+ * Conventions common to every call
+ * --------------------------------
+ * - Every array pointer is a DEVICE pointer owned by the caller, unless marked
+ *   "host".  The library never allocates, frees or synchronises; each call
+ *   enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *   default stream) and returns at once.  Results are valid once the stream
+ *   has reached the end of the call's work.
+ * - A batch is ragged: image b owns token rows offsets[b] .. offsets[b+1]-1 of
+ *   the packed row-major token matrix (row length D).  `offsets` is an int32
+ *   exclusive prefix sum with B+1 entries, offsets[0] = 0,
+ *   offsets[B] = total_tokens.  `total_tokens` and `max_tokens` (an upper
+ *   bound on any image's token count) are host scalars the caller knows.
+ * - Token indices in outputs are LOCAL to their image (0 .. N_b-1).
+ * - "Retention" is 1 - r, the fraction of tokens kept.
+ * - Return value: RTP_OK, or an error found on the host (bad pointer, size,
+ *   dtype or parameter; workspace too small), in which case NOTHING has been
+ *   enqueued.  Errors that only the device can see (offsets not monotone, an
+ *   image longer than max_tokens, offsets[B] != total_tokens) make every kernel
+ *   of the call skip its work, touch no output, and set a nonzero int32 at
+ *   byte 0 of the workspace (see RTP_DEV_*).  No call crashes on bad data.
+ * - Limits: 1 <= D <= 4096 and D % 4 == 0 (D % 8 == 0 for bf16);
+ *   max_tokens <= 8192;
+ *   (max(1,z) - min(-1,z)) / eps <= 600 (else RTP_EUNSUPPORTED).
+ * - Calls are thread-safe as long as concurrent calls use distinct workspaces.
+ */
+#ifndef RTPRUNE_H
+#define RTPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rtp_status {
+  RTP_OK = 0,
+  RTP_EINVAL = 1,       /* NULL pointer, negative size, bad dtype or parameter */
+  RTP_EUNSUPPORTED = 2, /* valid request outside the documented limits */
+  RTP_EWORKSPACE = 3,   /* workspace pointer NULL/unaligned or too small */
+  RTP_EHIP = 4          /* a kernel launch was rejected by the runtime */
+} rtp_status;
+
+typedef enum rtp_dtype {
+  RTP_F32 = 0,          /* IEEE binary32 tokens in, binary32 merged tokens out */
+  RTP_BF16 = 1          /* bfloat16 in and out (merge accumulates in fp32, one RNE) */
+} rtp_dtype;
+
+/* Device-side status word (int32 at byte 0 of the workspace), bit flags. */
+enum {
+  RTP_DEV_OK = 0,
+  RTP_DEV_BAD_OFFSETS = 1,   /* offsets not monotone / offsets[0] != 0 / offsets[B] != total_tokens */
+  RTP_DEV_IMAGE_TOO_LONG = 2 /* some image has more than max_tokens tokens */
+};
+
+/* Hyper-parameters.  Defaults in the paper: z = 0.2, alpha = 0.1 (Algorithm 1,
+ * input line), iters = 100 (Appendix C).  eps, the clamp and the form of
+ * f_normalize are not given by the paper (see each field). */
+typedef struct rtprune_params {
+  float z;         /* dustbin score of Eq. 4 */
+  float alpha;     /* merge strength of Eq. 6 */
+  float eps;       /* entropic temperature: the Sinkhorn log-kernel is S_bar / eps;
+                      eps = 1 uses the scores directly as Appendix C's Z. > 0 */
+  int32_t iters;   /* T, number of Sinkhorn iterations (u then v each). >= 0 */
+  int32_t dynamic; /* 0: fixed retention `ratio`; 1: retention from Eq. 9 */
+  float ratio;     /* fixed retention 1 - r, in (0, 1] */
+  float ratio_min; /* dynamic retention is clamped to [ratio_min, ratio_max] */
+  float ratio_max;
+  float phi_lo;    /* f_normalize(phi) = clamp((phi - phi_lo) / (phi_hi - phi_lo), 0, 1) */
+  float phi_hi;    /* phi_hi > phi_lo */
+} rtprune_params;
+
+/* One packed ragged batch of visual tokens. */
+typedef struct rtprune_batch {
+  const void* tokens;     /* device, [total_tokens, D] row-major, dtype below */
+  const int32_t* offsets; /* device, [B + 1] */
+  int64_t total_tokens;   /* host scalar, = offsets[B] */
+  int32_t B;              /* images */
+  int32_t D;              /* token width */
+  int32_t max_tokens;     /* host scalar, >= every image's token count */
+  int32_t dtype;          /* rtp_dtype */
+} rtprune_batch;
+
+/* Name of a status code (host string, static storage). */
+const char* rtprune_status_string(int status);
+
+/* Bytes of device workspace any call below needs for a batch of this shape.
+ * `bytes` is a host pointer.  The workspace must be 256-byte aligned.  Its
+ * content is scratch: nothing is carried from one call to the next. */
+int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t max_tokens,
+                            int32_t D, int32_t dtype, size_t* bytes);
+
+/* Dynamic pruning ratio (Sec. 3.3.3).  For each image: phi = mean pairwise
+ * cosine over all its tokens (Eq. 7; 0 when N < 2; a zero-norm token has cosine
+ * 0 with everything), retention = clamp(1 - f_normalize(phi) (1 - density[b]),
+ * ratio_min, ratio_max) (Eq. 9), keep_counts[b] = ceil(retention * N_b - 1e-3)
+ * clamped to [1, N_b] (0 when N_b = 0).
+ *   density      [B] fp32 in, textual density rho of Eq. 8 per image, in [0, 1]
+ *   phi          [B] fp32 out (may be NULL)
+ *   ratio        [B] fp32 out, the retention (may be NULL)
+ *   keep_counts  [B] int32 out */
+int rtprune_dynamic_ratio(const rtprune_batch* in, const float* density,
+                          const rtprune_params* params, float* phi, float* ratio,
+                          int32_t* keep_counts, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/* Stage 1, dominant-token selection (Sec. 3.3.1, Eq. 1).  Tokens are ranked by
+ * the fp32 rounding of their exactly accumulated squared norm, larger first,
+ * lower index first among equals; the first M_b are kept.
+ *   keep_counts_in  [B] int32 in, M_b per image (clamped to [min(1,N_b), N_b]);
+ *                   NULL: M_b = ceil(params->ratio * N_b - 1e-3), same clamp
+ *   norms           [total_tokens] fp32 out, ||T_k||_2 (may be NULL)
+ *   sel_idx         [total_tokens] int32 out; image b's segment starts at
+ *                   offsets[b]: first its M_b kept token indices, ascending,
+ *                   then its N_b - M_b pruned ("proposed-to-prune") indices,
+ *                   ascending
+ *   keep_counts     [B] int32 out, M_b (may alias keep_counts_in)
+ *   out_offsets     [B + 1] int32 out, exclusive prefix sum of M_b
+ *   plan_offsets    [B + 1] int64 out, exclusive prefix sum of M_b * (N_b - M_b) */
+int rtprune_norms_topk(const rtprune_batch* in, const int32_t* keep_counts_in,
+                       const rtprune_params* params, float* norms,
+                       int32_t* sel_idx, int32_t* keep_counts,
+                       int32_t* out_offsets, int64_t* plan_offsets,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stage 2, optimal token matching (Sec. 3.3.2, Eq. 2-5; Appendix C).
+ * For each image with R_b = N_b - M_b > 0: S = cosine(kept_i, pruned_j)
+ * (Eq. 3), S_bar = S plus a dustbin row and column of score z (Eq. 4),
+ * Z = S_bar / eps, log mu = [0_M, log R], log nu = [0_R, log M], duals start
+ * at 0, `iters` iterations of (u from v, then v from u), and
+ * P = exp(Z + u 1^T + 1 v^T) without its dustbin row and column.  The device
+ * iterates the same map in multiplicative form in fp64.
+ *   sel_idx, keep_counts, plan_offsets   as written by rtprune_norms_topk
+ *   scores  [sum M_b R_b] fp64 out, S packed row-major (M_b x R_b) at
+ *           plan_offsets[b] (may be NULL)
+ *   plan    [sum M_b R_b] fp32 out, P packed the same way (may be NULL)
+ *   pair    [total_tokens] int32 out, aligned with sel_idx: at a kept token's
+ *           position its own rank i in 0..M_b-1; at a pruned token's position
+ *           the rank of the kept token with the largest fp32 P_bar[i][j] in
+ *           its column (lowest rank wins ties), or -1 when the dustbin row
+ *           holds the column's maximum (may be NULL) */
+int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
+                    const int32_t* keep_counts, const int64_t* plan_offsets,
+                    const rtprune_params* params, double* scores, float* plan,
+                    int32_t* pair, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* Merge and compaction (Eq. 6).  Row out_offsets[b] + i of `out` receives
+ * T[kept_i] + alpha * sum_j plan[i][j] * T[pruned_j] for image b (fp32
+ * accumulation, one rounding to the token dtype); an image with R_b = 0 is
+ * copied through.
+ *   out   [sum M_b, D] same dtype as the tokens */
+int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
+                  const int32_t* keep_counts, const int32_t* out_offsets,
+                  const float* plan, const int64_t* plan_offsets,
+                  const rtprune_params* params, void* out, void* stream);
+
+/* The whole operator (Algorithm 1) on a ragged batch, one enqueue, no host
+ * synchronisation: [ratio ->] stage 1 -> stage 2 -> merge.
+ *   density      [B] fp32 in; read only when params->dynamic (else may be NULL)
+ *   out          device buffer with room for total_tokens rows of D; the first
+ *                out_offsets[B] rows are written
+ *   out_offsets  [B + 1] int32 out
+ *   keep_counts  [B] int32 out (may be NULL)
+ *   sel_idx      [total_tokens] int32 out (may be NULL)
+ *   pair         [total_tokens] int32 out (may be NULL)
+ *   ratio        [B] fp32 out, retention used per image (may be NULL) */
+int rtprune_prune(const rtprune_batch* in, const float* density,
+                  const rtprune_params* params, void* out, int32_t* out_offsets,
+                  int32_t* keep_counts, int32_t* sel_idx, int32_t* pair,
+                  float* ratio, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
+/* Measurement aid (not part of the operator; process-global, not thread-safe).
+ * While enabled, every kernel the calls above launch is bracketed by two HIP
+ * events recorded on the launch stream.  rtprune_profile_enable(1) discards
+ * earlier records and starts recording, (0) stops.  rtprune_profile_summary
+ * waits for the recorded events and writes a JSON array
+ *   [{"kernel": name, "launches": n, "total_ms": t}, ...]
+ * into the host buffer `buf` of `cap` bytes (RTP_EINVAL if it does not fit). */
+int rtprune_profile_enable(int on);
+int rtprune_profile_summary(char* buf, size_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTPRUNE_H */

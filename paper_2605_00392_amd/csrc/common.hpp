@@ -1,0 +1,121 @@
+// Shared device helpers for the RTPrune HIP kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtp {
+
+constexpr int kWave = 64;
+constexpr int kMaxTokens = 8192;   // per image
+constexpr int kMaxD = 4096;
+constexpr double kTinyNorm = 1e-12;
+
+typedef unsigned short bf16_t;     // raw bfloat16 bit pattern
+
+// Hyper-parameters widened once on the host; z, alpha, eps are the doubles of
+// the float32 values the caller passed.
+struct DevParams {
+  double z, alpha, eps;
+  double shift;      // max(1, z): exp((s - shift) / eps) <= 1 for every score s
+  float ratio, ratio_min, ratio_max, phi_lo, phi_hi;
+  int iters, dynamic;
+};
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+
+// Four consecutive elements of a token row, widened to float.
+__device__ __forceinline__ void load4(const bf16_t* p, float (&x)[4]) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  x[0] = __uint_as_float(u.x << 16);
+  x[1] = __uint_as_float(u.x & 0xffff0000u);
+  x[2] = __uint_as_float(u.y << 16);
+  x[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+__device__ __forceinline__ void load4(const float* p, float (&x)[4]) {
+  const float4 u = *reinterpret_cast<const float4*>(p);
+  x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+}
+__device__ __forceinline__ void store4(bf16_t* p, const float (&x)[4]) {
+  uint2 u;
+  u.x = static_cast<uint32_t>(f32_to_bf16(x[0])) | (static_cast<uint32_t>(f32_to_bf16(x[1])) << 16);
+  u.y = static_cast<uint32_t>(f32_to_bf16(x[2])) | (static_cast<uint32_t>(f32_to_bf16(x[3])) << 16);
+  *reinterpret_cast<uint2*>(p) = u;
+}
+__device__ __forceinline__ void store4(float* p, const float (&x)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+}
+
+// Butterfly sum over the 64 lanes of a wave; every lane gets the total.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Sum over a workgroup of NT threads (NT a multiple of 64, <= 1024).  `red`
+// holds at least NT / 64 doubles of LDS.  Every thread gets the total.
+template <int NT>
+__device__ __forceinline__ double block_sum(double v, double* red) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  v = wave_sum(v);
+  __syncthreads();               // `red` may still be read from a previous call
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  double t = 0.0;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) t += red[w];
+  return t;
+}
+
+// Index and extent guards for arrays that arrive from the caller (staged calls):
+// a wrong entry may give a wrong result but never an out-of-bounds access.
+__device__ __forceinline__ int clamp_index(int t, int n) { return min(max(t, 0), n - 1); }
+__device__ __forceinline__ bool plan_fits(long long off, int m, int r, long long cap) {
+  return off >= 0 && off + static_cast<long long>(m) * r <= cap;
+}
+
+// Kept count M = ceil(retention * N - 1e-3) clamped to [1, N] (0 for N = 0).
+// The product and the subtraction are rounded separately (no fused multiply-add)
+// so that the integer is the same one a host evaluation in doubles gives.
+__device__ __forceinline__ int kept_count(float retention, int n) {
+#pragma clang fp contract(off)
+  if (n <= 0) return 0;
+  if (!(retention == retention)) return n;
+  const double prod = static_cast<double>(retention) * static_cast<double>(n);
+  const double v = prod - 1e-3;
+  double c = ceil(v);
+  if (c < 1.0) c = 1.0;
+  if (c > static_cast<double>(n)) c = static_cast<double>(n);
+  return static_cast<int>(c);
+}
+
+// Retention 1 - f_normalize(phi) (1 - rho), clamped (Eq. 9); each operation
+// rounded on its own, phi entering as its float32 value.
+__device__ __forceinline__ float dynamic_retention(double phi, float rho, const DevParams& p) {
+#pragma clang fp contract(off)
+  const double phi32 = static_cast<double>(static_cast<float>(phi));
+  const double lo = static_cast<double>(p.phi_lo), hi = static_cast<double>(p.phi_hi);
+  const double f = fmin(1.0, fmax(0.0, (phi32 - lo) / (hi - lo)));
+  const double r = f * (1.0 - static_cast<double>(rho));
+  const double keep = 1.0 - r;
+  double ret = fmin(static_cast<double>(p.ratio_max), fmax(static_cast<double>(p.ratio_min), keep));
+  if (!(ret == ret)) ret = static_cast<double>(p.ratio_max);
+  return static_cast<float>(ret);
+}
+
+}  // namespace rtp

@@ -1,0 +1,436 @@
+// C ABI of the RTPrune operator: argument checks, workspace layout and kernel
+// launch sequences.  Every entry point only validates on the host and enqueues
+// on the caller's stream; see include/rtprune.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "rtprune.h"
+#include "common.hpp"
+#include "stage1.hpp"
+#include "stage2_ref.hpp"
+
+using namespace rtp;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Byte offsets of the workspace regions for a batch shape.
+struct Layout {
+  size_t status, sqnorm, score, partial, phi, ratio, keep, out_off, plan_off, sel, kmat, plan, total;
+  int chunks_per_image;
+  long long plan_cap;   // entries available in kmat / plan
+};
+
+Layout make_layout(int B, long long total, int max_tokens, int D) {
+  Layout L;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+  L.chunks_per_image = (max_tokens + kNormRowsPerChunk - 1) / kNormRowsPerChunk;
+  if (L.chunks_per_image < 1) L.chunks_per_image = 1;
+  // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4
+  L.plan_cap = total * static_cast<long long>(max_tokens) / 4 + 1;
+  L.status = take(256);
+  L.sqnorm = take(sizeof(double) * total);
+  L.score = take(sizeof(float) * total);
+  L.partial = take(sizeof(double) * static_cast<size_t>(B) * L.chunks_per_image * (D + 1));
+  L.phi = take(sizeof(float) * B);
+  L.ratio = take(sizeof(float) * B);
+  L.keep = take(sizeof(int32_t) * B);
+  L.out_off = take(sizeof(int32_t) * (B + 1));
+  L.plan_off = take(sizeof(long long) * (B + 1));
+  L.sel = take(sizeof(int32_t) * total);
+  L.kmat = take(sizeof(double) * L.plan_cap);
+  L.plan = take(sizeof(float) * L.plan_cap);
+  L.total = at;
+  return L;
+}
+
+template <typename T>
+inline T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+int check_batch(const rtprune_batch* in) {
+  if (!in) return RTP_EINVAL;
+  if (in->B < 0 || in->total_tokens < 0 || in->max_tokens < 0 || in->D <= 0) return RTP_EINVAL;
+  if (in->dtype != RTP_F32 && in->dtype != RTP_BF16) return RTP_EINVAL;
+  if (!in->offsets) return RTP_EINVAL;
+  if (in->total_tokens > 0 && !in->tokens) return RTP_EINVAL;
+  if (reinterpret_cast<uintptr_t>(in->tokens) % 16 != 0) return RTP_EINVAL;
+  if (in->D % 4 != 0 || (in->dtype == RTP_BF16 && in->D % 8 != 0)) return RTP_EUNSUPPORTED;
+  if (in->D > kMaxD || in->max_tokens > kMaxTokens) return RTP_EUNSUPPORTED;
+  if (in->total_tokens > 0x7fffffffLL) return RTP_EUNSUPPORTED;
+  if (in->total_tokens > static_cast<long long>(in->B) * in->max_tokens) return RTP_EINVAL;
+  return RTP_OK;
+}
+
+int check_params(const rtprune_params* p, DevParams* d) {
+  if (!p) return RTP_EINVAL;
+  if (!(p->eps > 0.f) || p->iters < 0) return RTP_EINVAL;
+  if (!std::isfinite(p->z) || !std::isfinite(p->alpha) || !std::isfinite(p->eps)) return RTP_EINVAL;
+  if (p->dynamic) {
+    if (!(p->ratio_min > 0.f) || !(p->ratio_max <= 1.f) || !(p->ratio_min <= p->ratio_max)) return RTP_EINVAL;
+    if (!(p->phi_hi > p->phi_lo)) return RTP_EINVAL;
+  } else {
+    if (!(p->ratio > 0.f) || !(p->ratio <= 1.f)) return RTP_EINVAL;
+  }
+  const double z = p->z, eps = p->eps;
+  const double hi = z > 1.0 ? z : 1.0, lo = z < -1.0 ? z : -1.0;
+  if ((hi - lo) / eps > 600.0) return RTP_EUNSUPPORTED;
+  d->z = z;
+  d->alpha = p->alpha;
+  d->eps = eps;
+  d->shift = hi;
+  d->ratio = p->ratio;
+  d->ratio_min = p->ratio_min;
+  d->ratio_max = p->ratio_max;
+  d->phi_lo = p->phi_lo;
+  d->phi_hi = p->phi_hi;
+  d->iters = p->iters;
+  d->dynamic = p->dynamic ? 1 : 0;
+  return RTP_OK;
+}
+
+int check_ws(const rtprune_batch* in, void* ws, size_t ws_bytes, Layout* L) {
+  *L = make_layout(in->B, in->total_tokens, in->max_tokens, in->D);
+  if (!ws || reinterpret_cast<uintptr_t>(ws) % kAlign != 0 || ws_bytes < L->total) return RTP_EWORKSPACE;
+  return RTP_OK;
+}
+
+inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EHIP; }
+
+#define RTP_TRY(expr)            \
+  do {                           \
+    const int rc_ = (expr);      \
+    if (rc_ != RTP_OK) return rc_; \
+  } while (0)
+
+// ---- per-kernel timing (measurement aid) ------------------------------------
+// When enabled, each kernel launch is bracketed by two HIP events recorded on
+// the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
+
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN, KID_MERGE, KID_COUNT };
+const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
+                                             "k_scores", "k_sinkhorn", "k_merge"};
+struct ProfRec { int kid; hipEvent_t start, stop; };
+struct ProfState {
+  std::mutex mu;
+  bool on = false;
+  std::vector<ProfRec> recs;
+} g_prof;
+
+struct ProfScope {
+  int kid;
+  hipStream_t s;
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool live = false;
+  ProfScope(int kid_, hipStream_t s_) : kid(kid_), s(s_) {
+    if (!g_prof.on) return;
+    if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) return;
+    live = hipEventRecord(start, s) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(stop, s);
+    std::lock_guard<std::mutex> g(g_prof.mu);
+    g_prof.recs.push_back({kid, start, stop});
+  }
+};
+
+// ---- launch helpers -------------------------------------------------------
+
+int launch_prepare(const rtprune_batch* in, int32_t* status, hipStream_t s) {
+  ProfScope prof(KID_PREPARE, s);
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(256), 0, s, in->offsets, in->B,
+                     static_cast<long long>(in->total_tokens), in->max_tokens, status);
+  return launched();
+}
+
+template <typename T>
+int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* ws, float* norms_out,
+                   hipStream_t s) {
+  const dim3 grid(L.chunks_per_image, in->B), block(kNormThreads);
+  const T* tok = static_cast<const T*>(in->tokens);
+  double* sq = at<double>(ws, L.sqnorm);
+  float* sc = at<float>(ws, L.score);
+  double* part = at<double>(ws, L.partial);
+  const int32_t* st = at<int32_t>(ws, L.status);
+  ProfScope prof(KID_NORMS, s);
+  if (in->D <= 1280)
+    hipLaunchKernelGGL((k_norms<T, 5>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, sc,
+                       norms_out, part, L.chunks_per_image, st);
+  else
+    hipLaunchKernelGGL((k_norms<T, 16>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, sc,
+                       norms_out, part, L.chunks_per_image, st);
+  return launched();
+}
+
+int launch_norms(const rtprune_batch* in, int dynamic, const Layout& L, void* ws, float* norms_out,
+                 hipStream_t s) {
+  if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
+  return in->dtype == RTP_BF16 ? launch_norms_t<bf16_t>(in, dynamic, L, ws, norms_out, s)
+                               : launch_norms_t<float>(in, dynamic, L, ws, norms_out, s);
+}
+
+int launch_select(const rtprune_batch* in, const DevParams& p, const float* density,
+                  const int32_t* keep_in, int do_select, const Layout& L, void* ws, float* phi,
+                  float* ratio, int32_t* keep_out, int32_t* sel, hipStream_t s) {
+  if (in->B == 0) return RTP_OK;
+  ProfScope prof(KID_SELECT, s);
+  hipLaunchKernelGGL(k_select, dim3(in->B), dim3(256), 0, s, in->offsets, in->D, p, density, keep_in,
+                     at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
+                     phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+  return launched();
+}
+
+int launch_scan(const rtprune_batch* in, const int32_t* keep, int32_t* out_off, long long* plan_off,
+                const int32_t* status, hipStream_t s) {
+  ProfScope prof(KID_SCAN, s);
+  hipLaunchKernelGGL(k_scan, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, out_off, plan_off,
+                     status);
+  return launched();
+}
+
+template <typename T>
+int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
+                    const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
+                    double* scores_out, hipStream_t s) {
+  const int tiles = (in->max_tokens + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock;
+  const dim3 grid(tiles, in->B), block(256);
+  const T* tok = static_cast<const T*>(in->tokens);
+  ProfScope prof(KID_SCORES, s);
+  if (in->D <= 1280)
+    hipLaunchKernelGGL((k_scores<T, 5>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                       at<double>(ws, L.sqnorm), p, at<double>(ws, L.kmat), L.plan_cap, scores_out,
+                       at<int32_t>(ws, L.status));
+  else
+    hipLaunchKernelGGL((k_scores<T, 16>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep,
+                       plan_off, at<double>(ws, L.sqnorm), p, at<double>(ws, L.kmat), L.plan_cap, scores_out,
+                       at<int32_t>(ws, L.status));
+  return launched();
+}
+
+int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
+              const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
+              int32_t* pair, hipStream_t s) {
+  if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
+  RTP_TRY(in->dtype == RTP_BF16
+              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, s)
+              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, s));
+  ProfScope prof(KID_SINKHORN, s);
+  hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p,
+                     at<double>(ws, L.kmat), L.plan_cap, plan, pair, at<int32_t>(ws, L.status));
+  return launched();
+}
+
+template <typename T>
+int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
+                   const int32_t* keep, const int32_t* out_off, const float* plan,
+                   const long long* plan_off, void* out, const int32_t* status, hipStream_t s) {
+  const int tiles = (in->max_tokens + kMergeRowsPerBlock - 1) / kMergeRowsPerBlock;
+  const dim3 grid(tiles, in->B), block(256);
+  const T* tok = static_cast<const T*>(in->tokens);
+  const float alpha = static_cast<float>(p.alpha);
+  ProfScope prof(KID_MERGE, s);
+  if (in->D <= 1024)
+    hipLaunchKernelGGL((k_merge<T, 1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
+                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+  else if (in->D <= 2048)
+    hipLaunchKernelGGL((k_merge<T, 2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
+                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+  else
+    hipLaunchKernelGGL((k_merge<T, 4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
+                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+  return launched();
+}
+
+int launch_merge(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
+                 const int32_t* out_off, const float* plan, const long long* plan_off, void* out,
+                 const int32_t* status, hipStream_t s) {
+  if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
+  return in->dtype == RTP_BF16
+             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, status, s)
+             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, status, s);
+}
+
+}  // namespace
+
+// ---- exported entry points --------------------------------------------------
+
+extern "C" const char* rtprune_status_string(int status) {
+  switch (status) {
+    case RTP_OK: return "RTP_OK";
+    case RTP_EINVAL: return "RTP_EINVAL: invalid argument";
+    case RTP_EUNSUPPORTED: return "RTP_EUNSUPPORTED: outside the supported limits";
+    case RTP_EWORKSPACE: return "RTP_EWORKSPACE: workspace missing, unaligned or too small";
+    case RTP_EHIP: return "RTP_EHIP: kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int rtprune_profile_enable(int on) {
+  std::lock_guard<std::mutex> g(g_prof.mu);
+  for (ProfRec& r : g_prof.recs) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.recs.clear();
+  g_prof.on = on != 0;
+  return RTP_OK;
+}
+
+extern "C" int rtprune_profile_summary(char* buf, size_t cap) {
+  if (!buf || cap == 0) return RTP_EINVAL;
+  std::lock_guard<std::mutex> g(g_prof.mu);
+  double total_ms[KID_COUNT] = {0};
+  long long launches[KID_COUNT] = {0};
+  for (ProfRec& r : g_prof.recs) {
+    if (hipEventSynchronize(r.stop) != hipSuccess) return RTP_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return RTP_EHIP;
+    total_ms[r.kid] += ms;
+    launches[r.kid] += 1;
+  }
+  std::string out = "[";
+  bool first = true;
+  for (int k = 0; k < KID_COUNT; ++k) {
+    if (!launches[k]) continue;
+    char line[160];
+    std::snprintf(line, sizeof(line), "%s{\"kernel\": \"%s\", \"launches\": %lld, \"total_ms\": %.6f}",
+                  first ? "" : ", ", kKernelNames[k], launches[k], total_ms[k]);
+    out += line;
+    first = false;
+  }
+  out += "]";
+  if (out.size() + 1 > cap) return RTP_EINVAL;
+  std::memcpy(buf, out.c_str(), out.size() + 1);
+  return RTP_OK;
+}
+
+extern "C" int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t max_tokens, int32_t D,
+                                       int32_t dtype, size_t* bytes) {
+  if (!bytes) return RTP_EINVAL;
+  rtprune_batch in;
+  std::memset(&in, 0, sizeof(in));
+  int32_t dummy = 0;
+  in.tokens = nullptr;
+  in.offsets = &dummy;
+  in.total_tokens = 0;
+  in.B = B;
+  in.D = D;
+  in.max_tokens = max_tokens;
+  in.dtype = dtype;
+  RTP_TRY(check_batch(&in));
+  if (total_tokens < 0 || total_tokens > 0x7fffffffLL) return RTP_EINVAL;
+  *bytes = make_layout(B, total_tokens, max_tokens, D).total;
+  return RTP_OK;
+}
+
+extern "C" int rtprune_dynamic_ratio(const rtprune_batch* in, const float* density,
+                                     const rtprune_params* params, float* phi, float* ratio,
+                                     int32_t* keep_counts, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  if (!params->dynamic) {
+    // the dynamic formula is what this call computes; the clamp fields must be valid
+    rtprune_params q = *params;
+    q.dynamic = 1;
+    RTP_TRY(check_params(&q, &p));
+  }
+  if (!density || !keep_counts) return RTP_EINVAL;
+  Layout L;
+  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
+  RTP_TRY(launch_norms(in, 1, L, workspace, nullptr, s));
+  return launch_select(in, p, density, nullptr, 0, L, workspace, phi, ratio, keep_counts, nullptr, s);
+}
+
+extern "C" int rtprune_norms_topk(const rtprune_batch* in, const int32_t* keep_counts_in,
+                                  const rtprune_params* params, float* norms, int32_t* sel_idx,
+                                  int32_t* keep_counts, int32_t* out_offsets, int64_t* plan_offsets,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  rtprune_params q;
+  if (!params) return RTP_EINVAL;
+  q = *params;
+  q.dynamic = 0;
+  if (keep_counts_in) q.ratio = 1.f;   // unused
+  RTP_TRY(check_params(&q, &p));
+  if (!sel_idx || !keep_counts || !out_offsets || !plan_offsets) return RTP_EINVAL;
+  Layout L;
+  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* status = at<int32_t>(workspace, L.status);
+  RTP_TRY(launch_prepare(in, status, s));
+  RTP_TRY(launch_norms(in, 0, L, workspace, norms, s));
+  RTP_TRY(launch_select(in, p, nullptr, keep_counts_in, 1, L, workspace, nullptr, nullptr, keep_counts,
+                        sel_idx, s));
+  return launch_scan(in, keep_counts, out_offsets, reinterpret_cast<long long*>(plan_offsets), status, s);
+}
+
+extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
+                               const int32_t* keep_counts, const int64_t* plan_offsets,
+                               const rtprune_params* params, double* scores, float* plan,
+                               int32_t* pair, void* workspace, size_t workspace_bytes, void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  if (!sel_idx || !keep_counts || !plan_offsets) return RTP_EINVAL;
+  Layout L;
+  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
+  // exact squared norms of every row (fp32 norms from stage 1 would cost 1e-7 on S)
+  RTP_TRY(launch_norms(in, 0, L, workspace, nullptr, s));
+  return launch_ot(in, p, sel_idx, keep_counts, reinterpret_cast<const long long*>(plan_offsets), L,
+                   workspace, scores, plan, pair, s);
+}
+
+extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
+                             const int32_t* keep_counts, const int32_t* out_offsets, const float* plan,
+                             const int64_t* plan_offsets, const rtprune_params* params, void* out,
+                             void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  if (!sel_idx || !keep_counts || !out_offsets || !plan || !plan_offsets || !out) return RTP_EINVAL;
+  return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan,
+                      reinterpret_cast<const long long*>(plan_offsets), out, nullptr,
+                      static_cast<hipStream_t>(stream));
+}
+
+extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
+                             const rtprune_params* params, void* out, int32_t* out_offsets,
+                             int32_t* keep_counts, int32_t* sel_idx, int32_t* pair, float* ratio,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  if (!out || !out_offsets) return RTP_EINVAL;
+  if (p.dynamic && !density) return RTP_EINVAL;
+  Layout L;
+  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* status = at<int32_t>(workspace, L.status);
+  int32_t* keep = keep_counts ? keep_counts : at<int32_t>(workspace, L.keep);
+  int32_t* sel = sel_idx ? sel_idx : at<int32_t>(workspace, L.sel);
+  long long* plan_off = at<long long>(workspace, L.plan_off);
+  float* plan = at<float>(workspace, L.plan);
+  RTP_TRY(launch_prepare(in, status, s));
+  RTP_TRY(launch_norms(in, p.dynamic, L, workspace, nullptr, s));
+  RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
+  RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s));
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, s));
+  return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, status, s);
+}

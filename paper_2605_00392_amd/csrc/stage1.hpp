@@ -1,0 +1,279 @@
+// Stage 1 and the dynamic ratio: token norms (Eq. 1), the similarity statistic
+// phi (Eq. 7) through the identity
+//     sum_{i<j} cos(T_i, T_j) = ( || sum_k T_k/||T_k|| ||^2 - sum_k ||T_k/||T_k|| ||^2 ) / 2,
+// the retention of Eq. 9, the kept count M = N(1-r), and the top-M selection.
+#pragma once
+#include "common.hpp"
+
+namespace rtp {
+
+constexpr int kNormRowsPerChunk = 128;  // token rows one workgroup of k_norms covers
+constexpr int kNormThreads = 256;
+
+// Validate the ragged layout; every later kernel of the call skips its work
+// when the status word is nonzero.
+__global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ offsets, int B,
+                                                 long long total_tokens, int max_tokens,
+                                                 int32_t* __restrict__ status) {
+  __shared__ int bad;
+  if (threadIdx.x == 0) bad = 0;
+  __syncthreads();
+  int flags = 0;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    const int lo = offsets[b], hi = offsets[b + 1];
+    if (hi < lo || lo < 0) flags |= RTP_DEV_BAD_OFFSETS;
+    else if (hi - lo > max_tokens) flags |= RTP_DEV_IMAGE_TOO_LONG;
+  }
+  if (threadIdx.x == 0) {
+    if (offsets[0] != 0) flags |= RTP_DEV_BAD_OFFSETS;
+    if (static_cast<long long>(offsets[B]) != total_tokens) flags |= RTP_DEV_BAD_OFFSETS;
+  }
+  if (flags) atomicOr(&bad, flags);
+  __syncthreads();
+  if (threadIdx.x == 0) status[0] = bad;
+}
+
+// One wave per token row.  A lane owns the 4-element groups g = lane + 64 k,
+// k < KMAX, of the row (D <= 256 KMAX).  The squared norm is accumulated in
+// fp64 (bf16 x bf16 and fp32 x fp32 products are exact in fp64), so its fp32
+// rounding - the selection score - does not depend on summation order except
+// in astronomically rare rounding-boundary cases.
+//
+// When `dynamic`, the workgroup also sums T_k / max(||T_k||, tiny) over its rows
+// and writes the D-vector (plus sum_k ||unit_k||^2 as element D) to
+// partial[(b * chunks_per_image + chunk) * (D + 1) ...].
+template <typename T, int KMAX>
+__global__ __launch_bounds__(kNormThreads) void k_norms(
+    const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
+    double* __restrict__ sqnorm, float* __restrict__ score, float* __restrict__ norms_out,
+    double* __restrict__ partial, int chunks_per_image, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  const int r0 = chunk * kNormRowsPerChunk;
+  if (r0 >= n) return;
+  const int r1 = min(n, r0 + kNormRowsPerChunk);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ngroups = D >> 2;
+
+  double acc[KMAX][4];
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[k][e] = 0.0;
+  double wsum = 0.0;
+
+  for (int r = r0 + wave; r < r1; r += kNormThreads / kWave) {
+    const T* row = tokens + static_cast<size_t>(lo + r) * D;
+    float x[KMAX][4];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const int g = lane + kWave * k;
+      if (g < ngroups) load4(row + 4 * g, x[k]);
+      else x[k][0] = x[k][1] = x[k][2] = x[k][3] = 0.f;
+    }
+    double q = 0.0;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const double v = static_cast<double>(x[k][e]);
+        q = fma(v, v, q);
+      }
+    q = wave_sum(q);
+    if (lane == 0) {
+      sqnorm[lo + r] = q;
+      score[lo + r] = static_cast<float>(q);
+      if (norms_out) norms_out[lo + r] = static_cast<float>(sqrt(q));
+    }
+    if (dynamic) {
+      const double inv = 1.0 / fmax(sqrt(q), kTinyNorm);
+      wsum += q * inv * inv;
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[k][e] = fma(static_cast<double>(x[k][e]), inv, acc[k][e]);
+    }
+  }
+  if (!dynamic) return;
+
+  // Sum the four waves' vectors through LDS, one wave's contribution at a time.
+  __shared__ double lds[kWave * KMAX * 4];
+  __shared__ double lds_w;
+  constexpr int kWaves = kNormThreads / kWave;
+  for (int w = 1; w < kWaves; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lds[(k * 4 + e) * kWave + lane] = acc[k][e];
+      if (lane == 0) lds_w = wsum;
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[k][e] += lds[(k * 4 + e) * kWave + lane];
+      wsum += lds_w;
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    double* out = partial + (static_cast<size_t>(b) * chunks_per_image + chunk) * (D + 1);
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const int g = lane + kWave * k;
+      if (g < ngroups) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[k][e];
+      }
+    }
+    if (lane == 0) out[D] = wsum;
+  }
+}
+
+// One workgroup per image: phi and the retention (when dynamic), the kept
+// count, and (when `do_select`) the top-M selection.
+//
+// Selection: a score's fp32 bit pattern orders like its value (scores are
+// >= 0; NaN patterns sort above +inf, which keeps the order total).  The rank
+// of token k is the number of tokens that precede it in (score descending,
+// index ascending) order; it is kept iff rank < M.  Kept and pruned indices
+// are then written in ascending order.
+__global__ __launch_bounds__(256) void k_select(
+    const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
+    const int32_t* __restrict__ keep_in, const float* __restrict__ score,
+    const double* __restrict__ partial, int chunks_per_image, int do_select,
+    float* __restrict__ phi_out, float* __restrict__ ratio_out, int32_t* __restrict__ keep_out,
+    int32_t* __restrict__ sel_idx, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  __shared__ uint32_t keys[kMaxTokens];
+  __shared__ unsigned char kept_flag[kMaxTokens];
+  __shared__ double red[4];
+  __shared__ int counts[256];
+  __shared__ int s_m;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+
+  double phi = 0.0;
+  float ret32 = p.ratio;
+  if (p.dynamic) {
+    if (n >= 2) {
+      const int nchunks = (n + kNormRowsPerChunk - 1) / kNormRowsPerChunk;
+      const double* base = partial + static_cast<size_t>(b) * chunks_per_image * (D + 1);
+      double local = 0.0;
+      for (int d = tid; d < D; d += 256) {
+        double s = 0.0;
+        for (int c = 0; c < nchunks; ++c) s += base[static_cast<size_t>(c) * (D + 1) + d];
+        local = fma(s, s, local);
+      }
+      const double ss = block_sum<256>(local, red);
+      double w = 0.0;
+      for (int c = 0; c < nchunks; ++c) w += base[static_cast<size_t>(c) * (D + 1) + D];
+      phi = (ss - w) / (static_cast<double>(n) * static_cast<double>(n - 1));
+    }
+    ret32 = dynamic_retention(phi, density[b], p);
+  }
+  if (tid == 0) {
+    int m;
+    if (keep_in && !p.dynamic) {
+      m = keep_in[b];
+      m = n > 0 ? min(n, max(1, m)) : 0;
+    } else {
+      m = kept_count(ret32, n);
+    }
+    s_m = m;
+    keep_out[b] = m;
+    if (phi_out) phi_out[b] = static_cast<float>(phi);
+    if (ratio_out) ratio_out[b] = ret32;
+  }
+  if (!do_select || n == 0) return;
+  for (int k = tid; k < n; k += 256) keys[k] = __float_as_uint(score[lo + k]);
+  __syncthreads();
+  const int m = s_m;
+
+  for (int k = tid; k < n; k += 256) {
+    const uint32_t mine = keys[k];
+    int rank = 0;
+    for (int l = 0; l < n; ++l) {
+      const uint32_t other = keys[l];
+      rank += (other > mine) || (other == mine && l < k);
+    }
+    kept_flag[k] = rank < m;
+  }
+  __syncthreads();
+
+  // Each thread owns a contiguous span of tokens; exclusive scan of the spans'
+  // kept counts gives every token its position in the ascending kept / pruned lists.
+  const int span = (n + 255) / 256;
+  const int k0 = min(n, tid * span), k1 = min(n, k0 + span);
+  int c = 0;
+  for (int k = k0; k < k1; ++k) c += kept_flag[k];
+  counts[tid] = c;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const int v = tid >= o ? counts[tid - o] : 0;
+    __syncthreads();
+    counts[tid] += v;
+    __syncthreads();
+  }
+  int kept_before = counts[tid] - c;
+  for (int k = k0; k < k1; ++k) {
+    if (kept_flag[k]) {
+      sel_idx[lo + kept_before] = k;
+      ++kept_before;
+    } else {
+      sel_idx[lo + m + (k - kept_before)] = k;
+    }
+  }
+}
+
+// Exclusive prefix sums over the images: out_offsets = scan(M_b) (int32),
+// plan_offsets = scan(M_b * R_b) (int64).  One workgroup.
+__global__ __launch_bounds__(256) void k_scan(const int32_t* __restrict__ offsets,
+                                              const int32_t* __restrict__ keep, int B,
+                                              int32_t* __restrict__ out_offsets,
+                                              long long* __restrict__ plan_offsets,
+                                              const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  __shared__ long long sm[256];
+  __shared__ long long sp[256];
+  const int tid = threadIdx.x;
+  const int span = (B + 255) / 256;
+  const int b0 = min(B, tid * span), b1 = min(B, b0 + span);
+  long long cm = 0, cp = 0;
+  for (int b = b0; b < b1; ++b) {
+    const long long m = keep[b];
+    const long long n = offsets[b + 1] - offsets[b];
+    cm += m;
+    cp += m * (n - m);
+  }
+  sm[tid] = cm;
+  sp[tid] = cp;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const long long vm = tid >= o ? sm[tid - o] : 0, vp = tid >= o ? sp[tid - o] : 0;
+    __syncthreads();
+    sm[tid] += vm;
+    sp[tid] += vp;
+    __syncthreads();
+  }
+  long long am = sm[tid] - cm, ap = sp[tid] - cp;
+  for (int b = b0; b < b1; ++b) {
+    if (out_offsets) out_offsets[b] = static_cast<int32_t>(am);
+    if (plan_offsets) plan_offsets[b] = ap;
+    const long long m = keep[b];
+    const long long n = offsets[b + 1] - offsets[b];
+    am += m;
+    ap += m * (n - m);
+  }
+  if (tid == 255) {
+    if (out_offsets) out_offsets[B] = static_cast<int32_t>(sm[255]);
+    if (plan_offsets) plan_offsets[B] = sp[255];
+  }
+}
+
+}  // namespace rtp

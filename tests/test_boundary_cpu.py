@@ -1,0 +1,124 @@
+"""Host-only checks of the C ABI: the library loads, exports every function the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_00392_amd import rtprune as rt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(rtprune_\w+)\s*\(", text))
+    return names
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rt.LIB_PATH):
+        from paper_2605_00392_amd.build import build_library
+        build_library()
+    return rt.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    declared = _declared()
+    assert declared == set(rt.EXPORTS), declared ^ set(rt.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(rt.rtprune_params) == 40
+    assert ctypes.sizeof(rt.rtprune_batch) == 40
+    assert rt.rtprune_batch.total_tokens.offset == 16 and rt.rtprune_batch.dtype.offset == 36
+
+
+def test_status_strings(lib):
+    assert rt.status_string(rt.RTP_OK) == "RTP_OK"
+    for code in (rt.RTP_EINVAL, rt.RTP_EUNSUPPORTED, rt.RTP_EWORKSPACE, rt.RTP_EHIP):
+        assert rt.status_string(code).startswith("RTP_E")
+    assert "unknown" in rt.status_string(99)
+
+
+def test_workspace_bytes(lib):
+    rc, small = rt.rtprune_workspace_bytes(1, 64, 64, 1280, rt.RTP_F32)
+    assert rc == rt.RTP_OK and small > 0 and small % 256 == 0
+    rc, big = rt.rtprune_workspace_bytes(1024, 409600, 400, 1280, rt.RTP_BF16)
+    assert rc == rt.RTP_OK and big > small
+    assert rt.rtprune_workspace_bytes(0, 0, 0, 1280, rt.RTP_BF16)[0] == rt.RTP_OK
+    assert rt.rtprune_workspace_bytes(-1, 0, 0, 1280, rt.RTP_BF16)[0] == rt.RTP_EINVAL
+    assert rt.rtprune_workspace_bytes(1, 64, 64, 1280, 7)[0] == rt.RTP_EINVAL
+    assert rt.rtprune_workspace_bytes(1, 64, 64, 1282, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
+    assert rt.rtprune_workspace_bytes(1, 64, 64, 1284, rt.RTP_BF16)[0] == rt.RTP_EUNSUPPORTED
+    assert rt.rtprune_workspace_bytes(1, 64, 64, 8192, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
+    assert rt.rtprune_workspace_bytes(1, 10000, 10000, 1280, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
+
+
+def _fake_batch(**kw):
+    # addresses are never dereferenced: every call below must fail validation first
+    v = dict(tokens=0x1000, offsets=0x2000, total_tokens=64, max_tokens=64, B=1, D=1280, dtype=rt.RTP_BF16)
+    v.update(kw)
+    return rt.DeviceBatch(**v)
+
+
+class _FakeWs:
+    def __init__(self, n, addr=0x10000):
+        self.n, self.addr = n, addr
+
+    def numel(self):
+        return self.n
+
+    def is_contiguous(self):
+        return True
+
+    def data_ptr(self):
+        return self.addr
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    ok = rt.make_params(dynamic=0, ratio=0.84)
+    ws = _FakeWs(1 << 30)
+    b = _fake_batch()
+    call = lambda batch, p, w=ws: rt.rtprune_prune(batch, 0x3000, p, 0x4000, 0x5000, None, None, None, None, w, stream=0)
+    assert call(_fake_batch(B=-1), ok) == rt.RTP_EINVAL
+    assert call(_fake_batch(D=0), ok) == rt.RTP_EINVAL
+    assert call(_fake_batch(dtype=5), ok) == rt.RTP_EINVAL
+    assert call(_fake_batch(tokens=None), ok) == rt.RTP_EINVAL
+    assert call(_fake_batch(tokens=0x1004), ok) == rt.RTP_EINVAL          # misaligned
+    assert call(_fake_batch(offsets=None), ok) == rt.RTP_EINVAL
+    assert call(_fake_batch(total_tokens=100), ok) == rt.RTP_EINVAL        # > B * max_tokens
+    assert call(_fake_batch(max_tokens=9000, total_tokens=64), ok) == rt.RTP_EUNSUPPORTED
+    assert call(_fake_batch(D=1290), ok) == rt.RTP_EUNSUPPORTED
+    assert call(b, rt.make_params(eps=0.0)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(eps=-1.0)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(iters=-1)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(ratio=0.0)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(ratio=1.5)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(z=float("nan"))) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(dynamic=1, ratio_min=0.0)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(dynamic=1, phi_lo=0.5, phi_hi=0.5)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(eps=0.001)) == rt.RTP_EUNSUPPORTED       # exp range
+    assert call(b, ok, _FakeWs(1024)) == rt.RTP_EWORKSPACE                 # too small
+    assert call(b, ok, _FakeWs(1 << 30, addr=0x10010)) == rt.RTP_EWORKSPACE  # unaligned
+    assert rt.rtprune_prune(b, 0x3000, ok, None, 0x5000, None, None, None, None, ws, stream=0) == rt.RTP_EINVAL
+    assert rt.rtprune_prune(b, None, rt.make_params(dynamic=1), 0x4000, 0x5000, None, None, None, None, ws,
+                            stream=0) == rt.RTP_EINVAL                      # dynamic needs density
+    # staged entry points: required pointers
+    assert rt.rtprune_dynamic_ratio(b, None, ok, None, None, 0x6000, ws, stream=0) == rt.RTP_EINVAL
+    assert rt.rtprune_norms_topk(b, None, ok, None, None, 0x6000, 0x7000, 0x8000, ws, stream=0) == rt.RTP_EINVAL
+    assert rt.rtprune_ot_pair(b, None, 0x6000, 0x8000, ok, None, None, None, ws, stream=0) == rt.RTP_EINVAL
+    assert rt.rtprune_merge(b, 0x6000, 0x6100, 0x6200, None, 0x8000, ok, 0x9000, stream=0) == rt.RTP_EINVAL
+
+
+def test_missing_library_is_an_error_not_a_fallback(tmp_path):
+    with pytest.raises(rt.RtpruneError):
+        rt.load_library(str(tmp_path / "nope.so"))

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Bars: index sets bit-exact except counted near-ties
+(relative gap < 1e-6 in the oracle's own fp32 scores); merged bf16 features
+within 1e-3 + 2e-3 |o| of the oracle's unrounded value and within 0.52 bf16 ulp;
+retention within 1e-5."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import rtprune_oracle as orc  # noqa: E402
+from paper_2605_00392_amd import rtprune as rt  # noqa: E402
+from paper_2605_00392_amd import synth  # noqa: E402
+from tests import harness as hz  # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    rt.load_library()          # raises if the HIP library is missing: no fallback
+
+
+def _log(rep, name):
+    print(f"\n[{name}] images={rep.images} ratio_boundary={rep.ratio_boundary} "
+          f"sel_near_ties={rep.selection_near_ties} pair_near_ties={rep.pairing_near_ties}/{rep.pairs_checked} "
+          f"max_ratio_err={rep.max_ratio_err:.2e} max_row_rel={rep.max_merge_row_rel:.2e} "
+          f"max_plan_rel={rep.max_plan_rel:.2e} max_score_abs={rep.max_score_abs:.2e}", flush=True)
+    for n in rep.notes:
+        print("   ", n, flush=True)
+
+
+def _assert_fused_equals_staged(f, s, batch):
+    np.testing.assert_array_equal(f["keep"], s["keep"])
+    np.testing.assert_array_equal(f["out_offsets"], s["out_offsets"])
+    np.testing.assert_array_equal(f["sel"], s["sel"])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+    n_out = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:n_out], s["out"][:n_out])
+
+
+# ------------------------------------------------------------- the five workloads
+def test_c1_single_image_fp32():
+    batch = synth.gen_batch(1)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    assert list(f["keep"]) == [54]
+    _log(hz.compare_batch(batch, f), "c1 fused")
+    s = hz.run_staged(batch)
+    _log(hz.compare_batch(batch, s, staged=True), "c1 staged")
+    _assert_fused_equals_staged(f, s, batch)
+
+
+def test_c2_batch32_256tok_bf16():
+    batch = synth.gen_batch(2)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    assert (f["keep"] == 216).all()
+    _log(hz.compare_batch(batch, f), "c2 fused")
+    s = hz.run_staged(batch)
+    _log(hz.compare_batch(batch, s, staged=True), "c2 staged")
+    _assert_fused_equals_staged(f, s, batch)
+
+
+def test_c3_batch64_400tok_dynamic():
+    batch = synth.gen_batch(3)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    _log(hz.compare_batch(batch, f), "c3 fused")
+    s = hz.run_staged(batch)
+    _log(hz.compare_batch(batch, s, staged=True), "c3 staged")
+    _assert_fused_equals_staged(f, s, batch)
+
+
+def test_c3_affine_normalisation_hits_the_clamp():
+    # f_normalize with (lo, hi) = (0, 0.05): larger pruned sets, some images at the 0.6 clamp
+    batch = synth.gen_batch(3, images=range(16))
+    params = dict(batch.params, phi_lo=0.0, phi_hi=0.05)
+    f = hz.run_prune(batch, params)
+    assert f["rc"] == 0 and f["status"] == 0
+    rep = hz.compare_batch(batch, f, params)
+    _log(rep, "c3 phi_hi=0.05")
+    assert (f["ratio"] == np.float32(0.6)).any() and f["ratio"].max() > 0.6
+
+
+def test_c4_ragged_multi_tile():
+    batch = synth.gen_batch(4)
+    assert batch.batch == 128 and batch.max_tokens <= 1156
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    picks = list(range(0, 128, 6))
+    _log(hz.compare_batch(batch, f, images=picks), "c4 fused (sampled images)")
+    sub = synth.subset(batch, picks[:6])
+    s = hz.run_staged(sub)
+    _log(hz.compare_batch(sub, s, staged=True), "c4 staged subset")
+    # a ragged batch equals each image alone
+    alone = hz.run_prune(synth.subset(batch, [picks[3]]))
+    b = picks[3]
+    o0, o1 = int(f["out_offsets"][b]), int(f["out_offsets"][b + 1])
+    np.testing.assert_array_equal(alone["out"][: o1 - o0], f["out"][o0:o1])
+
+
+def test_c5_full_batch_sampled_against_oracle():
+    batch = synth.gen_batch(5)
+    assert batch.batch == 1024 and batch.total_tokens == 409600
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    rng = np.random.default_rng(5)
+    picks = sorted(rng.choice(1024, size=40, replace=False).tolist())
+    _log(hz.compare_batch(batch, f, images=picks), "c5 fused (40 sampled images)")
+    # properties that hold for every image
+    keep = f["keep"].astype(np.int64)
+    assert (np.diff(f["out_offsets"].astype(np.int64)) == keep).all()
+    assert (keep >= np.ceil(0.6 * 400 - 1e-3)).all() and (keep <= 400).all()
+    for b in range(0, 1024, 37):
+        sel = f["sel"][b * 400:(b + 1) * 400]
+        assert sorted(sel.tolist()) == list(range(400))
+        pr = f["pair"][b * 400 + keep[b]:(b + 1) * 400]
+        assert ((pr >= -1) & (pr < keep[b])).all()
+    # run-to-run determinism
+    g = hz.run_prune(batch)
+    np.testing.assert_array_equal(f["out"], g["out"])
+    np.testing.assert_array_equal(f["pair"], g["pair"])
+
+
+# ------------------------------------------------------------------ parameter sweeps
+@pytest.mark.parametrize("override", [
+    dict(eps=1.0, iters=100),           # the literal text of Appendix C
+    dict(alpha=0.0),                    # pure pruning
+    dict(z=1.0),                        # dustbin as attractive as a perfect match
+    dict(z=0.0, alpha=0.5),
+    dict(iters=0),
+    dict(iters=1),
+    dict(ratio=0.5),
+    dict(ratio=0.25, iters=20),         # more pruned than kept
+])
+def test_parameter_variants_c2_subset(override):
+    batch = synth.gen_batch(2, images=range(4))
+    params = dict(batch.params, **override)
+    s = hz.run_staged(batch, params)
+    rep = hz.compare_batch(batch, s, params, staged=True)
+    _log(rep, f"c2 {override}")
+    if override.get("alpha") == 0.0:
+        for b in range(batch.batch):
+            lo = int(batch.offsets[b])
+            m = int(s["keep"][b])
+            rows = batch.tokens[lo + s["sel"][lo:lo + m]]
+            o0 = int(s["out_offsets"][b])
+            np.testing.assert_array_equal(s["out"][o0:o0 + m], rows)
+
+
+# ------------------------------------------------------------------------ edge cases
+def _random_batch(counts, d, dtype, seed, dynamic=0, **params):
+    rng = np.random.default_rng(seed)
+    imgs = [(rng.standard_normal((c, d)) * rng.lognormal(0, 0.5, size=(c, 1))).astype(np.float32) for c in counts]
+    dens = rng.uniform(0.1, 0.9, len(counts)).astype(np.float32)
+    p = dict(synth.DEFAULT_PARAMS, iters=20, dynamic=dynamic)
+    p.update(params)
+    return synth.pack(0, dtype, imgs, dens, p)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_sizes(dtype):
+    batch = _random_batch([0, 1, 2, 3, 0, 7, 1], 64, dtype, seed=1, dynamic=1, phi_hi=0.3)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    _log(hz.compare_batch(batch, f), f"degenerate {dtype}")
+    s = hz.run_staged(batch)
+    hz.compare_batch(batch, s, staged=True)
+    assert f["keep"][0] == 0 and f["keep"][1] == 1 and f["keep"][4] == 0
+
+
+def test_empty_batch_and_all_empty_images():
+    b0 = synth.pack(0, "bf16", [], [], dict(synth.DEFAULT_PARAMS))
+    f = hz.run_prune(b0)
+    assert f["rc"] == 0 and list(f["out_offsets"]) == [0]
+    b1 = _random_batch([0, 0, 0], 64, "bf16", seed=2)
+    f = hz.run_prune(b1)
+    assert f["rc"] == 0 and list(f["out_offsets"]) == [0, 0, 0, 0] and list(f["keep"]) == [0, 0, 0]
+
+
+def test_nothing_pruned_passes_through():
+    batch = _random_batch([33, 64], 128, "bf16", seed=3, ratio=1.0)
+    f = hz.run_prune(batch)
+    assert list(f["keep"]) == [33, 64]
+    np.testing.assert_array_equal(f["out"][:97], batch.tokens)
+    hz.compare_batch(batch, f)
+
+
+@pytest.mark.parametrize("d,dtype", [(8, "bf16"), (4, "f32"), (72, "bf16"), (1288, "bf16"), (2048, "bf16"), (4096, "f32")])
+def test_other_widths(d, dtype):
+    batch = _random_batch([40, 17], d, dtype, seed=4, ratio=0.7)
+    s = hz.run_staged(batch)
+    _log(hz.compare_batch(batch, s, staged=True), f"width {d} {dtype}")
+
+
+def test_identical_tokens_and_equal_norms():
+    rng = np.random.default_rng(6)
+    t = rng.standard_normal(64).astype(np.float32)
+    same = np.tile(t, (20, 1))
+    # all scores equal: the lowest indices are kept
+    batch = synth.pack(0, "bf16", [same], [0.5], dict(synth.DEFAULT_PARAMS, iters=10, ratio=0.5))
+    f = hz.run_prune(batch)
+    assert list(f["sel"][:10]) == list(range(10))
+    # every column of the plan is uniform: all kept rows tie, rank 0 wins
+    assert (f["pair"][10:20] == 0).all()
+    hz.compare_batch(batch, f)
+    # equal norms, different directions
+    u = rng.standard_normal((24, 64))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    batch = synth.pack(0, "f32", [u.astype(np.float32)], [0.5], dict(synth.DEFAULT_PARAMS, iters=10, ratio=0.5))
+    hz.compare_batch(batch, hz.run_prune(batch))
+
+
+def test_zero_norm_tokens():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((16, 64)).astype(np.float32)
+    x[3] = 0
+    x[9] = 0
+    batch = synth.pack(0, "bf16", [x], [0.2], dict(synth.DEFAULT_PARAMS, iters=10, dynamic=1, phi_hi=0.1, ratio_min=0.5))
+    f = hz.run_prune(batch)
+    assert np.isfinite(synth.bf16_bits_to_f32(f["out"][: f["keep"][0]])).all()
+    hz.compare_batch(batch, f)
+    s = hz.run_staged(batch)
+    hz.compare_batch(batch, s, staged=True)
+
+
+def test_explicit_keep_counts():
+    batch = _random_batch([30, 50, 12], 64, "bf16", seed=8)
+    s = hz.run_staged(batch, keep_counts_in=[10, 50, 200])
+    assert list(s["keep"]) == [10, 50, 12]          # clamped to N
+
+
+def test_largest_supported_image():
+    batch = _random_batch([8192], 64, "bf16", seed=9, ratio=0.97, iters=3)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    _log(hz.compare_batch(batch, f), "N=8192")
+
+
+# ------------------------------------------------------------------ device-side errors
+def test_bad_offsets_set_the_status_word_and_touch_nothing():
+    batch = _random_batch([10, 12], 64, "bf16", seed=10)
+    for bad, flag in (([0, 12, 10], rt.RTP_DEV_BAD_OFFSETS), ([1, 10, 22], rt.RTP_DEV_BAD_OFFSETS),
+                      ([0, 10, 21], rt.RTP_DEV_BAD_OFFSETS)):
+        b2 = synth.Batch(0, "bf16", batch.tokens, np.array(bad, dtype=np.int32), batch.density,
+                         batch.params, [0, 1])
+        db = rt.upload(b2)
+        db.total_tokens, db.max_tokens = 22, 12
+        ws = rt.alloc_workspace(db)
+        out = torch.full((22, 64), 3.0, dtype=torch.bfloat16, device="cuda:0")
+        off = torch.full((3,), -7, dtype=torch.int32, device="cuda:0")
+        rc = rt.rtprune_prune(db, None, rt.make_params(batch.params), out, off, None, None, None, None, ws)
+        torch.cuda.synchronize()
+        assert rc == 0
+        assert hz.device_status(ws) & flag
+        assert (off.cpu().numpy() == -7).all() and (out.float().cpu().numpy() == 3.0).all()
+    # an image longer than max_tokens
+    db = rt.upload(batch)
+    db.max_tokens = 11
+    ws = rt.alloc_workspace(db)
+    out = torch.zeros((22, 64), dtype=torch.bfloat16, device="cuda:0")
+    off = torch.full((3,), -7, dtype=torch.int32, device="cuda:0")
+    rc = rt.rtprune_prune(db, None, rt.make_params(batch.params), out, off, None, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert rc == 0 and hz.device_status(ws) & rt.RTP_DEV_IMAGE_TOO_LONG
+    assert (off.cpu().numpy() == -7).all()
+
+
+def test_non_default_stream():
+    batch = synth.gen_batch(2, images=range(3))
+    ref = hz.run_prune(batch)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        got = hz.run_prune(batch)
+    np.testing.assert_array_equal(ref["out"], got["out"])
