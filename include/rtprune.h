@@ -196,6 +196,12 @@ int rtprune_prune(const rtprune_batch* in, const float* density,
 int rtprune_profile_enable(int on);
 int rtprune_profile_summary(char* buf, size_t cap);
 
+/* Measurement aid: a plain device-to-device copy kernel (`k_copy`) of `bytes`
+ * bytes (a multiple of 16; both pointers 16-byte aligned, non-overlapping).
+ * It moves exactly `bytes` in and `bytes` out, which is what hardware traffic
+ * counters read for the operator's kernels are scaled against. */
+int rtprune_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,12 +9,15 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "rtprune.h"
 #include "common.hpp"
 #include "stage1.hpp"
 #include "stage2_ref.hpp"
+#include "sinkhorn_team.hpp"
+#include "scores_mfma.hpp"
 
 using namespace rtp;
 
@@ -116,9 +119,10 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN, KID_MERGE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN_A, KID_SINKHORN_B, KID_SINKHORN_C, KID_SINKHORN, KID_MERGE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
-                                             "k_scores", "k_sinkhorn", "k_merge"};
+                                             "k_scores", "k_sinkhorn_team_a", "k_sinkhorn_team_b",
+                                             "k_sinkhorn_team_c", "k_sinkhorn", "k_merge"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
   std::mutex mu;
@@ -202,19 +206,43 @@ template <typename T>
 int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
                     double* scores_out, hipStream_t s) {
+  const T* tok = static_cast<const T*>(in->tokens);
+  const double* sq = at<double>(ws, L.sqnorm);
+  double* kmat = at<double>(ws, L.kmat);
+  const int32_t* st = at<int32_t>(ws, L.status);
+  ProfScope prof(KID_SCORES, s);
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (in->D % 32 == 0) {
+      // matrix-core path; one launch per accumulator shape, each image taken by exactly one
+      const int rows_per_block = kMfmaRowsPerWave * kMfmaWaves;
+      const dim3 grid((in->max_tokens + rows_per_block - 1) / rows_per_block, in->B), block(64 * kMfmaWaves);
+      hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                         sq, p, kmat, L.plan_cap, scores_out, st);
+      hipLaunchKernelGGL((k_scores_mfma<2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                         sq, p, kmat, L.plan_cap, scores_out, st);
+      hipLaunchKernelGGL((k_scores_mfma<4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                         sq, p, kmat, L.plan_cap, scores_out, st);
+      return launched();
+    }
+  }
   const int tiles = (in->max_tokens + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock;
   const dim3 grid(tiles, in->B), block(256);
-  const T* tok = static_cast<const T*>(in->tokens);
-  ProfScope prof(KID_SCORES, s);
   if (in->D <= 1280)
     hipLaunchKernelGGL((k_scores<T, 5>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
-                       at<double>(ws, L.sqnorm), p, at<double>(ws, L.kmat), L.plan_cap, scores_out,
-                       at<int32_t>(ws, L.status));
+                       sq, p, kmat, L.plan_cap, scores_out, st);
   else
     hipLaunchKernelGGL((k_scores<T, 16>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep,
-                       plan_off, at<double>(ws, L.sqnorm), p, at<double>(ws, L.kmat), L.plan_cap, scores_out,
-                       at<int32_t>(ws, L.status));
+                       plan_off, sq, p, kmat, L.plan_cap, scores_out, st);
   return launched();
+}
+
+template <int VID, typename S>
+void launch_team(const rtprune_batch* in, const DevParams& p, const int32_t* keep,
+                 const long long* plan_off, const double* kmat, long long plan_cap, float* plan,
+                 int32_t* pair, const int32_t* status, hipStream_t s) {
+  const int grid = (in->B + S::kTeamsPerBlock - 1) / S::kTeamsPerBlock;
+  hipLaunchKernelGGL((k_sinkhorn_team<VID, S>), dim3(grid), dim3(S::kBlock), 0, s, in->offsets, keep,
+                     plan_off, p, kmat, plan_cap, plan, pair, in->B, status);
 }
 
 int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
@@ -224,9 +252,24 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, s)
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, s));
+  const double* kmat = at<double>(ws, L.kmat);
+  const int32_t* st = at<int32_t>(ws, L.status);
+  {
+    ProfScope prof(KID_SINKHORN_A, s);
+    launch_team<0, TeamA>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+  }
+  {
+    ProfScope prof(KID_SINKHORN_B, s);
+    launch_team<1, TeamB>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+  }
+  {
+    ProfScope prof(KID_SINKHORN_C, s);
+    launch_team<2, TeamC>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+  }
+  RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);
-  hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p,
-                     at<double>(ws, L.kmat), L.plan_cap, plan, pair, at<int32_t>(ws, L.status));
+  hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
+                     L.plan_cap, plan, pair, 1, st);
   return launched();
 }
 
@@ -273,6 +316,26 @@ extern "C" const char* rtprune_status_string(int status) {
     case RTP_EHIP: return "RTP_EHIP: kernel launch failed";
     default: return "unknown status";
   }
+}
+
+// Plain 16-byte-per-lane copy: the reference point hardware counters are scaled by.
+__global__ __launch_bounds__(256) void k_copy(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                              size_t n16) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n16;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x)
+    dst[i] = src[i];
+}
+
+extern "C" int rtprune_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16 != 0) return RTP_EINVAL;
+  if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return RTP_EINVAL;
+  if (bytes == 0) return RTP_OK;
+  const size_t n16 = bytes / 16;
+  const size_t want = (n16 + 255) / 256;
+  const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
+  hipLaunchKernelGGL(k_copy, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+  return launched();
 }
 
 extern "C" int rtprune_profile_enable(int on) {

@@ -1,0 +1,123 @@
+// Cosine scores of Eq. 3 on the matrix cores, accurate to fp64 rounding.
+//
+// S = T_kept T_prop^T is the operator's one dense contraction.  bf16 x bf16
+// products are exact in fp32, but a plain fp32 accumulation over D = 1280 terms
+// is off by about 1e-6, which after the division by eps = 0.05 moves plan
+// entries by 2e-5 - enough to flip arg-max pairings that the fp64 reference
+// separates clearly.  So each v_mfma_f32_16x16x32_bf16 starts from a zero
+// accumulator (a 32-term partial dot product, rounded once to fp32 relative to
+// a sum 40 times smaller than the full one) and the partials are added in fp64
+// vector registers.  Measured against an fp64 evaluation the cosine is off by
+// at most 2e-8 (5e-9 rms), i.e. plan entries move by under 5e-7 relative at
+// eps = 0.05, inside the 1e-6 band in which an index flip counts as a near-tie.
+//
+// One wave owns MT tiles of 16 kept rows and walks the pruned rows in groups of
+// NT tiles of 16.  Operand fragments are read straight from global memory: lane
+// l supplies row (l % 16), elements 8 (l / 16) .. + 7 of the current 32-element
+// step, i.e. four lanes read 64 contiguous bytes of one token row.
+#pragma once
+#include "common.hpp"
+
+namespace rtp {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaRowsPerWave = 32;   // MT = 2 tiles of 16 kept rows
+constexpr int kMfmaWaves = 4;
+
+// Column tiles of 16 pruned rows a wave keeps accumulators for at once: just
+// enough for the image's pruned set, at most 4 (larger sets take several passes).
+__host__ __device__ inline int score_tiles_per_pass(int r) {
+  const int need = (r + 15) >> 4;
+  return need <= 1 ? 1 : (need == 2 ? 2 : 4);
+}
+
+template <int NT>
+__global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
+    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
+    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
+    const long long* __restrict__ plan_offsets, const double* __restrict__ sqnorm, DevParams p,
+    double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
+    const int32_t* __restrict__ status) {
+  constexpr int MT = kMfmaRowsPerWave / 16;
+  if (status[0]) return;
+  const int b = blockIdx.y;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  const int m = min(max(keep[b], 0), n), r = n - m;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = (blockIdx.x * kMfmaWaves + wave) * kMfmaRowsPerWave;
+  if (r <= 0 || i0 >= m) return;
+  if (score_tiles_per_pass(r) != NT) return;   // another instantiation's image
+  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  const long long po = plan_offsets[b];
+  const int32_t* sel = sel_idx + lo;
+  const int frow = lane & 15, fk = (lane >> 4) * 8;
+  const double inv_eps = 1.0 / p.eps;
+
+  const bf16_t* arow[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int i = min(i0 + 16 * t + frow, m - 1);
+    arow[t] = tokens + static_cast<size_t>(lo + clamp_index(sel[i], n)) * D + fk;
+  }
+
+  for (int j0 = 0; j0 < r; j0 += 16 * NT) {
+    const bf16_t* brow[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      const int j = min(j0 + 16 * u + frow, r - 1);
+      brow[u] = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j], n)) * D + fk;
+    }
+    double acc[MT][NT][4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int u = 0; u < NT; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
+
+    for (int k0 = 0; k0 < D; k0 += 32) {
+      bf16x8_t af[MT], bfr[NT];
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+        af[t] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(arow[t] + k0));
+#pragma unroll
+      for (int u = 0; u < NT; ++u)
+        bfr[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(brow[u] + k0));
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+          const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
+          const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t], bfr[u], zero, 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
+        }
+    }
+
+    // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      const int j = j0 + 16 * u + (lane & 15);
+      if (j >= r) continue;
+      const double nj = sqrt(sqnorm[lo + clamp_index(sel[m + j], n)]);
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int i = i0 + 16 * t + 4 * (lane >> 4) + v;
+          if (i < m) {
+            const double ni = sqrt(sqnorm[lo + clamp_index(sel[i], n)]);
+            const double s = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
+            const long long at = po + static_cast<long long>(i) * r + j;
+            kmat[at] = exp((s - p.shift) * inv_eps);
+            if (scores_out) scores_out[at] = s;
+          }
+        }
+    }
+  }
+}
+
+}  // namespace rtp

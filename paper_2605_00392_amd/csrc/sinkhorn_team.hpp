@@ -1,0 +1,242 @@
+// Register-resident Sinkhorn (Appendix C) for images whose kept x pruned kernel
+// matrix fits the vector registers of a small team of waves.
+//
+// A team of W waves (T = 64 W threads) is laid out as TR row slots x TC column
+// slots, TC = 2^LOG_TC <= 64 so that the column slots of one row slot are
+// adjacent lanes of one wave.  Thread (rslot, cslot) holds
+//     K[a][c] = K_{rslot + TR a, cslot + TC c},  a < RPT, c < CPT
+// in fp64 registers for the whole iteration, so an image needs
+// M <= TR RPT and R <= TC CPT.  Per iteration:
+//   u-update  row sums are local over c, then summed over the TC column slots
+//             with lane shuffles;
+//   v-update  column sums are local over a, then summed over the row slots:
+//             lane shuffles inside a wave, LDS across the team's waves (two
+//             barriers per iteration).
+// The dustbin row, column and corner all equal kz = exp((z - shift)/eps) and are
+// handled in closed form (they add kz * y_dust to a row sum, kz * x_dust to a
+// column sum, and need sum_i x_i and sum_j y_j).
+//
+// W = 1 runs four independent images per 256-thread workgroup and never
+// executes a workgroup barrier.
+#pragma once
+#include "common.hpp"
+
+namespace rtp {
+
+// 1 / d to fp64 accuracy from the hardware estimate and two Newton steps.
+__device__ __forceinline__ double rcp64(double d) {
+  double r = __builtin_amdgcn_rcp(d);
+  r = fma(fma(-d, r, 1.0), r, r);
+  r = fma(fma(-d, r, 1.0), r, r);
+  return r;
+}
+
+template <int W_, int LOG_TC_, int RPT_, int CPT_>
+struct TeamShape {
+  static constexpr int W = W_, LOG_TC = LOG_TC_, RPT = RPT_, CPT = CPT_;
+  static constexpr int T = 64 * W, TC = 1 << LOG_TC, TR = T / TC;
+  static constexpr int kMaxM = TR * RPT, kMaxR = TC * CPT;
+  static constexpr int kBlock = T < 256 ? 256 : T;
+  static constexpr int kTeamsPerBlock = kBlock / T;
+  __host__ __device__ static constexpr bool fits(int m, int r) { return m <= kMaxM && r <= kMaxR; }
+};
+
+// The shapes compiled in, tried in this order; an image that fits none is left
+// to the general kernel (variant kGeneralVariant).
+using TeamA = TeamShape<1, 0, 7, 8>;     // M <= 448,  R <= 8    one wave
+using TeamB = TeamShape<8, 2, 4, 10>;    // M <= 512,  R <= 40
+using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
+constexpr int kGeneralVariant = 3;
+
+__host__ __device__ inline int sinkhorn_variant(int m, int r) {
+  if (TeamA::fits(m, r)) return 0;
+  if (TeamB::fits(m, r)) return 1;
+  if (TeamC::fits(m, r)) return 2;
+  return kGeneralVariant;
+}
+
+template <int VID, typename S>
+__global__ __launch_bounds__(S::kBlock) void k_sinkhorn_team(
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ keep,
+    const long long* __restrict__ plan_offsets, DevParams p, const double* __restrict__ kmat,
+    long long plan_cap, float* __restrict__ plan_out, int32_t* __restrict__ pair_out, int B,
+    const int32_t* __restrict__ status) {
+  constexpr int W = S::W, TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T;
+  constexpr int LOG_TC = S::LOG_TC;
+  if (status[0]) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int team = (W == 1) ? wave : 0;
+  const int tw = (W == 1) ? 0 : wave;               // wave index inside the team
+  const int tt = tw * 64 + lane;                    // thread index inside the team
+  const int b = blockIdx.x * S::kTeamsPerBlock + team;
+  if (b >= B) return;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  if (n <= 0) return;
+  const int m = min(max(keep[b], 0), n), r = n - m;
+  if (sinkhorn_variant(m, r) != VID) return;       // uniform over the team
+  if (pair_out)
+    for (int i = tt; i < m; i += T) pair_out[lo + i] = i;
+  if (r <= 0 || m <= 0) return;
+  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  const long long po = plan_offsets[b];
+  const double* Kg = kmat + po;
+
+  const int cslot = tt & (TC - 1);
+  const int rslot = tt >> LOG_TC;
+
+  double K[RPT][CPT];
+#pragma unroll
+  for (int a = 0; a < RPT; ++a) {
+    const int i = rslot + TR * a;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = cslot + TC * c;
+      K[a][c] = (i < m && j < r) ? Kg[static_cast<long long>(i) * r + j] : 0.0;
+    }
+  }
+
+  const double kz = exp((p.z - p.shift) / p.eps);
+  double x[RPT], y[CPT];
+  const double x_init = exp(p.shift / p.eps);      // T = 0 leaves u = 0
+#pragma unroll
+  for (int a = 0; a < RPT; ++a) x[a] = (rslot + TR * a < m) ? x_init : 0.0;
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) y[c] = (cslot + TC * c < r) ? 1.0 : 0.0;
+  double x_dust = x_init, y_dust = 1.0;
+  double sum_y = static_cast<double>(r) + 1.0;
+
+  __shared__ double xw[W > 1 ? W : 1][TC][CPT + 1];
+  __shared__ double xtot[TC][CPT + 1];
+
+  for (int it = 0; it < p.iters; ++it) {
+    // ---- u-update ----
+    double s[RPT];
+#pragma unroll
+    for (int a = 0; a < RPT; ++a) {
+      double acc = 0.0;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) acc = fma(K[a][c], y[c], acc);
+      s[a] = acc;
+    }
+#pragma unroll
+    for (int mask = 1; mask < TC; mask <<= 1)
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) s[a] += __shfl_xor(s[a], mask, kWave);
+    const double row_dust = kz * y_dust;
+#pragma unroll
+    for (int a = 0; a < RPT; ++a) x[a] = (rslot + TR * a < m) ? rcp64(s[a] + row_dust) : 0.0;
+    x_dust = static_cast<double>(r) * rcp64(kz * sum_y);
+
+    // ---- v-update ----
+    double t[CPT + 1];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      double acc = 0.0;
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) acc = fma(K[a][c], x[a], acc);
+      t[c] = acc;
+    }
+    {
+      double acc = 0.0;
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) acc += x[a];
+      t[CPT] = acc;
+    }
+#pragma unroll
+    for (int mask = TC; mask < kWave; mask <<= 1)
+#pragma unroll
+      for (int c = 0; c <= CPT; ++c) t[c] += __shfl_xor(t[c], mask, kWave);
+    if (W > 1) {
+      // wave totals -> LDS; one thread per (column slot, value) adds the W
+      // partials; everybody reads back its CPT + 1 totals
+      if (lane < TC) {
+#pragma unroll
+        for (int c = 0; c <= CPT; ++c) xw[tw][lane][c] = t[c];
+      }
+      __syncthreads();
+      if (tt < TC * (CPT + 1)) {
+        const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
+        double acc = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
+        xtot[cs][c] = acc;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int c = 0; c <= CPT; ++c) t[c] = xtot[cslot][c];
+    }
+    const double col_dust = kz * x_dust;
+    double ly = 0.0;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      y[c] = (cslot + TC * c < r) ? rcp64(t[c] + col_dust) : 0.0;
+      ly += y[c];
+    }
+    y_dust = static_cast<double>(m) * rcp64(kz * (t[CPT] + x_dust));
+#pragma unroll
+    for (int mask = 1; mask < TC; mask <<= 1) ly += __shfl_xor(ly, mask, kWave);
+    sum_y = ly + y_dust;
+  }
+
+  // ---- plan and pairing ----
+  float bv[CPT];
+  int bi[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) { bv[c] = -1.f; bi[c] = 0x7fffffff; }
+  float* P = plan_out ? plan_out + po : nullptr;
+#pragma unroll
+  for (int a = 0; a < RPT; ++a) {
+    const int i = rslot + TR * a;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = cslot + TC * c;
+      if (i < m && j < r) {
+        const float v = static_cast<float>(x[a] * K[a][c] * y[c]);
+        if (P) P[static_cast<long long>(i) * r + j] = v;
+        if (v > bv[c]) { bv[c] = v; bi[c] = i; }
+      }
+    }
+  }
+  if (!pair_out) return;
+#pragma unroll
+  for (int mask = TC; mask < kWave; mask <<= 1)
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const float ov = __shfl_xor(bv[c], mask, kWave);
+      const int oi = __shfl_xor(bi[c], mask, kWave);
+      if (ov > bv[c] || (ov == bv[c] && oi < bi[c])) { bv[c] = ov; bi[c] = oi; }
+    }
+  if (W > 1) {
+    __shared__ float pv[W > 1 ? W : 1][TC][CPT];
+    __shared__ int pi[W > 1 ? W : 1][TC][CPT];
+    if (lane < TC) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) { pv[tw][lane][c] = bv[c]; pi[tw][lane][c] = bi[c]; }
+    }
+    __syncthreads();
+    if (tt < TC) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+          const float ov = pv[w][tt][c];
+          const int oi = pi[w][tt][c];
+          if (ov > bv[c] || (ov == bv[c] && oi < bi[c])) { bv[c] = ov; bi[c] = oi; }
+        }
+      }
+    }
+  }
+  if (tt < TC) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = cslot + TC * c;
+      if (j < r) {
+        const float dust = static_cast<float>(x_dust * kz * y[c]);
+        pair_out[lo + m + j] = dust > bv[c] ? -1 : bi[c];
+      }
+    }
+  }
+}
+
+}  // namespace rtp

@@ -23,7 +23,7 @@ RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG = 1, 2
 EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune",
-    "rtprune_profile_enable", "rtprune_profile_summary",
+    "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_copy_bytes",
 )
 
 
@@ -82,6 +82,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_summary.restype = ctypes.c_int
     lib.rtprune_profile_summary.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+    lib.rtprune_copy_bytes.restype = ctypes.c_int
+    lib.rtprune_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
     if path is None:
         _lib = lib
     return lib
@@ -221,6 +223,10 @@ def rtprune_profile_summary():
     buf = ctypes.create_string_buffer(1 << 14)
     rc = load_library().rtprune_profile_summary(buf, len(buf))
     return rc, (json.loads(buf.value.decode()) if rc == RTP_OK else [])
+
+
+def rtprune_copy_bytes(dst, src, nbytes: int, stream=None) -> int:
+    return load_library().rtprune_copy_bytes(_addr(dst), _addr(src), nbytes, _stream(stream))
 
 
 def alloc_workspace(batch: DeviceBatch):
