@@ -55,6 +55,27 @@ __device__ __forceinline__ void store4(float* p, const float (&x)[4]) {
   *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
 }
 
+// A 4-element group of a token row as it sits in memory, and its widening.
+template <typename T> struct Raw4;
+template <> struct Raw4<bf16_t> { typedef uint2 type; };
+template <> struct Raw4<float> { typedef float4 type; };
+__device__ __forceinline__ void unpack4(const uint2& u, float (&x)[4]) {
+  x[0] = __uint_as_float(u.x << 16);
+  x[1] = __uint_as_float(u.x & 0xffff0000u);
+  x[2] = __uint_as_float(u.y << 16);
+  x[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+__device__ __forceinline__ void unpack4(const float4& u, float (&x)[4]) {
+  x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+}
+
+// Make the compiler forget where a register value came from (blocks common
+// subexpression elimination across the call; emits no instruction).
+__device__ __forceinline__ void forget_origin(uint2& u) { asm volatile("" : "+v"(u.x), "+v"(u.y)); }
+__device__ __forceinline__ void forget_origin(float4& u) {
+  asm volatile("" : "+v"(u.x), "+v"(u.y), "+v"(u.z), "+v"(u.w));
+}
+
 // Butterfly sum over the 64 lanes of a wave; every lane gets the total.
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll

@@ -17,7 +17,9 @@
 #include "stage1.hpp"
 #include "stage2_ref.hpp"
 #include "sinkhorn_team.hpp"
+#include "sinkhorn_dual.hpp"
 #include "scores_mfma.hpp"
+#include "merge_lds.hpp"
 
 using namespace rtp;
 
@@ -119,9 +121,9 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN_A, KID_SINKHORN_B, KID_SINKHORN_C, KID_SINKHORN, KID_MERGE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN_A, KID_SINKHORN_DUAL, KID_SINKHORN_B, KID_SINKHORN_C, KID_SINKHORN, KID_MERGE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
-                                             "k_scores", "k_sinkhorn_team_a", "k_sinkhorn_team_b",
+                                             "k_scores", "k_sinkhorn_team_a", "k_sinkhorn_dual", "k_sinkhorn_team_b",
                                              "k_sinkhorn_team_c", "k_sinkhorn", "k_merge"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
@@ -256,15 +258,20 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
   const int32_t* st = at<int32_t>(ws, L.status);
   {
     ProfScope prof(KID_SINKHORN_A, s);
-    launch_team<0, TeamA>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+    launch_team<kVariantA, TeamA>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+  }
+  {
+    ProfScope prof(KID_SINKHORN_DUAL, s);
+    hipLaunchKernelGGL(k_sinkhorn_dual, dim3(in->B), dim3(kDualThreads), 0, s, in->offsets, keep, plan_off,
+                       p, kmat, L.plan_cap, plan, pair, st);
   }
   {
     ProfScope prof(KID_SINKHORN_B, s);
-    launch_team<1, TeamB>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+    launch_team<kVariantB, TeamB>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
   }
   {
     ProfScope prof(KID_SINKHORN_C, s);
-    launch_team<2, TeamC>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+    launch_team<kVariantC, TeamC>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
   }
   RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);
@@ -282,6 +289,12 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   const T* tok = static_cast<const T*>(in->tokens);
   const float alpha = static_cast<float>(p.alpha);
   ProfScope prof(KID_MERGE, s);
+  if (in->D <= 1280) {
+    const dim3 g2((in->max_tokens + kMergeBlockRows - 1) / kMergeBlockRows, in->B);
+    hipLaunchKernelGGL((k_merge_lds<T, 5>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
+                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+    return launched();
+  }
   if (in->D <= 1024)
     hipLaunchKernelGGL((k_merge<T, 1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
                        plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);

@@ -1,0 +1,155 @@
+// Sinkhorn (Appendix C) with the kernel matrix held twice in registers, once
+// per sweep direction, so that neither sweep needs a cross-lane reduction.
+//
+// Workgroup = 8 waves = 512 threads, one image with M + 1 <= 512 and
+// R + 1 <= 32.  The dustbin row and column are ordinary entries here: the
+// augmented kernel Kb is (M+1) x (R+1) with Kb = kz = exp((z - shift)/eps) on
+// the last row and column, row marginals a = [1_M, R], column marginals
+// b = [1_R, M].
+//
+//   row copy     thread t owns row t of Kb (32 doubles): the u-update
+//                x_t = a_t / sum_j Kb_tj y_j is thread-local; y is read from
+//                LDS as a broadcast.
+//   column copy  lane = 32 h + j of wave w owns column j of the 32-row chunk
+//                q = 2 w + h (32 doubles): the v-update's partial column sums
+//                sum_{i in chunk} Kb_ij x_i are thread-local; x is read from
+//                LDS (each half-wave reads one address at a time).  The 16
+//                partials of a column go through LDS; every wave adds them up
+//                for itself, so y needs no third barrier.
+//
+// Two workgroup barriers per iteration, no lane shuffles.
+#pragma once
+#include "common.hpp"
+#include "sinkhorn_team.hpp"
+
+namespace rtp {
+
+constexpr int kDualThreads = 512;  // = kDualRows: one augmented row per thread
+constexpr int kDualChunks = 16;    // 32-row chunks of the column copy
+
+__global__ __launch_bounds__(kDualThreads) void k_sinkhorn_dual(
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ keep,
+    const long long* __restrict__ plan_offsets, DevParams p, const double* __restrict__ kmat,
+    long long plan_cap, float* __restrict__ plan_out, int32_t* __restrict__ pair_out,
+    const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  if (n <= 0) return;
+  const int m = min(max(keep[b], 0), n), r = n - m;
+  if (sinkhorn_variant(m, r) != kVariantDual) return;
+  if (pair_out)
+    for (int i = tid; i < m; i += kDualThreads) pair_out[lo + i] = i;
+  if (r <= 0 || m <= 0) return;
+  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  const long long po = plan_offsets[b];
+  const double* Kg = kmat + po;
+  const double kz = exp((p.z - p.shift) / p.eps);
+
+  __shared__ double xs[kDualRows];
+  __shared__ double part[kDualChunks][kDualCols];
+  __shared__ double ys[kDualThreads / 64][kDualCols];
+  __shared__ float pv[kDualChunks][kDualCols];
+  __shared__ int pi[kDualChunks][kDualCols];
+
+  // row copy: row `tid` of the augmented kernel
+  double Kr[kDualCols];
+#pragma unroll
+  for (int c = 0; c < kDualCols; ++c) {
+    double v = 0.0;
+    if (tid <= m && c <= r) v = (tid < m && c < r) ? Kg[static_cast<long long>(tid) * r + c] : kz;
+    Kr[c] = v;
+  }
+  // column copy: column j of rows 32 q .. 32 q + 31
+  const int j = lane & 31, q = 2 * wave + (lane >> 5);
+  double Kc[32];
+#pragma unroll
+  for (int a = 0; a < 32; ++a) {
+    const int i = 32 * q + a;
+    double v = 0.0;
+    if (i <= m && j <= r) v = (i < m && j < r) ? Kg[static_cast<long long>(i) * r + j] : kz;
+    Kc[a] = v;
+  }
+  const double a_row = tid < m ? 1.0 : static_cast<double>(r);   // row marginal of row tid
+  const double b_col = j < r ? 1.0 : static_cast<double>(m);     // column marginal of column j
+
+  double x = (tid <= m) ? exp(p.shift / p.eps) : 0.0;   // T = 0 leaves u = 0
+  double y = (j <= r) ? 1.0 : 0.0;
+  xs[tid] = x;
+  if (lane < 32) ys[wave][lane] = y;
+  __syncthreads();
+
+  for (int it = 0; it < p.iters; ++it) {
+    // ---- u-update (row copy) ----
+    {
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int c = 0; c < kDualCols; c += 2) {
+        s0 = fma(Kr[c], ys[wave][c], s0);
+        s1 = fma(Kr[c + 1], ys[wave][c + 1], s1);
+      }
+      x = (tid <= m) ? a_row * rcp64(s0 + s1) : 0.0;
+      xs[tid] = x;
+    }
+    __syncthreads();
+    // ---- v-update (column copy) ----
+    {
+      const double* xq = xs + 32 * q;
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int a = 0; a < 32; a += 2) {
+        s0 = fma(Kc[a], xq[a], s0);
+        s1 = fma(Kc[a + 1], xq[a + 1], s1);
+      }
+      part[q][j] = s0 + s1;
+    }
+    __syncthreads();
+    {
+      double t = 0.0;
+#pragma unroll
+      for (int c = 0; c < kDualChunks; ++c) t += part[c][j];
+      y = (j <= r) ? b_col * rcp64(t) : 0.0;
+      if (lane < 32) ys[wave][lane] = y;   // read back by this wave only
+    }
+  }
+  __syncthreads();
+
+  // ---- plan: row t of P = x_t K_tj y_j ----
+  if (plan_out && tid < m) {
+    float* P = plan_out + po + static_cast<long long>(tid) * r;
+#pragma unroll
+    for (int c = 0; c < kDualCols; ++c)
+      if (c < r) P[c] = static_cast<float>(x * Kr[c] * ys[wave][c]);
+  }
+  if (!pair_out) return;
+  // ---- pairing: arg-max over rows 0..M of column j (row M is the dustbin) ----
+  {
+    const double* xq = xs + 32 * q;
+    float bv = -1.f;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int a = 0; a < 32; ++a) {
+      const int i = 32 * q + a;
+      const float v = static_cast<float>(xq[a] * Kc[a] * y);
+      if (i <= m && v > bv) { bv = v; bi = i; }
+    }
+    pv[q][j] = bv;
+    pi[q][j] = bi;
+  }
+  __syncthreads();
+  if (tid < r) {
+    float bv = pv[0][tid];
+    int bi = pi[0][tid];
+#pragma unroll
+    for (int c = 1; c < kDualChunks; ++c) {
+      const float ov = pv[c][tid];
+      const int oi = pi[c][tid];
+      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    pair_out[lo + m + tid] = (bi >= m) ? -1 : bi;
+  }
+}
+
+}  // namespace rtp

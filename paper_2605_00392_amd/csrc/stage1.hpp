@@ -64,36 +64,68 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
     for (int e = 0; e < 4; ++e) acc[k][e] = 0.0;
   double wsum = 0.0;
 
-  for (int r = r0 + wave; r < r1; r += kNormThreads / kWave) {
-    const T* row = tokens + static_cast<size_t>(lo + r) * D;
-    float x[KMAX][4];
+  // A wave takes its rows four at a time: the four rows' loads are issued
+  // together (raw, still packed), their four squared norms go through the lane
+  // butterfly interleaved, and only then are the unit vectors accumulated.
+  typedef typename Raw4<T>::type raw_t;
+  constexpr int kStep = kNormThreads / kWave;      // row stride between a wave's rows
+  constexpr int NB = KMAX <= 5 ? 4 : 1;
+  for (int rb = r0 + wave; rb < r1; rb += kStep * NB) {
+    raw_t raw[NB][KMAX];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) {
-      const int g = lane + kWave * k;
-      if (g < ngroups) load4(row + 4 * g, x[k]);
-      else x[k][0] = x[k][1] = x[k][2] = x[k][3] = 0.f;
-    }
-    double q = 0.0;
+    for (int u = 0; u < NB; ++u) {
+      const int r = min(rb + kStep * u, r1 - 1);
+      const T* row = tokens + static_cast<size_t>(lo + r) * D;
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const double v = static_cast<double>(x[k][e]);
-        q = fma(v, v, q);
+      for (int k = 0; k < KMAX; ++k) {
+        const int g = lane + kWave * k;
+        if (g < ngroups) raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * g);
+        else raw[u][k] = raw_t{};
       }
-    q = wave_sum(q);
-    if (lane == 0) {
-      sqnorm[lo + r] = q;
-      score[lo + r] = static_cast<float>(q);
-      if (norms_out) norms_out[lo + r] = static_cast<float>(sqrt(q));
     }
-    if (dynamic) {
-      const double inv = 1.0 / fmax(sqrt(q), kTinyNorm);
-      wsum += q * inv * inv;
+    double q[NB];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k)
+    for (int u = 0; u < NB; ++u) {
+      double a = 0.0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[k][e] = fma(static_cast<double>(x[k][e]), inv, acc[k][e]);
+      for (int k = 0; k < KMAX; ++k) {
+        float x[4];
+        unpack4(raw[u][k], x);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const double v = static_cast<double>(x[e]);
+          a = fma(v, v, a);
+        }
+      }
+      q[u] = a;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+      for (int u = 0; u < NB; ++u) q[u] += __shfl_xor(q[u], o, kWave);
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int r = rb + kStep * u;
+      if (r >= r1) break;
+      if (lane == 0) {
+        sqnorm[lo + r] = q[u];
+        score[lo + r] = static_cast<float>(q[u]);
+        if (norms_out) norms_out[lo + r] = static_cast<float>(sqrt(q[u]));
+      }
+      if (dynamic) {
+        const double inv = 1.0 / fmax(sqrt(q[u]), kTinyNorm);
+        wsum += q[u] * inv * inv;
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+          // widen again from the packed registers instead of keeping the first
+          // pass's 80 doubles alive (the empty asm hides the value's origin)
+          forget_origin(raw[u][k]);
+          float x[4];
+          unpack4(raw[u][k], x);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[k][e] = fma(static_cast<double>(x[e]), inv, acc[k][e]);
+        }
+      }
     }
   }
   if (!dynamic) return;
