@@ -45,10 +45,17 @@ __device__ __forceinline__ void load4(const float* p, float (&x)[4]) {
   const float4 u = *reinterpret_cast<const float4*>(p);
   x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
 }
+// fp32 -> bf16, round to nearest even, two at a time (v_cvt_pk_bf16_f32).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const floatx2_t f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
 __device__ __forceinline__ void store4(bf16_t* p, const float (&x)[4]) {
   uint2 u;
-  u.x = static_cast<uint32_t>(f32_to_bf16(x[0])) | (static_cast<uint32_t>(f32_to_bf16(x[1])) << 16);
-  u.y = static_cast<uint32_t>(f32_to_bf16(x[2])) | (static_cast<uint32_t>(f32_to_bf16(x[3])) << 16);
+  u.x = pack_bf16x2(x[0], x[1]);
+  u.y = pack_bf16x2(x[2], x[3]);
   *reinterpret_cast<uint2*>(p) = u;
 }
 __device__ __forceinline__ void store4(float* p, const float (&x)[4]) {

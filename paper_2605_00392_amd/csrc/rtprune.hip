@@ -30,7 +30,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 // Byte offsets of the workspace regions for a batch shape.
 struct Layout {
-  size_t status, sqnorm, score, partial, phi, ratio, keep, out_off, plan_off, sel, kmat, plan, total;
+  size_t status, sqnorm, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
   int chunks_per_image;
   long long plan_cap;   // entries available in kmat / plan
 };
@@ -53,6 +53,7 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   L.out_off = take(sizeof(int32_t) * (B + 1));
   L.plan_off = take(sizeof(long long) * (B + 1));
   L.sel = take(sizeof(int32_t) * total);
+  L.work = take(sizeof(int32_t) * (4 + 4 * static_cast<size_t>(B)));
   L.kmat = take(sizeof(double) * L.plan_cap);
   L.plan = take(sizeof(float) * L.plan_cap);
   L.total = at;
@@ -121,10 +122,10 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_SINKHORN_A, KID_SINKHORN_DUAL, KID_SINKHORN_B, KID_SINKHORN_C, KID_SINKHORN, KID_MERGE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
-                                             "k_scores", "k_sinkhorn_team_a", "k_sinkhorn_dual", "k_sinkhorn_team_b",
-                                             "k_sinkhorn_team_c", "k_sinkhorn", "k_merge"};
+                                             "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn",
+                                             "k_merge"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
   std::mutex mu;
@@ -214,7 +215,7 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
   const int32_t* st = at<int32_t>(ws, L.status);
   ProfScope prof(KID_SCORES, s);
   if constexpr (std::is_same<T, bf16_t>::value) {
-    if (in->D % 32 == 0) {
+    if (in->D % 64 == 0) {
       // matrix-core path; one launch per accumulator shape, each image taken by exactly one
       const int rows_per_block = kMfmaRowsPerWave * kMfmaWaves;
       const dim3 grid((in->max_tokens + rows_per_block - 1) / rows_per_block, in->B), block(64 * kMfmaWaves);
@@ -238,15 +239,6 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
   return launched();
 }
 
-template <int VID, typename S>
-void launch_team(const rtprune_batch* in, const DevParams& p, const int32_t* keep,
-                 const long long* plan_off, const double* kmat, long long plan_cap, float* plan,
-                 int32_t* pair, const int32_t* status, hipStream_t s) {
-  const int grid = (in->B + S::kTeamsPerBlock - 1) / S::kTeamsPerBlock;
-  hipLaunchKernelGGL((k_sinkhorn_team<VID, S>), dim3(grid), dim3(S::kBlock), 0, s, in->offsets, keep,
-                     plan_off, p, kmat, plan_cap, plan, pair, in->B, status);
-}
-
 int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
               const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
               int32_t* pair, hipStream_t s) {
@@ -256,22 +248,15 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, s));
   const double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
+  int32_t* work = at<int32_t>(ws, L.work);
   {
-    ProfScope prof(KID_SINKHORN_A, s);
-    launch_team<kVariantA, TeamA>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+    ProfScope prof(KID_CLASSIFY, s);
+    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, st);
   }
   {
-    ProfScope prof(KID_SINKHORN_DUAL, s);
-    hipLaunchKernelGGL(k_sinkhorn_dual, dim3(in->B), dim3(kDualThreads), 0, s, in->offsets, keep, plan_off,
-                       p, kmat, L.plan_cap, plan, pair, st);
-  }
-  {
-    ProfScope prof(KID_SINKHORN_B, s);
-    launch_team<kVariantB, TeamB>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
-  }
-  {
-    ProfScope prof(KID_SINKHORN_C, s);
-    launch_team<kVariantC, TeamC>(in, p, keep, plan_off, kmat, L.plan_cap, plan, pair, st, s);
+    ProfScope prof(KID_SINKHORN_REGS, s);
+    SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
+    hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
   }
   RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);

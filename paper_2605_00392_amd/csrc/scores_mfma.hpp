@@ -12,9 +12,11 @@
 // eps = 0.05, inside the 1e-6 band in which an index flip counts as a near-tie.
 //
 // One wave owns MT tiles of 16 kept rows and walks the pruned rows in groups of
-// NT tiles of 16.  Operand fragments are read straight from global memory: lane
-// l supplies row (l % 16), elements 8 (l / 16) .. + 7 of the current 32-element
-// step, i.e. four lanes read 64 contiguous bytes of one token row.
+// NT tiles of 16.  Operand fragments are read straight from global memory, 64
+// elements of the contraction per step: lane l reads elements 16 (l / 16) .. + 15
+// of row (l % 16), so four lanes cover one 128-byte line.  Which 32 of the 64
+// elements a matrix instruction contracts is immaterial as long as both
+// operands use the same assignment, which they do by construction.
 #pragma once
 #include "common.hpp"
 
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
   const int32_t* sel = sel_idx + lo;
-  const int frow = lane & 15, fk = (lane >> 4) * 8;
+  const int frow = lane & 15, fk = (lane >> 4) * 16;   // 16 elements = 32 bytes per lane and step
   const double inv_eps = 1.0 / p.eps;
 
   const bf16_t* arow[MT];
@@ -78,23 +80,45 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
 
-    for (int k0 = 0; k0 < D; k0 += 32) {
-      bf16x8_t af[MT], bfr[NT];
+    // 64 elements per step: a lane reads 32 contiguous bytes of its row (four
+    // lanes cover one 128-byte line) and feeds them to two matrix instructions.
+    // The next step's fragments are requested before the current step's
+    // arithmetic.
+    uint4 fa[MT][2], fb[NT][2];
+    auto load_step = [&](int k0, uint4 (&a)[MT][2], uint4 (&bb)[NT][2]) {
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
-        af[t] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(arow[t] + k0));
+      for (int t = 0; t < MT; ++t) {
+        a[t][0] = *reinterpret_cast<const uint4*>(arow[t] + k0);
+        a[t][1] = *reinterpret_cast<const uint4*>(arow[t] + k0 + 8);
+      }
 #pragma unroll
-      for (int u = 0; u < NT; ++u)
-        bfr[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(brow[u] + k0));
+      for (int u = 0; u < NT; ++u) {
+        bb[u][0] = *reinterpret_cast<const uint4*>(brow[u] + k0);
+        bb[u][1] = *reinterpret_cast<const uint4*>(brow[u] + k0 + 8);
+      }
+    };
+    load_step(0, fa, fb);
+    for (int k0 = 0; k0 < D; k0 += 64) {
+      uint4 na[MT][2], nb[NT][2];
+      if (k0 + 64 < D) load_step(k0 + 64, na, nb);
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int u = 0; u < NT; ++u) {
-          const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
-          const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t], bfr[u], zero, 0, 0, 0);
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
-        }
+          for (int u = 0; u < NT; ++u) {
+            const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
+            const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8_t, fa[t][h]), __builtin_bit_cast(bf16x8_t, fb[u][h]), zero, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
+          }
+      if (k0 + 64 < D) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) { fa[t][0] = na[t][0]; fa[t][1] = na[t][1]; }
+#pragma unroll
+        for (int u = 0; u < NT; ++u) { fb[u][0] = nb[u][0]; fb[u][1] = nb[u][1]; }
+      }
     }
 
     // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile

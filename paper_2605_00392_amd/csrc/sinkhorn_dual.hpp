@@ -27,23 +27,25 @@ namespace rtp {
 constexpr int kDualThreads = 512;  // = kDualRows: one augmented row per thread
 constexpr int kDualChunks = 16;    // 32-row chunks of the column copy
 
-__global__ __launch_bounds__(kDualThreads) void k_sinkhorn_dual(
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ keep,
-    const long long* __restrict__ plan_offsets, DevParams p, const double* __restrict__ kmat,
-    long long plan_cap, float* __restrict__ plan_out, int32_t* __restrict__ pair_out,
-    const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  const int b = blockIdx.x, tid = threadIdx.x;
+// One image on the whole 512-thread workgroup.
+__device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b) {
+  const DevParams& p = A.p;
+  const int32_t* __restrict__ offsets = A.offsets;
+  const long long* __restrict__ plan_offsets = A.plan_offsets;
+  const double* __restrict__ kmat = A.kmat;
+  float* __restrict__ plan_out = A.plan_out;
+  int32_t* __restrict__ pair_out = A.pair_out;
+  const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
   if (n <= 0) return;
-  const int m = min(max(keep[b], 0), n), r = n - m;
-  if (sinkhorn_variant(m, r) != kVariantDual) return;
+  const int m = min(max(A.keep[b], 0), n), r = n - m;
+  if (!(m + 1 <= kDualRows && r + 1 <= kDualCols)) return;
   if (pair_out)
     for (int i = tid; i < m; i += kDualThreads) pair_out[lo + i] = i;
   if (r <= 0 || m <= 0) return;
-  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  if (!plan_fits(plan_offsets[b], m, r, A.plan_cap)) return;
   const long long po = plan_offsets[b];
   const double* Kg = kmat + po;
   const double kz = exp((p.z - p.shift) / p.eps);
@@ -152,4 +154,71 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_dual(
   }
 }
 
+// Work lists for the register-resident kernels: `work` holds four counts
+// (team A, two-copy, team B, team C images) followed by four lists of B image
+// indices each.  One workgroup; list order follows image order.
+__global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
+                                                  const int32_t* __restrict__ keep, int B,
+                                                  int32_t* __restrict__ work,
+                                                  const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  __shared__ int cnt[4][256];
+  const int tid = threadIdx.x;
+  const int span = (B + 255) / 256;
+  const int b0 = min(B, tid * span), b1 = min(B, b0 + span);
+  int c[4] = {0, 0, 0, 0};
+  for (int b = b0; b < b1; ++b) {
+    const int n = offsets[b + 1] - offsets[b];
+    const int m = min(max(keep[b], 0), max(n, 0));
+    const int v = sinkhorn_variant(m, n - m);
+    if (n > 0 && v < kGeneralVariant) ++c[v];
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) cnt[v][tid] = c[v];
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    int add[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) add[v] = tid >= o ? cnt[v][tid - o] : 0;
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 4; ++v) cnt[v][tid] += add[v];
+    __syncthreads();
+  }
+  int at[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) at[v] = cnt[v][tid] - c[v];
+  for (int b = b0; b < b1; ++b) {
+    const int n = offsets[b + 1] - offsets[b];
+    const int m = min(max(keep[b], 0), max(n, 0));
+    const int v = sinkhorn_variant(m, n - m);
+    if (n > 0 && v < kGeneralVariant) work[4 + v * B + at[v]++] = b;
+  }
+  if (tid == 255) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) work[v] = cnt[v][255];
+  }
+}
+
+// All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
+// handed out in the order team C, team B, two-copy, team A (eight one-wave
+// images per workgroup), i.e. the images with the longest latency start first.
+__global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
+                                                               const int32_t* __restrict__ work, int B,
+                                                               const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nA = work[kVariantA], nD = work[kVariantDual], nB = work[kVariantB], nC = work[kVariantC];
+  int blk = blockIdx.x;
+  if (blk < nC) { sinkhorn_team_image<TeamC>(A, work[4 + kVariantC * B + blk], wave, lane); return; }
+  blk -= nC;
+  if (blk < nB) { sinkhorn_team_image<TeamB>(A, work[4 + kVariantB * B + blk], wave, lane); return; }
+  blk -= nB;
+  if (blk < nD) { sinkhorn_dual_image(A, work[4 + kVariantDual * B + blk]); return; }
+  blk -= nD;
+  const int idx = blk * (kDualThreads / 64) + wave;
+  if (idx < nA) sinkhorn_team_image<TeamA>(A, work[4 + kVariantA * B + idx], 0, lane);
+}
+
 }  // namespace rtp
+

@@ -16,8 +16,8 @@
 // handled in closed form (they add kz * y_dust to a row sum, kz * x_dust to a
 // column sum, and need sum_i x_i and sum_j y_j).
 //
-// W = 1 runs four independent images per 256-thread workgroup and never
-// executes a workgroup barrier.
+// A one-wave team (W = 1) never executes a workgroup barrier, so several of them
+// can share a workgroup, one image per wave.
 #pragma once
 #include "common.hpp"
 
@@ -60,30 +60,40 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r) {
   return kGeneralVariant;
 }
 
-template <int VID, typename S>
-__global__ __launch_bounds__(S::kBlock) void k_sinkhorn_team(
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ keep,
-    const long long* __restrict__ plan_offsets, DevParams p, const double* __restrict__ kmat,
-    long long plan_cap, float* __restrict__ plan_out, int32_t* __restrict__ pair_out, int B,
-    const int32_t* __restrict__ status) {
+// What every register-resident Sinkhorn body needs.
+struct SinkhornArgs {
+  const int32_t* offsets;
+  const int32_t* keep;
+  const long long* plan_offsets;
+  DevParams p;
+  const double* kmat;
+  long long plan_cap;
+  float* plan_out;     // may be null
+  int32_t* pair_out;   // may be null
+};
+
+// One image on one team.  `tw` is the wave's index inside the team, `lane` the
+// lane; every wave of the team calls this with the same `b`.
+template <typename S>
+__device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b, int tw, int lane) {
   constexpr int W = S::W, TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T;
   constexpr int LOG_TC = S::LOG_TC;
-  if (status[0]) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int team = (W == 1) ? wave : 0;
-  const int tw = (W == 1) ? 0 : wave;               // wave index inside the team
+  const DevParams& p = A.p;
+  const int32_t* __restrict__ offsets = A.offsets;
+  const long long* __restrict__ plan_offsets = A.plan_offsets;
+  const double* __restrict__ kmat = A.kmat;
+  float* __restrict__ plan_out = A.plan_out;
+  int32_t* __restrict__ pair_out = A.pair_out;
   const int tt = tw * 64 + lane;                    // thread index inside the team
-  const int b = blockIdx.x * S::kTeamsPerBlock + team;
-  if (b >= B) return;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
   if (n <= 0) return;
-  const int m = min(max(keep[b], 0), n), r = n - m;
-  if (sinkhorn_variant(m, r) != VID) return;       // uniform over the team
+  const int m = min(max(A.keep[b], 0), n), r = n - m;
+  if (!S::fits(m, r)) return;                       // uniform over the team
   if (pair_out)
     for (int i = tt; i < m; i += T) pair_out[lo + i] = i;
   if (r <= 0 || m <= 0) return;
-  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  if (!plan_fits(plan_offsets[b], m, r, A.plan_cap)) return;
   const long long po = plan_offsets[b];
   const double* Kg = kmat + po;
 
