@@ -73,7 +73,7 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     if kernel == "k_scores":
         # fp64 vector arithmetic: one multiply-add per (kept, pruned, d)
         return "alu", 2.0 * float((m * r).sum()) * d, "TFLOP/s", FP64_VECTOR_TFLOPS
-    if kernel == "k_sinkhorn":
+    if kernel in ("k_sinkhorn", "k_sinkhorn_regs"):
         # two sweeps of multiply-adds over the augmented matrix per iteration
         return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
     return "hbm", 0.0, "GB/s", HBM_PEAK_GBS
@@ -168,7 +168,8 @@ def main() -> int:
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
             try:
-                traffic = json.load(open(tpath)).get(w.name, {}).get(dominant)
+                tmap = json.load(open(tpath)).get(w.name, {})
+                traffic = next((v for k_, v in tmap.items() if k_.startswith(dominant)), None)
             except Exception:
                 traffic = None
         roofline = dict(kernel=dominant, bound=bound, achieved=round(achieved, 3), peak=peak, unit=unit,
