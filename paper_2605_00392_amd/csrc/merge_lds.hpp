@@ -1,10 +1,10 @@
 // Merge and compaction (Eq. 6): out_i = T_i + alpha * sum_j P_ij T_j, streamed.
 //
-// A workgroup of 4 waves owns 32 consecutive kept rows of one image.  The
+// A workgroup of 4 waves owns 64 consecutive kept rows of one image.  The
 // pruned rows are staged through LDS in chunks (all of them at once when they
 // fit, which is the common case: the pruned set is small), so every kept row
 // is read from memory exactly once and written exactly once, and the pruned
-// rows come from LDS for all 32 kept rows.  A wave merges four kept rows at a
+// rows come from LDS for all 64 kept rows.  A wave merges four kept rows at a
 // time: their loads are issued together and stay packed in registers (a lane
 // owns the 4-element groups lane + 64 k), the staged pruned rows are walked
 // once for all four with the plan entries P_ij broadcast from a
@@ -15,12 +15,13 @@
 
 namespace rtp {
 
-constexpr int kMergeBlockRows = 32;
+constexpr int kMergeBlockRows = 64;
 constexpr int kMergeWaveRows = 4;    // kept rows a wave merges at a time
 constexpr int kMergeLdsBytes = 30 * 1024;
 constexpr int kMergeMaxChunk = 64;   // pruned rows per LDS chunk, at most one per lane
 
-template <typename T, int KMAX>
+// EXACT: D == 256 KMAX, every lane owns exactly KMAX groups (no bounds tests).
+template <typename T, int KMAX, bool EXACT>
 __global__ __launch_bounds__(256) void k_merge_lds(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
@@ -53,13 +54,16 @@ __global__ __launch_bounds__(256) void k_merge_lds(
     const int ia = i0 + pass * kPassRows + wave * NB;
     raw_t raw[NB][KMAX];
     float acc[NB][KMAX][4];
+    // the wave's NB token indices with one load, then all row loads back to back
+    const int my_tok = clamp_index(sel[min(ia + min(lane, NB - 1), m - 1)], n);
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
-      const T* row = tokens + static_cast<size_t>(lo + clamp_index(sel[min(ia + u, m - 1)], n)) * D;
+      const int tok = __builtin_amdgcn_readlane(my_tok, u);
+      const T* row = tokens + static_cast<size_t>(lo + tok) * D;
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int g = lane + kWave * k;
-        if (g < ngroups) raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * g);
+        if (EXACT || g < ngroups) raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * g);
         else raw[u][k] = raw_t{};
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[u][k][e] = 0.f;
@@ -67,20 +71,41 @@ __global__ __launch_bounds__(256) void k_merge_lds(
     }
     for (int c = 0; c < nchunks; ++c) {
       const int j0 = c * chunk, jn = min(chunk, r - j0);
-      if (nchunks > 1 || pass == 0) {
-        if (nchunks > 1) __syncthreads();          // the previous chunk is still being read
-        for (int idx = threadIdx.x; idx < jn * ngroups; idx += 256) {
-          const int j = idx / ngroups, g = idx - j * ngroups;
-          const T* src = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j0 + j], n)) * D + 4 * g;
-          *reinterpret_cast<raw_t*>(lds + j * D + 4 * g) = *reinterpret_cast<const raw_t*>(src);
-        }
-        __syncthreads();
-      }
       // lane l holds the plan entries of pruned row j0 + l for the wave's kept rows
+      // (requested before the staging so that they travel together with it)
       float pl[NB];
 #pragma unroll
       for (int u = 0; u < NB; ++u)
         pl[u] = (lane < jn && ia + u < m) ? P[static_cast<long long>(ia + u) * r + j0 + lane] : 0.f;
+      if (nchunks > 1 || pass == 0) {
+        if (nchunks > 1) __syncthreads();          // the previous chunk is still being read
+        // each wave stages whole pruned rows, two at a time: one load for the token
+        // indices, then the rows' loads back to back, then the LDS writes
+        const int p_tok = clamp_index(sel[m + j0 + min(lane, jn - 1)], n);
+        for (int j = 2 * wave; j < jn; j += 8) {
+          const int ja = j, jb = min(j + 1, jn - 1);
+          const T* ra = tokens + static_cast<size_t>(lo + __builtin_amdgcn_readlane(p_tok, ja)) * D;
+          const T* rb = tokens + static_cast<size_t>(lo + __builtin_amdgcn_readlane(p_tok, jb)) * D;
+          raw_t va_[KMAX], vb_[KMAX];
+#pragma unroll
+          for (int k = 0; k < KMAX; ++k) {
+            const int g = lane + kWave * k;
+            if (EXACT || g < ngroups) {
+              va_[k] = *reinterpret_cast<const raw_t*>(ra + 4 * g);
+              vb_[k] = *reinterpret_cast<const raw_t*>(rb + 4 * g);
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < KMAX; ++k) {
+            const int g = lane + kWave * k;
+            if (EXACT || g < ngroups) {
+              *reinterpret_cast<raw_t*>(lds + ja * D + 4 * g) = va_[k];
+              *reinterpret_cast<raw_t*>(lds + jb * D + 4 * g) = vb_[k];
+            }
+          }
+        }
+        __syncthreads();
+      }
       for (int j = 0; j < jn; ++j) {
         float pj[NB];
 #pragma unroll
@@ -89,7 +114,7 @@ __global__ __launch_bounds__(256) void k_merge_lds(
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
           const int g = lane + kWave * k;
-          if (g < ngroups) {
+          if (EXACT || g < ngroups) {
             float xj[4];
             unpack4(*reinterpret_cast<const raw_t*>(lds + j * D + 4 * g), xj);
 #pragma unroll
@@ -106,7 +131,7 @@ __global__ __launch_bounds__(256) void k_merge_lds(
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int g = lane + kWave * k;
-        if (g < ngroups) {
+        if (EXACT || g < ngroups) {
           float x[4], o[4];
           unpack4(raw[u][k], x);
 #pragma unroll

@@ -208,23 +208,30 @@ int launch_scan(const rtprune_batch* in, const int32_t* keep, int32_t* out_off, 
 template <typename T>
 int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
-                    double* scores_out, hipStream_t s) {
+                    double* scores_out, int max_pruned_hint, hipStream_t s) {
   const T* tok = static_cast<const T*>(in->tokens);
   const double* sq = at<double>(ws, L.sqnorm);
   double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   ProfScope prof(KID_SCORES, s);
   if constexpr (std::is_same<T, bf16_t>::value) {
-    if (in->D % 64 == 0) {
-      // matrix-core path; one launch per accumulator shape, each image taken by exactly one
+    if (in->D % 128 == 0) {
+      // matrix-core path.  With a fixed retention the pruned-set size is known up
+      // to rounding; with the dynamic ratio it is usually a few percent of the
+      // image, so the leanest shape is used and larger sets take several passes.
       const int rows_per_block = kMfmaRowsPerWave * kMfmaWaves;
       const dim3 grid((in->max_tokens + rows_per_block - 1) / rows_per_block, in->B), block(64 * kMfmaWaves);
-      hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
-                         sq, p, kmat, L.plan_cap, scores_out, st);
-      hipLaunchKernelGGL((k_scores_mfma<2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
-                         sq, p, kmat, L.plan_cap, scores_out, st);
-      hipLaunchKernelGGL((k_scores_mfma<4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
-                         sq, p, kmat, L.plan_cap, scores_out, st);
+      int nt = 1;
+      if (max_pruned_hint >= 0) nt = score_tiles_per_pass(max_pruned_hint);
+      if (nt == 1)
+        hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                           sq, p, kmat, L.plan_cap, scores_out, st);
+      else if (nt == 2)
+        hipLaunchKernelGGL((k_scores_mfma<2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                           sq, p, kmat, L.plan_cap, scores_out, st);
+      else
+        hipLaunchKernelGGL((k_scores_mfma<4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+                           sq, p, kmat, L.plan_cap, scores_out, st);
       return launched();
     }
   }
@@ -241,11 +248,11 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
 
 int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
               const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
-              int32_t* pair, hipStream_t s) {
+              int32_t* pair, int max_pruned_hint, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   RTP_TRY(in->dtype == RTP_BF16
-              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, s)
-              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, s));
+              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
+              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
   const double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   int32_t* work = at<int32_t>(ws, L.work);
@@ -276,8 +283,12 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   ProfScope prof(KID_MERGE, s);
   if (in->D <= 1280) {
     const dim3 g2((in->max_tokens + kMergeBlockRows - 1) / kMergeBlockRows, in->B);
-    hipLaunchKernelGGL((k_merge_lds<T, 5>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
-                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+    if (in->D == 1280)
+      hipLaunchKernelGGL((k_merge_lds<T, 5, true>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep,
+                         out_off, plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+    else
+      hipLaunchKernelGGL((k_merge_lds<T, 5, false>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep,
+                         out_off, plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
     return launched();
   }
   if (in->D <= 1024)
@@ -454,8 +465,9 @@ extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
   // exact squared norms of every row (fp32 norms from stage 1 would cost 1e-7 on S)
   RTP_TRY(launch_norms(in, 0, L, workspace, nullptr, s));
+  // the kept counts live on the device: no host-side bound on the pruned sets
   return launch_ot(in, p, sel_idx, keep_counts, reinterpret_cast<const long long*>(plan_offsets), L,
-                   workspace, scores, plan, pair, s);
+                   workspace, scores, plan, pair, -1, s);
 }
 
 extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
@@ -492,6 +504,9 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   RTP_TRY(launch_norms(in, p.dynamic, L, workspace, nullptr, s));
   RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
   RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s));
-  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, s));
+  // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image
+  const int max_pruned = p.dynamic ? -1
+                                   : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
   return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, status, s);
 }

@@ -28,10 +28,13 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 constexpr int kMfmaRowsPerWave = 32;   // MT = 2 tiles of 16 kept rows
 constexpr int kMfmaWaves = 4;
 
-// Column tiles of 16 pruned rows a wave keeps accumulators for at once: just
-// enough for the image's pruned set, at most 4 (larger sets take several passes).
-__host__ __device__ inline int score_tiles_per_pass(int r) {
-  const int need = (r + 15) >> 4;
+// Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
+// the kernel below), chosen on the host from the largest pruned set the call
+// can produce: a larger NT reads the kept rows fewer times when R is large but
+// costs registers, hence occupancy, when R is small.  Any NT is correct for any
+// image: the kernel walks the pruned rows in groups of 16 NT.
+inline int score_tiles_per_pass(int max_pruned) {
+  const int need = (max_pruned + 15) >> 4;
   return need <= 1 ? 1 : (need == 2 ? 2 : 4);
 }
 
@@ -51,7 +54,6 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i0 = (blockIdx.x * kMfmaWaves + wave) * kMfmaRowsPerWave;
   if (r <= 0 || i0 >= m) return;
-  if (score_tiles_per_pass(r) != NT) return;   // another instantiation's image
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
   const int32_t* sel = sel_idx + lo;
@@ -97,10 +99,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
         bb[u][1] = *reinterpret_cast<const uint4*>(brow[u] + k0 + 8);
       }
     };
-    load_step(0, fa, fb);
-    for (int k0 = 0; k0 < D; k0 += 64) {
-      uint4 na[MT][2], nb[NT][2];
-      if (k0 + 64 < D) load_step(k0 + 64, na, nb);
+    auto compute_step = [&](const uint4 (&a)[MT][2], const uint4 (&bb)[NT][2]) {
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -109,16 +108,29 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
           for (int u = 0; u < NT; ++u) {
             const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
             const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8_t, fa[t][h]), __builtin_bit_cast(bf16x8_t, fb[u][h]), zero, 0, 0, 0);
+                __builtin_bit_cast(bf16x8_t, a[t][h]), __builtin_bit_cast(bf16x8_t, bb[u][h]), zero, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
           }
-      if (k0 + 64 < D) {
-#pragma unroll
-        for (int t = 0; t < MT; ++t) { fa[t][0] = na[t][0]; fa[t][1] = na[t][1]; }
-#pragma unroll
-        for (int u = 0; u < NT; ++u) { fb[u][0] = nb[u][0]; fb[u][1] = nb[u][1]; }
-      }
+    };
+    // two fragment buffers used alternately, so that the loads of one are in
+    // flight while the other is consumed (no register copies between steps)
+    uint4 ga[MT][2], gb[NT][2];
+    // Loads are unconditional (the step index is clamped instead) so that the
+    // number of loads in flight is fixed and the waits can be counted ones.
+    // D is a multiple of 128 here, so steps come in pairs and nothing in the
+    // loop body is conditional.
+    const int last = D - 64;
+    load_step(0, fa, fb);
+    for (int k0 = 0; k0 < D; k0 += 128) {
+      load_step(k0 + 64, ga, gb);
+      __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic
+      compute_step(fa, fb);
+      __builtin_amdgcn_sched_barrier(0);
+      load_step(min(k0 + 128, last), fa, fb);
+      __builtin_amdgcn_sched_barrier(0);
+      compute_step(ga, gb);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
     // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile
