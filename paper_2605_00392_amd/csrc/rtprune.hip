@@ -191,9 +191,10 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
                   float* ratio, int32_t* keep_out, int32_t* sel, hipStream_t s) {
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SELECT, s);
-  hipLaunchKernelGGL(k_select, dim3(in->B), dim3(256), 0, s, in->offsets, in->D, p, density, keep_in,
+  const size_t lds = 9 * static_cast<size_t>((in->max_tokens + 1) & ~1);   // 8-byte key + flag per token
+  hipLaunchKernelGGL(k_select, dim3(in->B), dim3(256), lds, s, in->offsets, in->D, p, density, keep_in,
                      at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
-                     phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+                     in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
   return launched();
 }
 

@@ -201,23 +201,28 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
 }
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
-// handed out in the order team C, team B, two-copy, team A (eight one-wave
-// images per workgroup), i.e. the images with the longest latency start first.
+// handed out in the order team C, team B, team A (eight one-wave images per
+// workgroup), two-copy: the images with the longest latency start first.
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
                                                                const int32_t* __restrict__ work, int B,
                                                                const int32_t* __restrict__ status) {
   if (status[0]) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nA = work[kVariantA], nD = work[kVariantDual], nB = work[kVariantB], nC = work[kVariantC];
+  // longest-running roles first: team C, team B, then team A, then two-copy
   int blk = blockIdx.x;
   if (blk < nC) { sinkhorn_team_image<TeamC>(A, work[4 + kVariantC * B + blk], wave, lane); return; }
   blk -= nC;
   if (blk < nB) { sinkhorn_team_image<TeamB>(A, work[4 + kVariantB * B + blk], wave, lane); return; }
   blk -= nB;
-  if (blk < nD) { sinkhorn_dual_image(A, work[4 + kVariantDual * B + blk]); return; }
-  blk -= nD;
-  const int idx = blk * (kDualThreads / 64) + wave;
-  if (idx < nA) sinkhorn_team_image<TeamA>(A, work[4 + kVariantA * B + idx], 0, lane);
+  const int nAblocks = (nA + kDualThreads / 64 - 1) / (kDualThreads / 64);
+  if (blk < nAblocks) {
+    const int idx = blk * (kDualThreads / 64) + wave;
+    if (idx < nA) sinkhorn_team_image<TeamA>(A, work[4 + kVariantA * B + idx], 0, lane);
+    return;
+  }
+  blk -= nAblocks;
+  if (blk < nD) sinkhorn_dual_image(A, work[4 + kVariantDual * B + blk]);
 }
 
 }  // namespace rtp

@@ -177,12 +177,14 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
 __global__ __launch_bounds__(256) void k_select(
     const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
     const int32_t* __restrict__ keep_in, const float* __restrict__ score,
-    const double* __restrict__ partial, int chunks_per_image, int do_select,
+    const double* __restrict__ partial, int chunks_per_image, int do_select, int max_tokens,
     float* __restrict__ phi_out, float* __restrict__ ratio_out, int32_t* __restrict__ keep_out,
     int32_t* __restrict__ sel_idx, const int32_t* __restrict__ status) {
   if (status[0]) return;
-  __shared__ uint32_t keys[kMaxTokens];
-  __shared__ unsigned char kept_flag[kMaxTokens];
+  // dynamic LDS: 8-byte keys for n_pad = 2 * ceil(max_tokens / 2) tokens, then one flag byte each
+  extern __shared__ __attribute__((aligned(16))) unsigned char select_lds[];
+  unsigned long long* keys = reinterpret_cast<unsigned long long*>(select_lds);
+  unsigned char* kept_flag = select_lds + 8 * static_cast<size_t>((max_tokens + 1) & ~1);
   __shared__ double red[4];
   __shared__ int counts[256];
   __shared__ int s_m;
@@ -223,18 +225,33 @@ __global__ __launch_bounds__(256) void k_select(
     if (ratio_out) ratio_out[b] = ret32;
   }
   if (!do_select || n == 0) return;
-  for (int k = tid; k < n; k += 256) keys[k] = __float_as_uint(score[lo + k]);
+  // 64-bit key = (score bits, ~index): token l precedes token k in (score
+  // descending, index ascending) order exactly when key_l > key_k.
+  const int n_pad = (n + 1) & ~1;
+  for (int k = tid; k < n_pad; k += 256)
+    keys[k] = k < n ? (static_cast<unsigned long long>(__float_as_uint(score[lo + k])) << 32) |
+                          (0xffffffffu - static_cast<uint32_t>(k))
+                    : 0ull;                                   // padding precedes nothing
   __syncthreads();
   const int m = s_m;
 
-  for (int k = tid; k < n; k += 256) {
-    const uint32_t mine = keys[k];
-    int rank = 0;
-    for (int l = 0; l < n; ++l) {
-      const uint32_t other = keys[l];
-      rank += (other > mine) || (other == mine && l < k);
+  const ulonglong2* keys2 = reinterpret_cast<const ulonglong2*>(keys);
+  for (int kb = tid; kb < n; kb += 4 * 256) {
+    unsigned long long mine[4];
+    int rank[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      mine[u] = keys[min(kb + 256 * u, n - 1)];
+      rank[u] = 0;
     }
-    kept_flag[k] = rank < m;
+    for (int l2 = 0; l2 < n_pad / 2; ++l2) {
+      const ulonglong2 o = keys2[l2];                         // same address in every lane
+#pragma unroll
+      for (int u = 0; u < 4; ++u) rank[u] += (o.x > mine[u]) + (o.y > mine[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (kb + 256 * u < n) kept_flag[kb + 256 * u] = rank[u] < m;
   }
   __syncthreads();
 
