@@ -15,6 +15,8 @@ Every function cites the passage it follows:
 * log-space Sinkhorn iterations and the final plan: Appendix C;
 * merge: Eq. 6 (also the last equation of Appendix C);
 * inter-token similarity and the dynamic pruning ratio: Sec. 3.3.3, Eq. 7, 9;
+* textual density from Sobel edges: Sec. 3.3.3, Eq. 8, and Appendix B (exact
+  integer arithmetic on 8-bit pixels; the only real number is the threshold);
 * order of the steps: Algorithm 1.
 
 Arithmetic is float64 throughout.  Inputs are the exact values the device sees
@@ -365,3 +367,62 @@ def pairing_gaps(P_bar: np.ndarray) -> np.ndarray:
         return np.full(r, np.inf)
     top = np.sort(P32, axis=0)[::-1]
     return (top[0] - top[1]) / np.maximum(np.abs(top[0]), 1e-300)
+
+
+# ---------------------------------------------------------------------------
+# textual density (Sec. 3.3.3, Eq. 8; Appendix B)
+# ---------------------------------------------------------------------------
+GRAY_MILLI = (299, 587, 114)     # ITU-R BT.601 weights x 1000 (Appendix B)
+
+
+def gray_milli(rgb_u8: np.ndarray) -> np.ndarray:
+    """1000 x 255 x I(i, j): the BT.601 grayscale of Appendix B in exact integers.
+
+    With 8-bit channels and intensities scaled to [0, 1] (the scale on which the
+    default threshold tau = 0.2 is meaningful), I = (0.299 R + 0.587 G + 0.114 B) / 255.
+    """
+    c = np.asarray(rgb_u8).astype(np.int64)
+    return GRAY_MILLI[0] * c[..., 0] + GRAY_MILLI[1] * c[..., 1] + GRAY_MILLI[2] * c[..., 2]
+
+
+def sobel_xy(gray: np.ndarray):
+    """G_x and G_y of Appendix B (the printed 3x3 kernels) on an integer image.
+
+    Border pixels see their nearest neighbour repeated (reading: the paper does
+    not say; zero padding would turn every border pixel of a white page into an
+    edge).  Convolution versus correlation only flips signs, which the magnitude
+    does not see.
+    """
+    p = np.pad(gray, 1, mode="edge")
+    gx = (p[:-2, 2:] + 2 * p[1:-1, 2:] + p[2:, 2:]) - (p[:-2, :-2] + 2 * p[1:-1, :-2] + p[2:, :-2])
+    gy = (p[:-2, :-2] + 2 * p[:-2, 1:-1] + p[:-2, 2:]) - (p[2:, :-2] + 2 * p[2:, 1:-1] + p[2:, 2:])
+    return gx, gy
+
+
+def edge_map(rgb_u8: np.ndarray, tau: float) -> np.ndarray:
+    """E(i, j) = [G(i, j) >= tau], G = sqrt(G_x^2 + G_y^2) on intensities in [0, 1].
+
+    Evaluated without a square root and without rounding: in units of
+    1/(255 * 1000) the squared magnitude is an integer, compared with
+    (float32(tau) * 255000)^2.
+    """
+    gx, gy = sobel_xy(gray_milli(rgb_u8))
+    mag2 = (gx * gx + gy * gy).astype(np.float64)          # exact: below 2**53
+    t = float(np.float32(tau)) * 255000.0
+    return mag2 >= t * t
+
+
+def text_density(rgb_u8: np.ndarray, patch_h: int, patch_w: int, tau: float):
+    """rho_k per token patch (Eq. 8) and their average rho, both float32.
+
+    The image (H x W x 3, uint8) is cut into (H / patch_h) x (W / patch_w)
+    patches in raster order, one per visual token.
+    """
+    h, w = rgb_u8.shape[:2]
+    assert h % patch_h == 0 and w % patch_w == 0
+    e = edge_map(rgb_u8, tau)
+    counts = e.reshape(h // patch_h, patch_h, w // patch_w, patch_w).sum(axis=(1, 3)).astype(np.int64)
+    area = patch_h * patch_w
+    rho_k = (counts.astype(np.float64) / area).astype(np.float32).ravel()
+    rho = np.float32(float(counts.sum()) / float(counts.size * area))
+    return rho, rho_k

@@ -246,3 +246,48 @@ def subset(batch: Batch, picks: Sequence[int]) -> Batch:
               else batch.tokens[:0].copy())
     return Batch(batch.cfg, batch.dtype, tokens, offsets,
                  np.asarray(rho, dtype=np.float32), dict(batch.params), ids)
+
+
+# ---------------------------------------------------------------------------
+# synthetic page images (for the textual-density kernel)
+# ---------------------------------------------------------------------------
+# Encoder resolution modes: page side in pixels -> visual tokens; every token
+# covers a 64 x 64 pixel patch (512^2 -> 64, 640^2 -> 100, 1024^2 -> 256, 1280^2 -> 400).
+PAGE_MODES = {"tiny": 512, "small": 640, "base": 1024, "large": 1280}
+PATCH_PIXELS = 64
+
+
+def gen_page(seed: int, side: int = 1280) -> np.ndarray:
+    """A document-like RGB page (uint8, [side, side, 3]): light paper with faint
+    noise, margins, and a random number of text lines made of dark glyph-like
+    strokes, plus an occasional grey figure block.  A stand-in for benchmark page
+    scans; only the statistics that matter to an edge-density measure are modelled.
+    """
+    rng = np.random.default_rng(500000 + seed)
+    page = rng.normal(244.0, 2.0, size=(side, side)).astype(np.float32)
+    margin = int(side * rng.uniform(0.04, 0.12))
+    line_h = int(rng.integers(14, 30))
+    fill = rng.uniform(0.15, 0.95)                 # fraction of the text area that is used
+    y = margin
+    while y + line_h < side - margin:
+        if rng.uniform() < fill:
+            x0 = margin
+            x1 = side - margin - int(rng.integers(0, side // 3))
+            glyph_w = int(rng.integers(2, 5))
+            n_cols = max(1, (x1 - x0) // glyph_w)
+            ink = rng.uniform(size=(max(1, (line_h * 2 // 3) // glyph_w), n_cols)) < 0.45
+            block = np.kron(ink, np.ones((glyph_w, glyph_w), dtype=bool))
+            hh, ww = min(block.shape[0], line_h), min(block.shape[1], x1 - x0)
+            page[y:y + hh, x0:x0 + ww][block[:hh, :ww]] = rng.uniform(15, 70)
+        y += int(line_h * rng.uniform(1.2, 1.9))
+    if rng.uniform() < 0.3:                        # a flat grey figure
+        fy, fx = int(rng.integers(margin, side // 2)), int(rng.integers(margin, side // 2))
+        page[fy:fy + side // 4, fx:fx + side // 3] = rng.uniform(120, 200)
+    g = np.clip(np.rint(page), 0, 255).astype(np.uint8)
+    tint = rng.integers(-3, 4, size=3)
+    return np.clip(g[..., None].astype(np.int16) + tint[None, None, :], 0, 255).astype(np.uint8)
+
+
+def gen_pages(count: int, side: int = 1280, first: int = 0) -> np.ndarray:
+    """``count`` pages stacked as uint8 [count, side, side, 3]."""
+    return np.stack([gen_page(first + i, side) for i in range(count)], axis=0)
