@@ -65,7 +65,9 @@ typedef enum rtp_dtype {
 enum {
   RTP_DEV_OK = 0,
   RTP_DEV_BAD_OFFSETS = 1,   /* offsets not monotone / offsets[0] != 0 / offsets[B] != total_tokens */
-  RTP_DEV_IMAGE_TOO_LONG = 2 /* some image has more than max_tokens tokens */
+  RTP_DEV_IMAGE_TOO_LONG = 2, /* some image has more than max_tokens tokens */
+  RTP_DEV_BAD_IMAGE = 4       /* rtprune_text_density: a page's size is negative, above the stated
+                                 maximum, not a multiple of the patch size, or overruns its pixel span */
 };
 
 /* Hyper-parameters.  Defaults in the paper: z = 0.2, alpha = 0.1 (Algorithm 1,
@@ -185,6 +187,37 @@ int rtprune_prune(const rtprune_batch* in, const float* density,
                   int32_t* keep_counts, int32_t* sel_idx, int32_t* pair,
                   float* ratio, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/* Textual density (Sec. 3.3.3, Eq. 8; Appendix B): for each page image,
+ * grayscale I = (0.299 R + 0.587 G + 0.114 B) / 255, the two 3x3 Sobel responses
+ * G_x, G_y (border pixels see their nearest neighbour repeated), an edge pixel
+ * where sqrt(G_x^2 + G_y^2) >= tau, rho_k = fraction of edge pixels in token
+ * patch k, rho = average of rho_k over the page's patches.  The arithmetic is
+ * exact (integers; tau enters as (double)tau * 255000), so results do not
+ * depend on rounding.  rho is what rtprune_dynamic_ratio / rtprune_prune take
+ * as `density`.
+ *   pixels         device, uint8, pages packed back to back; page b is
+ *                  heights[b] x widths[b] x 3 (RGB interleaved, row-major) and
+ *                  starts at byte pixel_offsets[b]
+ *   pixel_offsets  [B + 1] int64 (device), heights / widths [B] int32 (device)
+ *   max_height, max_width   host upper bounds on the page sizes
+ *   patch_h, patch_w        pixels per token patch (64 x 64 for DeepSeek-OCR's
+ *                  native modes); every page size must be a multiple of them
+ *   density        [B] fp32 out
+ *   patch_density  fp32 out, rho_k in raster order, page b's patches starting
+ *                  at patch_offsets[b] (may be NULL; then patch_offsets may be)
+ *   patch_offsets  [B + 1] int32 (device)
+ * Device-visible errors set RTP_DEV_BAD_IMAGE in the workspace status word and
+ * leave the outputs untouched.  Limits: page sides <= 65536, and at least three
+ * luma rows of max_width + 2 ints must fit 60 KB of LDS (width <= 5118). */
+int rtprune_text_density_workspace_bytes(int32_t B, int32_t max_height, int32_t max_width,
+                                         int32_t patch_h, int32_t patch_w, size_t* bytes);
+int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_offsets,
+                         const int32_t* heights, const int32_t* widths, int32_t B,
+                         int32_t max_height, int32_t max_width, int32_t patch_h,
+                         int32_t patch_w, float tau, float* density, float* patch_density,
+                         const int32_t* patch_offsets, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /* Measurement aid (not part of the operator; process-global, not thread-safe).
  * While enabled, every kernel the calls above launch is bracketed by two HIP

@@ -20,6 +20,7 @@
 #include "sinkhorn_dual.hpp"
 #include "scores_mfma.hpp"
 #include "merge_lds.hpp"
+#include "density.hpp"
 
 using namespace rtp;
 
@@ -122,10 +123,11 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
                                              "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn",
-                                             "k_merge"};
+                                             "k_merge", "k_density_prepare", "k_density_sobel",
+                                             "k_density_finish"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
   std::mutex mu;
@@ -404,6 +406,79 @@ extern "C" int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t 
   if (total_tokens < 0 || total_tokens > 0x7fffffffLL) return RTP_EINVAL;
   *bytes = make_layout(B, total_tokens, max_tokens, D).total;
   return RTP_OK;
+}
+
+namespace {
+struct DensityLayout { size_t status, counts, total; int patches_max; long long ncounts; };
+DensityLayout make_density_layout(int B, int max_h, int max_w, int patch_h, int patch_w) {
+  DensityLayout L;
+  L.patches_max = (max_h / patch_h) * (max_w / patch_w);
+  L.ncounts = static_cast<long long>(B) * L.patches_max;
+  L.status = 0;
+  L.counts = 256;
+  L.total = align_up(256 + sizeof(int32_t) * static_cast<size_t>(L.ncounts));
+  return L;
+}
+int check_density_shape(int B, int max_h, int max_w, int patch_h, int patch_w) {
+  if (B < 0 || max_h < 0 || max_w < 0 || patch_h <= 0 || patch_w <= 0) return RTP_EINVAL;
+  if (max_h > 65536 || max_w > 65536) return RTP_EUNSUPPORTED;
+  if (max_w > 0 && density_strip_rows(patch_h, max_w) == 0) return RTP_EUNSUPPORTED;
+  return RTP_OK;
+}
+}  // namespace
+
+extern "C" int rtprune_text_density_workspace_bytes(int32_t B, int32_t max_height, int32_t max_width,
+                                                    int32_t patch_h, int32_t patch_w, size_t* bytes) {
+  if (!bytes) return RTP_EINVAL;
+  RTP_TRY(check_density_shape(B, max_height, max_width, patch_h, patch_w));
+  *bytes = make_density_layout(B, max_height, max_width, patch_h, patch_w).total;
+  return RTP_OK;
+}
+
+extern "C" int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_offsets,
+                                    const int32_t* heights, const int32_t* widths, int32_t B,
+                                    int32_t max_height, int32_t max_width, int32_t patch_h,
+                                    int32_t patch_w, float tau, float* density, float* patch_density,
+                                    const int32_t* patch_offsets, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  RTP_TRY(check_density_shape(B, max_height, max_width, patch_h, patch_w));
+  if (!pixel_offsets || !heights || !widths || !density) return RTP_EINVAL;
+  if (patch_density && !patch_offsets) return RTP_EINVAL;
+  if (!(tau == tau)) return RTP_EINVAL;
+  const DensityLayout L = make_density_layout(B, max_height, max_width, patch_h, patch_w);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < L.total)
+    return RTP_EWORKSPACE;
+  if (B == 0) return RTP_OK;
+  if (!pixels && max_height > 0 && max_width > 0) return RTP_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* status = at<int32_t>(workspace, L.status);
+  int32_t* counts = at<int32_t>(workspace, L.counts);
+  const long long* poff = reinterpret_cast<const long long*>(pixel_offsets);
+  {
+    ProfScope prof(KID_DENSITY_PREPARE, s);
+    const long long want = (L.ncounts + 255) / 256;
+    const unsigned grid = static_cast<unsigned>(want < 1 ? 1 : (want > 4096 ? 4096 : want));
+    hipLaunchKernelGGL(k_density_prepare, dim3(grid), dim3(256), 0, s, poff, heights, widths, B, max_height,
+                       max_width, patch_h, patch_w, counts, L.ncounts, status);
+  }
+  RTP_TRY(launched());
+  if (max_height > 0 && max_width > 0) {
+    const int strip = density_strip_rows(patch_h, max_width);
+    const size_t lds = sizeof(int) * (static_cast<size_t>(strip + 2) * (max_width + 2) + max_width / patch_w + 1);
+    // G >= tau on [0, 1] intensities <=> G_x^2 + G_y^2 >= (tau * 255 * 1000)^2 in luma units of 1/1000
+    const double t = static_cast<double>(tau) * 255000.0;
+    const double thr2 = t * t;
+    const float lo = static_cast<float>(thr2 * (1.0 - 2e-6)), hi = static_cast<float>(thr2 * (1.0 + 2e-6));
+    ProfScope prof(KID_DENSITY_SOBEL, s);
+    hipLaunchKernelGGL(k_density_sobel, dim3((max_height + strip - 1) / strip, B), dim3(kDensityThreads), lds, s,
+                       pixels, poff, heights, widths, strip, patch_h, patch_w, L.patches_max, lo, hi, thr2,
+                       counts, status);
+    RTP_TRY(launched());
+  }
+  ProfScope prof(KID_DENSITY_FINISH, s);
+  hipLaunchKernelGGL(k_density_finish, dim3(B), dim3(256), 0, s, heights, widths, patch_h, patch_w,
+                     L.patches_max, counts, density, patch_density, patch_offsets, status);
+  return launched();
 }
 
 extern "C" int rtprune_dynamic_ratio(const rtprune_batch* in, const float* density,

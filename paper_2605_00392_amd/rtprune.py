@@ -18,12 +18,13 @@ LIB_PATH = os.path.join(HERE, "librtprune.so")
 
 RTP_OK, RTP_EINVAL, RTP_EUNSUPPORTED, RTP_EWORKSPACE, RTP_EHIP = range(5)
 RTP_F32, RTP_BF16 = 0, 1
-RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG = 1, 2
+RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE = 1, 2, 4
 
 EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune",
     "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_copy_bytes",
+    "rtprune_text_density_workspace_bytes", "rtprune_text_density",
 )
 
 
@@ -82,6 +83,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_summary.restype = ctypes.c_int
     lib.rtprune_profile_summary.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+    lib.rtprune_text_density_workspace_bytes.restype = ctypes.c_int
+    lib.rtprune_text_density_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.rtprune_text_density.restype = ctypes.c_int
+    lib.rtprune_text_density.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp,
+                                         vp, ctypes.c_size_t, vp]
     lib.rtprune_copy_bytes.restype = ctypes.c_int
     lib.rtprune_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
     if path is None:
@@ -227,6 +233,23 @@ def rtprune_profile_summary():
 
 def rtprune_copy_bytes(dst, src, nbytes: int, stream=None) -> int:
     return load_library().rtprune_copy_bytes(_addr(dst), _addr(src), nbytes, _stream(stream))
+
+
+def rtprune_text_density_workspace_bytes(B: int, max_height: int, max_width: int, patch_h: int, patch_w: int):
+    """Returns ``(status, bytes)``."""
+    n = ctypes.c_size_t(0)
+    rc = load_library().rtprune_text_density_workspace_bytes(B, max_height, max_width, patch_h, patch_w,
+                                                             ctypes.byref(n))
+    return rc, int(n.value)
+
+
+def rtprune_text_density(pixels, pixel_offsets, heights, widths, B: int, max_height: int, max_width: int,
+                         patch_h: int, patch_w: int, tau: float, density, patch_density, patch_offsets,
+                         workspace, stream=None) -> int:
+    return load_library().rtprune_text_density(
+        _addr(pixels), _addr(pixel_offsets), _addr(heights), _addr(widths), B, max_height, max_width,
+        patch_h, patch_w, tau, _addr(density), _addr(patch_density), _addr(patch_offsets),
+        _addr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream))
 
 
 def alloc_workspace(batch: DeviceBatch):
