@@ -79,6 +79,57 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     return "hbm", 0.0, "GB/s", HBM_PEAK_GBS
 
 
+def bench_density(rt, torch, steps: int, unique: int = 16, copies: int = 16):
+    """Time rtprune_text_density on `unique * copies` large-mode pages (1280 x 1280 RGB)."""
+    from paper_2605_00392_amd import synth
+    side, patch = synth.PAGE_MODES["large"], synth.PATCH_PIXELS
+    pages = synth.gen_pages(unique, side)
+    dev = "cuda:0"
+    B = unique * copies
+    pix = torch.from_numpy(pages).to(dev).repeat(copies, 1, 1, 1).contiguous()
+    per = side * side * 3
+    poff = torch.arange(B + 1, dtype=torch.int64, device=dev) * per
+    hs = torch.full((B,), side, dtype=torch.int32, device=dev)
+    npatch = (side // patch) ** 2
+    pto = torch.arange(B + 1, dtype=torch.int32, device=dev) * npatch
+    rc, nbytes = rt.rtprune_text_density_workspace_bytes(B, side, side, patch, patch)
+    rt.check(rc)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    rho = torch.empty(B, dtype=torch.float32, device=dev)
+    rho_k = torch.empty(B * npatch, dtype=torch.float32, device=dev)
+
+    def run():
+        rt.check(rt.rtprune_text_density(pix, poff, hs, hs, B, side, side, patch, patch, 0.2, rho, rho_k, pto, ws))
+
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    rt.rtprune_profile_enable(1)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rc, prof = rt.rtprune_profile_summary()
+    rt.rtprune_profile_enable(0)
+    rt.check(rc)
+    ms = (t1 - t0) * 1e3 / steps
+    sobel = next((r["total_ms"] / r["launches"] for r in prof if r["kernel"] == "k_density_sobel"), None)
+    from oracle import rtprune_oracle as orc
+    c0 = time.perf_counter()
+    want = [orc.text_density(pages[i], patch, patch, 0.2)[0] for i in range(min(unique, 8))]
+    c1 = time.perf_counter()
+    got = rho.cpu().numpy()
+    assert all(got[i] == want[i] for i in range(len(want))), "text density differs from the oracle"
+    return {"pages": B, "page": f"{side}x{side}x3 u8", "ms_per_call": round(ms, 4),
+            "pages_per_s": round(B / (ms * 1e-3), 1),
+            "kernel": "k_density_sobel", "kernel_ms": None if sobel is None else round(sobel, 4),
+            "bound": "hbm", "achieved_GBs": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9, 1),
+            "peak_GBs": HBM_PEAK_GBS,
+            "frac": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "cpu_oracle_pages_per_s": round(len(want) / (c1 - c0), 2), "bit_exact_vs_oracle": True}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +138,7 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..5 (5 = 1024 x 400 tokens)")
     ap.add_argument("--cpu-images", type=int, default=192, help="images the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-density", action="store_true", help="skip the textual-density side measurement")
     ap.add_argument("--gen-workers", type=int, default=16,
                     help="processes drawing the synthetic batch (1: in-process, for runs under a profiler)")
     args = ap.parse_args()
@@ -205,6 +257,12 @@ def main() -> int:
                    near_ties=rep.selection_near_ties + rep.pairing_near_ties)
         del res
 
+    density = None
+    if not args.no_density:
+        del out, ws
+        torch.cuda.empty_cache()
+        density = bench_density(rt, torch, max(3, args.steps // 2))
+
     line = {
         "metric": "images/s pruned (fused rtprune_prune, 400-token 1280-d bf16 pages)",
         "value": round(images_per_s, 2),
@@ -222,6 +280,7 @@ def main() -> int:
         "step_hbm_floor_frac": round(step_hbm_frac, 5),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "text_density": density,
     }
     print(json.dumps(line))
     return 0
