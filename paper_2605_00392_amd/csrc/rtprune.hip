@@ -31,7 +31,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 // Byte offsets of the workspace regions for a batch shape.
 struct Layout {
-  size_t status, sqnorm, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
+  size_t status, norm64, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
   int chunks_per_image;
   long long plan_cap;   // entries available in kmat / plan
 };
@@ -45,7 +45,7 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4
   L.plan_cap = total * static_cast<long long>(max_tokens) / 4 + 1;
   L.status = take(256);
-  L.sqnorm = take(sizeof(double) * total);
+  L.norm64 = take(sizeof(double) * total);
   L.score = take(sizeof(float) * total);
   L.partial = take(sizeof(double) * static_cast<size_t>(B) * L.chunks_per_image * (D + 1));
   L.phi = take(sizeof(float) * B);
@@ -167,7 +167,7 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* 
                    hipStream_t s) {
   const dim3 grid(L.chunks_per_image, in->B), block(kNormThreads);
   const T* tok = static_cast<const T*>(in->tokens);
-  double* sq = at<double>(ws, L.sqnorm);
+  double* sq = at<double>(ws, L.norm64);
   float* sc = at<float>(ws, L.score);
   double* part = at<double>(ws, L.partial);
   const int32_t* st = at<int32_t>(ws, L.status);
@@ -213,7 +213,7 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
                     double* scores_out, int max_pruned_hint, hipStream_t s) {
   const T* tok = static_cast<const T*>(in->tokens);
-  const double* sq = at<double>(ws, L.sqnorm);
+  const double* sq = at<double>(ws, L.norm64);
   double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   ProfScope prof(KID_SCORES, s);

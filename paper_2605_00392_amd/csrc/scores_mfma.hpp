@@ -42,7 +42,7 @@ template <int NT>
 __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
     const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
-    const long long* __restrict__ plan_offsets, const double* __restrict__ sqnorm, DevParams p,
+    const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
     double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
     const int32_t* __restrict__ status) {
   constexpr int MT = kMfmaRowsPerWave / 16;
@@ -138,14 +138,14 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
     for (int u = 0; u < NT; ++u) {
       const int j = j0 + 16 * u + (lane & 15);
       if (j >= r) continue;
-      const double nj = sqrt(sqnorm[lo + clamp_index(sel[m + j], n)]);
+      const double nj = norm64[lo + clamp_index(sel[m + j], n)];
 #pragma unroll
       for (int t = 0; t < MT; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int i = i0 + 16 * t + 4 * (lane >> 4) + v;
           if (i < m) {
-            const double ni = sqrt(sqnorm[lo + clamp_index(sel[i], n)]);
+            const double ni = norm64[lo + clamp_index(sel[i], n)];
             const double s = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
             const long long at = po + static_cast<long long>(i) * r + j;
             kmat[at] = exp((s - p.shift) * inv_eps);

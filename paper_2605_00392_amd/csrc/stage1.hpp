@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ off
 template <typename T, int KMAX>
 __global__ __launch_bounds__(kNormThreads) void k_norms(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
-    double* __restrict__ sqnorm, float* __restrict__ score, float* __restrict__ norms_out,
+    double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
     double* __restrict__ partial, int chunks_per_image, const int32_t* __restrict__ status) {
   if (status[0]) return;
   const int b = blockIdx.y, chunk = blockIdx.x;
@@ -103,29 +103,44 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
     for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
       for (int u = 0; u < NB; ++u) q[u] += __shfl_xor(q[u], o, kWave);
+    // unit vectors: x / ||x|| in fp32 (exact 8-bit significand times a rounded
+    // reciprocal), summed over the group's rows in fp32 and folded into the fp64
+    // accumulators once per group; the rounding errors are independent and far
+    // below what moves the fp32 value of phi
+    float acc32[KMAX][4];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc32[k][e] = 0.f;
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int r = rb + kStep * u;
       if (r >= r1) break;
+      const double nrm = sqrt(q[u]);
       if (lane == 0) {
-        sqnorm[lo + r] = q[u];
+        norm64[lo + r] = nrm;
         score[lo + r] = static_cast<float>(q[u]);
-        if (norms_out) norms_out[lo + r] = static_cast<float>(sqrt(q[u]));
+        if (norms_out) norms_out[lo + r] = static_cast<float>(nrm);
       }
       if (dynamic) {
-        const double inv = 1.0 / fmax(sqrt(q[u]), kTinyNorm);
+        const double inv = 1.0 / fmax(nrm, kTinyNorm);
         wsum += q[u] * inv * inv;
+        const float inv32 = static_cast<float>(inv);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
-          // widen again from the packed registers instead of keeping the first
-          // pass's 80 doubles alive (the empty asm hides the value's origin)
-          forget_origin(raw[u][k]);
+          forget_origin(raw[u][k]);      // widen again rather than keep 80 floats alive
           float x[4];
           unpack4(raw[u][k], x);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[k][e] = fma(static_cast<double>(x[e]), inv, acc[k][e]);
+          for (int e = 0; e < 4; ++e) acc32[k][e] = fmaf(x[e], inv32, acc32[k][e]);
         }
       }
+    }
+    if (dynamic) {
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[k][e] += static_cast<double>(acc32[k][e]);
     }
   }
   if (!dynamic) return;

@@ -23,7 +23,7 @@ template <typename T, int KMAX>
 __global__ __launch_bounds__(256) void k_scores(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
-    const long long* __restrict__ plan_offsets, const double* __restrict__ sqnorm, DevParams p,
+    const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
     double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
     const int32_t* __restrict__ status) {
   if (status[0]) return;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void k_scores(
       if (g < ngroups) load4(rowi + 4 * g, xi[k]);
       else xi[k][0] = xi[k][1] = xi[k][2] = xi[k][3] = 0.f;
     }
-    const double ni = sqrt(sqnorm[lo + ti]);
+    const double ni = norm64[lo + ti];
     for (int j = 0; j < r; ++j) {
       const int tj = clamp_index(sel[m + j], n);
       const T* rowj = tokens + static_cast<size_t>(lo + tj) * D;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void k_scores(
       }
       dot = wave_sum(dot);
       if (lane == 0) {
-        const double nj = sqrt(sqnorm[lo + tj]);
+        const double nj = norm64[lo + tj];
         const double s = dot / fmax(ni * nj, kTinyNorm * kTinyNorm);
         const long long at = po + static_cast<long long>(i) * r + j;
         kmat[at] = exp((s - p.shift) * inv_eps);
