@@ -138,6 +138,7 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..5 (5 = 1024 x 400 tokens)")
     ap.add_argument("--cpu-images", type=int, default=192, help="images the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lib", default=None, help="path of an alternative build of librtprune.so")
     ap.add_argument("--no-density", action="store_true", help="skip the textual-density side measurement")
     ap.add_argument("--gen-workers", type=int, default=16,
                     help="processes drawing the synthetic batch (1: in-process, for runs under a profiler)")
@@ -158,6 +159,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.lib:
+        rt._lib = rt.load_library(args.lib)
     rt.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)

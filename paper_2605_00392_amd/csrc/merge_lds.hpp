@@ -1,10 +1,13 @@
 // Merge and compaction (Eq. 6): out_i = T_i + alpha * sum_j P_ij T_j, streamed.
 //
-// A workgroup of 4 waves owns 64 consecutive kept rows of one image.  The
+// A workgroup of 4 waves owns 16 consecutive kept rows of one image (measured:
+// many small single-pass workgroups keep the memory system busier than fewer
+// multi-pass ones, 0.38 ms against 0.46 ms at 64 rows on the 1024 x 400 batch,
+// although the pruned rows are then re-read from L2 by more workgroups).  The
 // pruned rows are staged through LDS in chunks (all of them at once when they
 // fit, which is the common case: the pruned set is small), so every kept row
 // is read from memory exactly once and written exactly once, and the pruned
-// rows come from LDS for all 64 kept rows.  A wave merges four kept rows at a
+// rows come from LDS for all the workgroup's kept rows.  A wave merges four kept rows at a
 // time: their loads are issued together and stay packed in registers (a lane
 // owns the 4-element groups lane + 64 k), the staged pruned rows are walked
 // once for all four with the plan entries P_ij broadcast from a
@@ -15,7 +18,10 @@
 
 namespace rtp {
 
-constexpr int kMergeBlockRows = 64;
+#ifndef RTP_MERGE_BLOCK_ROWS
+#define RTP_MERGE_BLOCK_ROWS 16
+#endif
+constexpr int kMergeBlockRows = RTP_MERGE_BLOCK_ROWS;
 constexpr int kMergeWaveRows = 4;    // kept rows a wave merges at a time
 constexpr int kMergeLdsBytes = 30 * 1024;
 constexpr int kMergeMaxChunk = 64;   // pruned rows per LDS chunk, at most one per lane

@@ -25,8 +25,14 @@ namespace rtp {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kMfmaRowsPerWave = 32;   // MT = 2 tiles of 16 kept rows
-constexpr int kMfmaWaves = 4;
+#ifndef RTP_MFMA_ROWS_PER_WAVE
+#define RTP_MFMA_ROWS_PER_WAVE 32
+#endif
+#ifndef RTP_MFMA_WAVES
+#define RTP_MFMA_WAVES 1
+#endif
+constexpr int kMfmaRowsPerWave = RTP_MFMA_ROWS_PER_WAVE;   // MT tiles of 16 kept rows
+constexpr int kMfmaWaves = RTP_MFMA_WAVES;
 
 // Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
 // the kernel below), chosen on the host from the largest pruned set the call

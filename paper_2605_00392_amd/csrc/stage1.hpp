@@ -7,7 +7,10 @@
 
 namespace rtp {
 
-constexpr int kNormRowsPerChunk = 128;  // token rows one workgroup of k_norms covers
+#ifndef RTP_NORM_ROWS_PER_CHUNK
+#define RTP_NORM_ROWS_PER_CHUNK 64
+#endif
+constexpr int kNormRowsPerChunk = RTP_NORM_ROWS_PER_CHUNK;  // token rows one workgroup of k_norms covers
 constexpr int kNormThreads = 256;
 
 // Validate the ragged layout; every later kernel of the call skips its work
