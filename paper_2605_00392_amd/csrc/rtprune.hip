@@ -54,7 +54,7 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   L.out_off = take(sizeof(int32_t) * (B + 1));
   L.plan_off = take(sizeof(long long) * (B + 1));
   L.sel = take(sizeof(int32_t) * total);
-  L.work = take(sizeof(int32_t) * (4 + 4 * static_cast<size_t>(B)));
+  L.work = take(sizeof(int32_t) * kWorkLists * (1 + static_cast<size_t>(B)));
   L.kmat = take(sizeof(double) * L.plan_cap);
   L.plan = take(sizeof(float) * L.plan_cap);
   L.total = at;

@@ -154,76 +154,223 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
   }
 }
 
-// Work lists for the register-resident kernels: `work` holds four counts
-// (team A, two-copy, team B, team C images) followed by four lists of B image
+// The same two-copy scheme for up to 47 pruned tokens (R + 1 <= 48,
+// M + 1 <= 512).  The row copy stays fp64 (48 doubles per thread); the column
+// copy, which only feeds the v-update's sums, is held in fp32 (lane = column,
+// wave = 64-row chunk) so that both fit the register file: a relative rounding
+// of 6e-8 per entry averages out to a few 1e-9 on a column sum, far inside the
+// 1e-6 near-tie band.  The plan and the pairing are formed from the fp64 row copy.
+constexpr int kDual48Cols = 48;
+
+__device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int b) {
+  const DevParams& p = A.p;
+  const int32_t* __restrict__ offsets = A.offsets;
+  const long long* __restrict__ plan_offsets = A.plan_offsets;
+  const double* __restrict__ kmat = A.kmat;
+  float* __restrict__ plan_out = A.plan_out;
+  int32_t* __restrict__ pair_out = A.pair_out;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  if (n <= 0) return;
+  const int m = min(max(A.keep[b], 0), n), r = n - m;
+  if (!(m + 1 <= kDualRows && r + 1 <= kDual48Cols)) return;
+  if (pair_out)
+    for (int i = tid; i < m; i += kDualThreads) pair_out[lo + i] = i;
+  if (r <= 0 || m <= 0) return;
+  if (!plan_fits(plan_offsets[b], m, r, A.plan_cap)) return;
+  const long long po = plan_offsets[b];
+  const double* Kg = kmat + po;
+  const double kz = exp((p.z - p.shift) / p.eps);
+  constexpr int NW = kDualThreads / 64;
+
+  __shared__ double xs[kDualRows];
+  __shared__ double part[NW][64];
+  __shared__ double ys[NW][64];
+  __shared__ float pv[NW][kDual48Cols];
+  __shared__ int pi[NW][kDual48Cols];
+
+  double Kr[kDual48Cols];
+#pragma unroll
+  for (int c = 0; c < kDual48Cols; ++c) {
+    double v = 0.0;
+    if (tid <= m && c <= r) v = (tid < m && c < r) ? Kg[static_cast<long long>(tid) * r + c] : kz;
+    Kr[c] = v;
+  }
+  float Kc[64];
+#pragma unroll
+  for (int a = 0; a < 64; ++a) {
+    const int i = 64 * wave + a;
+    double v = 0.0;
+    if (i <= m && lane <= r) v = (i < m && lane < r) ? Kg[static_cast<long long>(i) * r + lane] : kz;
+    Kc[a] = static_cast<float>(v);
+  }
+  const double a_row = tid < m ? 1.0 : static_cast<double>(r);
+  const double b_col = lane < r ? 1.0 : static_cast<double>(m);
+
+  double x = (tid <= m) ? exp(p.shift / p.eps) : 0.0;
+  double y = (lane <= r) ? 1.0 : 0.0;
+  xs[tid] = x;
+  ys[wave][lane] = y;
+  __syncthreads();
+
+  for (int it = 0; it < p.iters; ++it) {
+    {
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int c = 0; c < kDual48Cols; c += 2) {
+        s0 = fma(Kr[c], ys[wave][c], s0);
+        s1 = fma(Kr[c + 1], ys[wave][c + 1], s1);
+      }
+      x = (tid <= m) ? a_row * rcp64(s0 + s1) : 0.0;
+      xs[tid] = x;
+    }
+    __syncthreads();
+    {
+      const double* xq = xs + 64 * wave;
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int a = 0; a < 64; a += 2) {
+        s0 = fma(static_cast<double>(Kc[a]), xq[a], s0);
+        s1 = fma(static_cast<double>(Kc[a + 1]), xq[a + 1], s1);
+      }
+      part[wave][lane] = s0 + s1;
+    }
+    __syncthreads();
+    {
+      double t = 0.0;
+#pragma unroll
+      for (int c = 0; c < NW; ++c) t += part[c][lane];
+      y = (lane <= r) ? b_col * rcp64(t) : 0.0;
+      ys[wave][lane] = y;                  // read back by this wave only
+    }
+  }
+  __syncthreads();
+
+  // plan row and, per column, the wave's best (value, row): the dustbin is row m
+  float* P = (plan_out && tid < m) ? plan_out + po + static_cast<long long>(tid) * r : nullptr;
+  for (int c = 0; c < r; ++c) {
+    float v = -1.f;
+    int idx = 0x7fffffff;
+    if (tid <= m) {
+      double kc = 0.0;
+#pragma unroll
+      for (int cc = 0; cc < kDual48Cols; ++cc) kc = (cc == c) ? Kr[cc] : kc;   // static register indexing
+      v = static_cast<float>(x * kc * ys[wave][c]);
+      idx = tid;
+      if (P) P[c] = v;
+    }
+    if (pair_out) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, kWave);
+        const int oi = __shfl_xor(idx, o, kWave);
+        if (ov > v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+      }
+      if (lane == 0) { pv[wave][c] = v; pi[wave][c] = idx; }
+    }
+  }
+  if (!pair_out) return;
+  __syncthreads();
+  if (tid < r) {
+    float bv = pv[0][tid];
+    int bi = pi[0][tid];
+#pragma unroll
+    for (int c = 1; c < NW; ++c) {
+      const float ov = pv[c][tid];
+      const int oi = pi[c][tid];
+      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    pair_out[lo + m + tid] = (bi >= m) ? -1 : bi;
+  }
+}
+
+// Work lists for the register-resident kernels: `work` holds kWorkLists counts
+// (one per shape, indexed by variant id) followed by as many lists of B image
 // indices each.  One workgroup; list order follows image order.
 __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
                                                   const int32_t* __restrict__ keep, int B,
                                                   int32_t* __restrict__ work,
                                                   const int32_t* __restrict__ status) {
   if (status[0]) return;
-  __shared__ int cnt[4][256];
+  constexpr int NV = kWorkLists;
+  __shared__ int cnt[NV][256];
   const int tid = threadIdx.x;
   const int span = (B + 255) / 256;
   const int b0 = min(B, tid * span), b1 = min(B, b0 + span);
-  int c[4] = {0, 0, 0, 0};
+  int c[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) c[v] = 0;
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
     const int v = sinkhorn_variant(m, n - m);
-    if (n > 0 && v < kGeneralVariant) ++c[v];
+    if (n > 0 && v < kGeneralVariant) {
+#pragma unroll
+      for (int u = 0; u < NV; ++u) c[u] += (u == v);
+    }
   }
 #pragma unroll
-  for (int v = 0; v < 4; ++v) cnt[v][tid] = c[v];
+  for (int v = 0; v < NV; ++v) cnt[v][tid] = c[v];
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {
-    int add[4];
+    int add[NV];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) add[v] = tid >= o ? cnt[v][tid - o] : 0;
+    for (int v = 0; v < NV; ++v) add[v] = tid >= o ? cnt[v][tid - o] : 0;
     __syncthreads();
 #pragma unroll
-    for (int v = 0; v < 4; ++v) cnt[v][tid] += add[v];
+    for (int v = 0; v < NV; ++v) cnt[v][tid] += add[v];
     __syncthreads();
   }
-  int at[4];
+  int at[NV];
 #pragma unroll
-  for (int v = 0; v < 4; ++v) at[v] = cnt[v][tid] - c[v];
+  for (int v = 0; v < NV; ++v) at[v] = cnt[v][tid] - c[v];
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
     const int v = sinkhorn_variant(m, n - m);
-    if (n > 0 && v < kGeneralVariant) work[4 + v * B + at[v]++] = b;
+    if (n > 0 && v < kGeneralVariant) {
+#pragma unroll
+      for (int u = 0; u < NV; ++u)
+        if (u == v) work[NV + u * B + at[u]++] = b;
+    }
   }
   if (tid == 255) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) work[v] = cnt[v][255];
+    for (int v = 0; v < NV; ++v) work[v] = cnt[v][255];
   }
 }
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
-// handed out in the order team C, team B, team A (eight one-wave images per
-// workgroup), two-copy: the images with the longest latency start first.
+// handed out longest-running role first: team C, team B, two-copy (48 columns),
+// team A (eight one-wave images per workgroup), two-copy (32 columns).
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
                                                                const int32_t* __restrict__ work, int B,
                                                                const int32_t* __restrict__ status) {
   if (status[0]) return;
+  constexpr int NV = kWorkLists;
+  constexpr int kWavesPerBlock = kDualThreads / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nA = work[kVariantA], nD = work[kVariantDual], nB = work[kVariantB], nC = work[kVariantC];
-  // longest-running roles first: team C, team B, then team A, then two-copy
   int blk = blockIdx.x;
-  if (blk < nC) { sinkhorn_team_image<TeamC>(A, work[4 + kVariantC * B + blk], wave, lane); return; }
-  blk -= nC;
-  if (blk < nB) { sinkhorn_team_image<TeamB>(A, work[4 + kVariantB * B + blk], wave, lane); return; }
-  blk -= nB;
-  const int nAblocks = (nA + kDualThreads / 64 - 1) / (kDualThreads / 64);
-  if (blk < nAblocks) {
-    const int idx = blk * (kDualThreads / 64) + wave;
-    if (idx < nA) sinkhorn_team_image<TeamA>(A, work[4 + kVariantA * B + idx], 0, lane);
+  int cnt = work[kVariantC];
+  if (blk < cnt) { sinkhorn_team_image<TeamC>(A, work[NV + kVariantC * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantB];
+  if (blk < cnt) { sinkhorn_team_image<TeamB>(A, work[NV + kVariantB * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantDual48];
+  if (blk < cnt) { sinkhorn_dual48_image(A, work[NV + kVariantDual48 * B + blk]); return; }
+  blk -= cnt;
+  const int nA = work[kVariantA];
+  cnt = (nA + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (blk < cnt) {
+    const int idx = blk * kWavesPerBlock + wave;
+    if (idx < nA) sinkhorn_team_image<TeamA>(A, work[NV + kVariantA * B + idx], 0, lane);
     return;
   }
-  blk -= nAblocks;
-  if (blk < nD) sinkhorn_dual_image(A, work[4 + kVariantDual * B + blk]);
+  blk -= cnt;
+  if (blk < work[kVariantDual]) sinkhorn_dual_image(A, work[NV + kVariantDual * B + blk]);
 }
 
 }  // namespace rtp
-

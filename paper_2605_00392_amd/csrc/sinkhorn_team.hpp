@@ -46,15 +46,19 @@ struct TeamShape {
 using TeamA = TeamShape<1, 0, 7, 8>;     // M <= 448,  R <= 8    one wave
 using TeamB = TeamShape<8, 2, 4, 10>;    // M <= 512,  R <= 40
 using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
-// The two-copy kernel (sinkhorn_dual.hpp) takes M + 1 <= 512, R + 1 <= 32.
+// The two-copy kernels (sinkhorn_dual.hpp) take M + 1 <= 512 and R + 1 <= 32
+// (both copies fp64) or R + 1 <= 48 (column copy fp32).
 constexpr int kDualRows = 512, kDualCols = 32;
-constexpr int kVariantA = 0, kVariantDual = 1, kVariantB = 2, kVariantC = 3, kGeneralVariant = 4;
+constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
+              kGeneralVariant = 5;
+constexpr int kWorkLists = 5;
 
 // Which Sinkhorn kernel serves an image; every kernel evaluates this and takes
 // only its own images, so each image is processed exactly once.
 __host__ __device__ inline int sinkhorn_variant(int m, int r) {
   if (TeamA::fits(m, r)) return kVariantA;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
+  if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if (TeamC::fits(m, r)) return kVariantC;
   return kGeneralVariant;
