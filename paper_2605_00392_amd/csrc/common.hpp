@@ -89,6 +89,40 @@ __device__ __forceinline__ double wave_sum(double v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
   return v;
 }
+// The same total with register-to-register lane exchanges only (no LDS
+// crossbar): two quad permutes and two mirror steps inside each row of 16
+// lanes - after the quad steps all lanes of a quad agree, so mirroring 8 and
+// then 16 lanes pairs each group with its neighbour - then the row swap and
+// half swap instructions, which hand each lane its partner's value in the other
+// operand.  Every lane gets the total.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_sum_dpp(double v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  {
+    const unsigned lo = __double2loint(v), hi = __double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    v = __hiloint2double(static_cast<int>(b[0]), static_cast<int>(a[0])) +
+        __hiloint2double(static_cast<int>(b[1]), static_cast<int>(a[1]));
+  }
+  {
+    const unsigned lo = __double2loint(v), hi = __double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    v = __hiloint2double(static_cast<int>(b[0]), static_cast<int>(a[0])) +
+        __hiloint2double(static_cast<int>(b[1]), static_cast<int>(a[1]));
+  }
+  return v;
+}
 __device__ __forceinline__ int wave_sum(int v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

