@@ -172,12 +172,19 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* 
   double* part = at<double>(ws, L.partial);
   const int32_t* st = at<int32_t>(ws, L.status);
   ProfScope prof(KID_NORMS, s);
-  if (in->D <= 1280)
-    hipLaunchKernelGGL((k_norms<T, 5>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, sc,
-                       norms_out, part, L.chunks_per_image, st);
-  else
-    hipLaunchKernelGGL((k_norms<T, 16>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, sc,
-                       norms_out, part, L.chunks_per_image, st);
+  // groups of four elements per row; the lean variants need every k but the last
+  // to be fully populated
+  const int ngroups = in->D / 4;
+#define RTP_LAUNCH_NORMS(KMAX, KFULL)                                                                  \
+  hipLaunchKernelGGL((k_norms<T, KMAX, KFULL>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, \
+                     sc, norms_out, part, L.chunks_per_image, st)
+  if (in->D <= 1280) {
+    if (ngroups >= 64 * 4) RTP_LAUNCH_NORMS(5, 4);
+    else RTP_LAUNCH_NORMS(5, 0);
+  } else {
+    RTP_LAUNCH_NORMS(16, 0);
+  }
+#undef RTP_LAUNCH_NORMS
   return launched();
 }
 

@@ -21,10 +21,12 @@
 #pragma once
 #include "common.hpp"
 #include "sinkhorn_team.hpp"
+#include "sinkhorn_wave.hpp"
 
 namespace rtp {
 
 constexpr int kDualThreads = 512;  // = kDualRows: one augmented row per thread
+static_assert(kDualThreads == 64 * kSinkhornBlockWaves, "workgroup shape");
 constexpr int kDualChunks = 16;    // 32-row chunks of the column copy
 
 // One image on the whole 512-thread workgroup.
@@ -347,7 +349,8 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
 // handed out longest-running role first: team C, team B, two-copy (48 columns),
-// team A (eight one-wave images per workgroup), two-copy (32 columns).
+// one-wave (eight images per workgroup), two-copy (32 columns), two-wave (four
+// images per workgroup).
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
                                                                const int32_t* __restrict__ work, int B,
                                                                const int32_t* __restrict__ status) {
@@ -356,11 +359,12 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   constexpr int kWavesPerBlock = kDualThreads / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int blk = blockIdx.x;
-#ifdef RTP_ONLY_ROLE   // timing aid: run one role only (0 = C, 1 = B, 2 = two-copy 48, 3 = A, 4 = two-copy 32)
+#ifdef RTP_ONLY_ROLE   // timing aid: run one role only (0 = C, 1 = B, 2 = two-copy 48, 3 = one-wave, 4 = two-copy 32, 5 = two-wave)
   {
     const int n0 = work[kVariantC], n1 = work[kVariantB], n2 = work[kVariantDual48],
-              n3 = (work[kVariantA] + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int role = blk < n0 ? 0 : blk < n0 + n1 ? 1 : blk < n0 + n1 + n2 ? 2 : blk < n0 + n1 + n2 + n3 ? 3 : 4;
+              n3 = (work[kVariantA] + kWavesPerBlock - 1) / kWavesPerBlock, n4 = work[kVariantDual];
+    const int role = blk < n0 ? 0 : blk < n0 + n1 ? 1 : blk < n0 + n1 + n2 ? 2 : blk < n0 + n1 + n2 + n3 ? 3
+                     : blk < n0 + n1 + n2 + n3 + n4 ? 4 : 5;
     if (role != RTP_ONLY_ROLE) return;
   }
 #endif
@@ -383,11 +387,20 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   cnt = (nA + kWavesPerBlock - 1) / kWavesPerBlock;
   if (blk < cnt) {
     const int idx = blk * kWavesPerBlock + wave;
-    if (idx < nA) sinkhorn_team_image<TeamA>(A, work[NV + kVariantA * B + idx], 0, lane);
+    if (idx < nA) sinkhorn_waves_image<WaveShape>(A, work[NV + kVariantA * B + idx], wave, 0, lane);
     return;
   }
   blk -= cnt;
-  if (blk < work[kVariantDual]) sinkhorn_dual_image(A, work[NV + kVariantDual * B + blk]);
+  cnt = work[kVariantDual];
+  if (blk < cnt) { sinkhorn_dual_image(A, work[NV + kVariantDual * B + blk]); return; }
+  blk -= cnt;
+  constexpr int kPairsPerBlock = kWavesPerBlock / PairShape::kWaves;
+  const int nP = work[kVariantPair];
+  if (blk < (nP + kPairsPerBlock - 1) / kPairsPerBlock) {
+    const int slot = wave / PairShape::kWaves, idx = blk * kPairsPerBlock + slot;
+    sinkhorn_waves_image<PairShape>(A, idx < nP ? work[NV + kVariantPair * B + idx] : -1, slot,
+                                    wave % PairShape::kWaves, lane);
+  }
 }
 
 }  // namespace rtp

@@ -43,20 +43,33 @@ struct TeamShape {
 
 // The shapes compiled in, tried in this order; an image that fits none is left
 // to the general kernel (variant kGeneralVariant).
-using TeamA = TeamShape<1, 0, 7, 8>;     // M <= 448,  R <= 8    one wave
 using TeamB = TeamShape<8, 2, 4, 10>;    // M <= 512,  R <= 40
 using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
+// The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
+// lane, kCols augmented columns.
+struct WaveShape {
+  static constexpr int kWaves = 1, kRows = 7, kCols = 8;
+  static constexpr int kMaxRows = 64 * kWaves * kRows;
+  __host__ __device__ static constexpr bool fits(int m, int r) { return m + 1 <= kMaxRows && r + 1 <= kCols; }
+};
+struct PairShape {
+  static constexpr int kWaves = 2, kRows = 4, kCols = 16;
+  static constexpr int kMaxRows = 64 * kWaves * kRows;
+  __host__ __device__ static constexpr bool fits(int m, int r) { return m + 1 <= kMaxRows && r + 1 <= kCols; }
+};
+constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 // The two-copy kernels (sinkhorn_dual.hpp) take M + 1 <= 512 and R + 1 <= 32
-// (both copies fp64) or R + 1 <= 48 (column copy fp32).
+// or R + 1 <= 48.
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
-              kGeneralVariant = 5;
-constexpr int kWorkLists = 5;
+              kVariantPair = 5, kGeneralVariant = 6;
+constexpr int kWorkLists = 6;
 
 // Which Sinkhorn kernel serves an image; every kernel evaluates this and takes
 // only its own images, so each image is processed exactly once.
 __host__ __device__ inline int sinkhorn_variant(int m, int r) {
-  if (TeamA::fits(m, r)) return kVariantA;
+  if (WaveShape::fits(m, r)) return kVariantA;
+  if (PairShape::fits(m, r)) return kVariantPair;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;

@@ -8,7 +8,7 @@
 namespace rtp {
 
 #ifndef RTP_NORM_ROWS_PER_CHUNK
-#define RTP_NORM_ROWS_PER_CHUNK 64
+#define RTP_NORM_ROWS_PER_CHUNK 80
 #endif
 constexpr int kNormRowsPerChunk = RTP_NORM_ROWS_PER_CHUNK;  // token rows one workgroup of k_norms covers
 constexpr int kNormThreads = 256;
@@ -45,47 +45,41 @@ __global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ off
 // When `dynamic`, the workgroup also sums T_k / max(||T_k||, tiny) over its rows
 // and writes the D-vector (plus sum_k ||unit_k||^2 as element D) to
 // partial[(b * chunks_per_image + chunk) * (D + 1) ...].
-template <typename T, int KMAX>
-__global__ __launch_bounds__(kNormThreads) void k_norms(
-    const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
-    double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
-    double* __restrict__ partial, int chunks_per_image, const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  const int b = blockIdx.y, chunk = blockIdx.x;
-  const int lo = offsets[b];
-  const int n = offsets[b + 1] - lo;
-  const int r0 = chunk * kNormRowsPerChunk;
-  if (r0 >= n) return;
-  const int r1 = min(n, r0 + kNormRowsPerChunk);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int ngroups = D >> 2;
-
-  double acc[KMAX][4];
-#pragma unroll
-  for (int k = 0; k < KMAX; ++k)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[k][e] = 0.0;
-  double wsum = 0.0;
-
-  // A wave takes its rows four at a time: the four rows' loads are issued
-  // together (raw, still packed), their four squared norms go through the lane
-  // butterfly interleaved, and only then are the unit vectors accumulated.
+//
+// KFULL = number of k whose 64 groups all lie inside the row (their loads need
+// no guard); the remaining k read a clamped address and are zeroed by a select.
+template <typename T, int KMAX, int KFULL, int NB>
+struct NormRows {
   typedef typename Raw4<T>::type raw_t;
-  constexpr int kStep = kNormThreads / kWave;      // row stride between a wave's rows
-  constexpr int NB = KMAX <= 5 ? 4 : 1;
-  for (int rb = r0 + wave; rb < r1; rb += kStep * NB) {
-    raw_t raw[NB][KMAX];
+  static constexpr int kStep = kNormThreads / kWave;   // row stride between a wave's rows
+
+  // Issue the loads of rows rb, rb + kStep, ... (clamped to last_row), still packed.
+  static __device__ __forceinline__ void load(raw_t (&raw)[NB][KMAX], const T* __restrict__ tokens, int lo,
+                                              int rb, int last_row, int D, int ngroups, int lane) {
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
-      const int r = min(rb + kStep * u, r1 - 1);
+      const int r = min(rb + kStep * u, last_row);
       const T* row = tokens + static_cast<size_t>(lo + r) * D;
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int g = lane + kWave * k;
-        if (g < ngroups) raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * g);
-        else raw[u][k] = raw_t{};
+        raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * (k < KFULL ? g : min(g, ngroups - 1)));
       }
     }
+  }
+
+  // Norms and scores of the loaded rows (those below r1), and their unit vectors
+  // into acc32 / wsum.
+  static __device__ __forceinline__ void reduce(raw_t (&raw)[NB][KMAX], int lo, int rb, int r1, int ngroups,
+                                                int lane, int dynamic, double* __restrict__ norm64,
+                                                float* __restrict__ score, float* __restrict__ norms_out,
+                                                float (&acc32)[KMAX][4], double& wsum) {
+#pragma unroll
+    for (int k = KFULL; k < KMAX; ++k)
+      if (lane + kWave * k >= ngroups) {
+#pragma unroll
+        for (int u = 0; u < NB; ++u) raw[u][k] = raw_t{};
+      }
     double q[NB];
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
@@ -104,15 +98,6 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) q[u] = wave_sum_dpp(q[u]);
-    // unit vectors: x / ||x|| in fp32 (exact 8-bit significand times a rounded
-    // reciprocal), summed over the group's rows in fp32 and folded into the fp64
-    // accumulators once per group; the rounding errors are independent and far
-    // below what moves the fp32 value of phi
-    float acc32[KMAX][4];
-#pragma unroll
-    for (int k = 0; k < KMAX; ++k)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc32[k][e] = 0.f;
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int r = rb + kStep * u;
@@ -137,48 +122,94 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
         }
       }
     }
-    if (dynamic) {
+  }
+};
+
+template <typename T, int KMAX, int KFULL>
+__global__ __launch_bounds__(kNormThreads) void k_norms(
+    const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
+    double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
+    double* __restrict__ partial, int chunks_per_image, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  const int r0 = chunk * kNormRowsPerChunk;
+  if (r0 >= n) return;
+  const int r1 = min(n, r0 + kNormRowsPerChunk);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ngroups = D >> 2;
+
+  // Unit vectors x / ||x|| are formed in fp32 (an exact 8- or 24-bit significand
+  // times a rounded reciprocal) and a wave adds up those of its own rows - a
+  // quarter of the chunk, at most kNormRowsPerChunk / 4 - in fp32; across waves
+  // and chunks the sums continue in fp64.  The fp32 rounding errors are
+  // independent, at most 2^-24 of a partial sum of a few units each, and far
+  // below what moves the fp32 value of phi.
+  float acc32[KMAX][4];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k)
+  for (int k = 0; k < KMAX; ++k)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[k][e] += static_cast<double>(acc32[k][e]);
+    for (int e = 0; e < 4; ++e) acc32[k][e] = 0.f;
+  double wsum = 0.0;
+
+  // A wave takes its rows four at a time: the four rows' loads are issued
+  // together (raw, still packed), their four squared norms go through the lane
+  // butterfly interleaved, and only then are the unit vectors accumulated.
+  constexpr int NB = KMAX <= 5 ? 4 : 1;
+  typedef NormRows<T, KMAX, KFULL, NB> Rows;
+  constexpr int kStride = Rows::kStep * NB;             // rows between a wave's successive groups
+  constexpr int kGroups = kNormRowsPerChunk / kStride;  // groups per wave in a full chunk
+  if (NB == 4 && kGroups >= 2 && r1 - r0 == kNormRowsPerChunk) {
+    // Full chunk: straight-line code over two register buffers, the next group's
+    // loads always in flight while the current one is reduced.
+    typename Rows::raw_t bufa[NB][KMAX], bufb[NB][KMAX];
+    Rows::load(bufa, tokens, lo, r0 + wave, r1 - 1, D, ngroups, lane);
+#pragma unroll
+    for (int i = 0; i < kGroups; ++i) {
+      if (i + 1 < kGroups)
+        Rows::load((i & 1) ? bufa : bufb, tokens, lo, r0 + wave + kStride * (i + 1), r1 - 1, D, ngroups, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      Rows::reduce((i & 1) ? bufb : bufa, lo, r0 + wave + kStride * i, r1, ngroups, lane, dynamic, norm64, score,
+                   norms_out, acc32, wsum);
+    }
+  } else {
+    for (int rb = r0 + wave; rb < r1; rb += kStride) {
+      typename Rows::raw_t raw[NB][KMAX];
+      Rows::load(raw, tokens, lo, rb, r1 - 1, D, ngroups, lane);
+      Rows::reduce(raw, lo, rb, r1, ngroups, lane, dynamic, norm64, score, norms_out, acc32, wsum);
     }
   }
   if (!dynamic) return;
 
-  // Sum the four waves' vectors through LDS, one wave's contribution at a time.
-  __shared__ double lds[kWave * KMAX * 4];
-  __shared__ double lds_w;
+  // The four waves' vectors meet in LDS, laid out by column; every thread then
+  // adds the four partials of its columns in fp64 and writes them out.
   constexpr int kWaves = kNormThreads / kWave;
-  for (int w = 1; w < kWaves; ++w) {
-    if (wave == w) {
+  constexpr int kCols = 4 * kWave * KMAX;
+  __shared__ __attribute__((aligned(16))) float lds[kWaves][kCols];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k)
+  for (int k = 0; k < KMAX; ++k)
+    *reinterpret_cast<float4*>(&lds[wave][4 * (lane + kWave * k)]) =
+        make_float4(acc32[k][0], acc32[k][1], acc32[k][2], acc32[k][3]);
+  __syncthreads();
+  double* out = partial + (static_cast<size_t>(b) * chunks_per_image + chunk) * (D + 1);
+  for (int c = threadIdx.x; c < D; c += kNormThreads) {
+    double s = 0.0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) lds[(k * 4 + e) * kWave + lane] = acc[k][e];
-      if (lane == 0) lds_w = wsum;
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int k = 0; k < KMAX; ++k)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[k][e] += lds[(k * 4 + e) * kWave + lane];
-      wsum += lds_w;
-    }
-    __syncthreads();
+    for (int w = 0; w < kWaves; ++w) s += static_cast<double>(lds[w][c]);
+    out[c] = s;
   }
-  if (wave == 0) {
-    double* out = partial + (static_cast<size_t>(b) * chunks_per_image + chunk) * (D + 1);
+  // sum_k ||unit_k||^2: the waves' counts go through the first words of the
+  // (now idle) vector buffer
+  __syncthreads();
+  double* lds_w = reinterpret_cast<double*>(&lds[0][0]);
+  if (lane == 0) lds_w[wave] = wsum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) {
-      const int g = lane + kWave * k;
-      if (g < ngroups) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) out[4 * g + e] = acc[k][e];
-      }
-    }
-    if (lane == 0) out[D] = wsum;
+    for (int w = 0; w < kWaves; ++w) s += lds_w[w];
+    out[D] = s;
   }
 }
 
