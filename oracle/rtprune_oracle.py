@@ -72,6 +72,7 @@ class Params:
     ratio_max: float = 1.0
     phi_lo: float = 0.0     # f_normalize(phi) = clamp((phi - lo) / (hi - lo), 0, 1)
     phi_hi: float = 1.0
+    metric: int = 0         # importance score: 0 = l2 norm (Eq. 1), 1 = variance (Table 7 ablation)
 
     @staticmethod
     def from_dict(d: Dict[str, float]) -> "Params":
@@ -129,12 +130,36 @@ def token_norms(X: np.ndarray) -> np.ndarray:
     return np.sqrt(token_sqnorms(X))
 
 
-def selection_scores(X: np.ndarray) -> np.ndarray:
-    """The float32 score tokens are ranked by: float32 of the squared norm.
+METRIC_L2NORM, METRIC_VARIANCE = 0, 1
 
-    Ranking by the squared norm equals ranking by the norm (sqrt is monotone);
-    the squared form is what both sides round to float32.
+
+def token_variances(X: np.ndarray) -> np.ndarray:
+    """Variance of each token's D feature values (selection-metric ablation,
+    Sec. 4.4 / Table 7), by the two-pass definition in float64.
+
+    The paper names the metric without a formula; the population form (divide
+    by D) is taken - the sample form differs by the constant D/(D-1) and ranks
+    tokens identically.
     """
+    X = np.asarray(X, dtype=np.float64)
+    if X.shape[1] == 0:
+        return np.zeros(X.shape[0])
+    mean = np.sum(X, axis=1, keepdims=True) / X.shape[1]
+    dev = X - mean
+    return np.sum(dev * dev, axis=1) / X.shape[1]
+
+
+def selection_scores(X: np.ndarray, metric: int = METRIC_L2NORM) -> np.ndarray:
+    """The float32 score tokens are ranked by.
+
+    l2 norm (Eq. 1): float32 of the squared norm - ranking by the squared norm
+    equals ranking by the norm (sqrt is monotone), and the squared form is what
+    both sides round to float32.  Variance: float32 of the variance.
+    """
+    if metric == METRIC_VARIANCE:
+        return token_variances(X).astype(np.float32)
+    if metric != METRIC_L2NORM:
+        raise ValueError("unknown selection metric")
     return token_sqnorms(X).astype(np.float32)
 
 
@@ -313,7 +338,7 @@ def prune_image(X: np.ndarray, density32: float, p: Params,
     """
     n = X.shape[0]
     q = token_sqnorms(X)
-    score = q.astype(np.float32)
+    score = selection_scores(X, p.metric)
     phi = 0.0
     if p.dynamic:
         phi = inter_token_similarity(X)

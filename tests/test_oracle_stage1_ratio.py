@@ -201,3 +201,61 @@ def test_widen_bf16_is_exact():
     bits = bits[(bits & 0x7F80) != 0x7F80]                     # skip inf / nan
     want = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
     np.testing.assert_array_equal(orc.widen(bits, "bf16"), want)
+
+
+# ------------------------------------------------- variance metric (Table 7 ablation)
+def test_variance_hand_values_and_library():
+    # (1, 2, 3, 4): mean 2.5, squared deviations 2.25 .25 .25 2.25 -> 5/4
+    assert orc.token_variances(np.array([[1.0, 2.0, 3.0, 4.0]]))[0] == 1.25
+    assert orc.token_variances(np.array([[7.0, 7.0, 7.0]]))[0] == 0.0
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((23, 77)) * 3 + 5
+    np.testing.assert_allclose(orc.token_variances(X), np.var(X, axis=1), rtol=1e-13)
+    # identity E[x^2] - E[x]^2, evaluated in exact rational arithmetic on small integers
+    from fractions import Fraction
+    Xi = rng.integers(-9, 10, size=(5, 12))
+    for row, v in zip(Xi, orc.token_variances(Xi.astype(np.float64))):
+        ex2 = Fraction(int((row * row).sum()), 12)
+        ex = Fraction(int(row.sum()), 12)
+        assert abs(v - float(ex2 - ex * ex)) < 1e-13
+
+
+def test_variance_shift_and_scale():
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((9, 64))
+    v = orc.token_variances(X)
+    np.testing.assert_allclose(orc.token_variances(X + 3.5), v, rtol=1e-12)      # a feature shift leaves it
+    np.testing.assert_allclose(orc.token_variances(-2.0 * X), 4.0 * v, rtol=1e-12)
+    # squared norm = D (variance + mean^2): the two metrics differ exactly by the mean term
+    np.testing.assert_allclose(orc.token_sqnorms(X), 64 * (v + X.mean(axis=1) ** 2), rtol=1e-12)
+
+
+def test_variance_misses_a_token_whose_norm_comes_from_a_feature_shift():
+    # what Sec. 4.4 says of the variance metric: a token that is large because all
+    # features moved together has a large norm and an ordinary variance
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((20, 256))
+    X[7] = 0.5 * X[7] + 4.0                     # norm ~ 64, variance ~ 0.25
+    l2_kept, _ = orc.select_topk(orc.selection_scores(X, orc.METRIC_L2NORM), 5)
+    var_kept, _ = orc.select_topk(orc.selection_scores(X, orc.METRIC_VARIANCE), 5)
+    assert 7 in l2_kept and 7 not in var_kept
+    assert int(np.argmin(orc.selection_scores(X, orc.METRIC_VARIANCE))) == 7
+    with pytest.raises(ValueError):
+        orc.selection_scores(X, 2)
+
+
+def test_metric_only_changes_the_selection_step():
+    rng = np.random.default_rng(14)
+    X = rng.standard_normal((30, 48)) + rng.standard_normal((30, 1))
+    p0 = orc.Params(iters=5, ratio=0.7)
+    p1 = orc.Params(iters=5, ratio=0.7, metric=orc.METRIC_VARIANCE)
+    a, b = orc.prune_image(X, 0.0, p0), orc.prune_image(X, 0.0, p1)
+    assert a.m == b.m == 21
+    exp_kept, _ = orc.select_topk(orc.token_variances(X).astype(np.float32), 21)
+    np.testing.assert_array_equal(b.kept, exp_kept)
+    assert not np.array_equal(a.kept, b.kept)
+    # stage 2 of the variance run is the l2 run's stage 2 on the other split: cosines
+    # still use the l2 norms
+    np.testing.assert_allclose(b.S, orc.cosine_scores(X, b.kept, b.prop), rtol=0, atol=0)
+    G = (X / np.linalg.norm(X, axis=1, keepdims=True))
+    np.testing.assert_allclose(b.S, (G @ G.T)[np.ix_(b.kept, b.prop)], atol=1e-14)
