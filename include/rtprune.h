@@ -70,6 +70,14 @@ enum {
                                  maximum, not a multiple of the patch size, or overruns its pixel span */
 };
 
+/* Importance score of stage 1.  The method uses the l2 norm (Eq. 1); the
+ * variance of a token's D feature values is the alternative the paper's
+ * selection-metric ablation measures (Sec. 4.4, Table 7), taken here in its
+ * population form sum_d (x_d - mean)^2 / D and accumulated in fp64 (mean first,
+ * then the squared deviations).  Stage 2 is the same for both: cosines always
+ * use the l2 norms. */
+typedef enum rtp_metric { RTP_METRIC_L2NORM = 0, RTP_METRIC_VARIANCE = 1 } rtp_metric;
+
 /* Hyper-parameters.  Defaults in the paper: z = 0.2, alpha = 0.1 (Algorithm 1,
  * input line), iters = 100 (Appendix C).  eps, the clamp and the form of
  * f_normalize are not given by the paper (see each field). */
@@ -85,6 +93,7 @@ typedef struct rtprune_params {
   float ratio_max;
   float phi_lo;    /* f_normalize(phi) = clamp((phi - phi_lo) / (phi_hi - phi_lo), 0, 1) */
   float phi_hi;    /* phi_hi > phi_lo */
+  int32_t metric;  /* rtp_metric: the importance score stage 1 ranks tokens by */
 } rtprune_params;
 
 /* One packed ragged batch of visual tokens. */
@@ -122,7 +131,8 @@ int rtprune_dynamic_ratio(const rtprune_batch* in, const float* density,
                           size_t workspace_bytes, void* stream);
 
 /* Stage 1, dominant-token selection (Sec. 3.3.1, Eq. 1).  Tokens are ranked by
- * the fp32 rounding of their exactly accumulated squared norm, larger first,
+ * the fp32 rounding of their exactly accumulated squared norm (or, with
+ * params->metric = RTP_METRIC_VARIANCE, of their variance), larger first,
  * lower index first among equals; the first M_b are kept.
  *   keep_counts_in  [B] int32 in, M_b per image (clamped to [min(1,N_b), N_b]);
  *                   NULL: M_b = ceil(params->ratio * N_b - 1e-3), same clamp

@@ -18,7 +18,7 @@ struct DevParams {
   double z, alpha, eps;
   double shift;      // max(1, z): exp((s - shift) / eps) <= 1 for every score s
   float ratio, ratio_min, ratio_max, phi_lo, phi_hi;
-  int iters, dynamic;
+  int iters, dynamic, metric;
 };
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) {

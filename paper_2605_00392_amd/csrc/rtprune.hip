@@ -81,6 +81,7 @@ int check_batch(const rtprune_batch* in) {
 int check_params(const rtprune_params* p, DevParams* d) {
   if (!p) return RTP_EINVAL;
   if (!(p->eps > 0.f) || p->iters < 0) return RTP_EINVAL;
+  if (p->metric != RTP_METRIC_L2NORM && p->metric != RTP_METRIC_VARIANCE) return RTP_EINVAL;
   if (!std::isfinite(p->z) || !std::isfinite(p->alpha) || !std::isfinite(p->eps)) return RTP_EINVAL;
   if (p->dynamic) {
     if (!(p->ratio_min > 0.f) || !(p->ratio_max <= 1.f) || !(p->ratio_min <= p->ratio_max)) return RTP_EINVAL;
@@ -102,6 +103,7 @@ int check_params(const rtprune_params* p, DevParams* d) {
   d->phi_hi = p->phi_hi;
   d->iters = p->iters;
   d->dynamic = p->dynamic ? 1 : 0;
+  d->metric = p->metric;
   return RTP_OK;
 }
 
@@ -163,8 +165,8 @@ int launch_prepare(const rtprune_batch* in, int32_t* status, hipStream_t s) {
 }
 
 template <typename T>
-int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* ws, float* norms_out,
-                   hipStream_t s) {
+int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layout& L, void* ws,
+                   float* norms_out, hipStream_t s) {
   const dim3 grid(L.chunks_per_image, in->B), block(kNormThreads);
   const T* tok = static_cast<const T*>(in->tokens);
   double* sq = at<double>(ws, L.norm64);
@@ -175,9 +177,15 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* 
   // groups of four elements per row; the lean variants need every k but the last
   // to be fully populated
   const int ngroups = in->D / 4;
-#define RTP_LAUNCH_NORMS(KMAX, KFULL)                                                                  \
-  hipLaunchKernelGGL((k_norms<T, KMAX, KFULL>), grid, block, 0, s, tok, in->offsets, in->D, dynamic, sq, \
-                     sc, norms_out, part, L.chunks_per_image, st)
+#define RTP_LAUNCH_NORMS(KMAX, KFULL)                                                                    \
+  do {                                                                                                   \
+    if (metric == RTP_METRIC_VARIANCE)                                                                   \
+      hipLaunchKernelGGL((k_norms<T, KMAX, KFULL, true>), grid, block, 0, s, tok, in->offsets, in->D,    \
+                         dynamic, sq, sc, norms_out, part, L.chunks_per_image, st);                      \
+    else                                                                                                 \
+      hipLaunchKernelGGL((k_norms<T, KMAX, KFULL, false>), grid, block, 0, s, tok, in->offsets, in->D,   \
+                         dynamic, sq, sc, norms_out, part, L.chunks_per_image, st);                      \
+  } while (0)
   if (in->D <= 1280) {
     if (ngroups >= 64 * 4) RTP_LAUNCH_NORMS(5, 4);
     else RTP_LAUNCH_NORMS(5, 0);
@@ -188,11 +196,11 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, const Layout& L, void* 
   return launched();
 }
 
-int launch_norms(const rtprune_batch* in, int dynamic, const Layout& L, void* ws, float* norms_out,
-                 hipStream_t s) {
+int launch_norms(const rtprune_batch* in, int dynamic, int metric, const Layout& L, void* ws,
+                 float* norms_out, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
-  return in->dtype == RTP_BF16 ? launch_norms_t<bf16_t>(in, dynamic, L, ws, norms_out, s)
-                               : launch_norms_t<float>(in, dynamic, L, ws, norms_out, s);
+  return in->dtype == RTP_BF16 ? launch_norms_t<bf16_t>(in, dynamic, metric, L, ws, norms_out, s)
+                               : launch_norms_t<float>(in, dynamic, metric, L, ws, norms_out, s);
 }
 
 int launch_select(const rtprune_batch* in, const DevParams& p, const float* density,
@@ -506,7 +514,7 @@ extern "C" int rtprune_dynamic_ratio(const rtprune_batch* in, const float* densi
   RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
-  RTP_TRY(launch_norms(in, 1, L, workspace, nullptr, s));
+  RTP_TRY(launch_norms(in, 1, p.metric, L, workspace, nullptr, s));
   return launch_select(in, p, density, nullptr, 0, L, workspace, phi, ratio, keep_counts, nullptr, s);
 }
 
@@ -528,7 +536,7 @@ extern "C" int rtprune_norms_topk(const rtprune_batch* in, const int32_t* keep_c
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* status = at<int32_t>(workspace, L.status);
   RTP_TRY(launch_prepare(in, status, s));
-  RTP_TRY(launch_norms(in, 0, L, workspace, norms, s));
+  RTP_TRY(launch_norms(in, 0, p.metric, L, workspace, norms, s));
   RTP_TRY(launch_select(in, p, nullptr, keep_counts_in, 1, L, workspace, nullptr, nullptr, keep_counts,
                         sel_idx, s));
   return launch_scan(in, keep_counts, out_offsets, reinterpret_cast<long long*>(plan_offsets), status, s);
@@ -547,7 +555,7 @@ extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
   hipStream_t s = static_cast<hipStream_t>(stream);
   RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
   // exact squared norms of every row (fp32 norms from stage 1 would cost 1e-7 on S)
-  RTP_TRY(launch_norms(in, 0, L, workspace, nullptr, s));
+  RTP_TRY(launch_norms(in, 0, RTP_METRIC_L2NORM, L, workspace, nullptr, s));
   // the kept counts live on the device: no host-side bound on the pruned sets
   return launch_ot(in, p, sel_idx, keep_counts, reinterpret_cast<const long long*>(plan_offsets), L,
                    workspace, scores, plan, pair, -1, s);
@@ -584,7 +592,7 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   long long* plan_off = at<long long>(workspace, L.plan_off);
   float* plan = at<float>(workspace, L.plan);
   RTP_TRY(launch_prepare(in, status, s));
-  RTP_TRY(launch_norms(in, p.dynamic, L, workspace, nullptr, s));
+  RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
   RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
   RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s));
   // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image

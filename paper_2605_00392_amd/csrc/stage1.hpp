@@ -48,7 +48,12 @@ __global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ off
 //
 // KFULL = number of k whose 64 groups all lie inside the row (their loads need
 // no guard); the remaining k read a clamped address and are zeroed by a select.
-template <typename T, int KMAX, int KFULL, int NB>
+//
+// VARIANCE: the selection score is the population variance of the row's D values
+// instead of its squared norm - the mean first (fp64), then the squared
+// deviations from it (fp64), as the definition reads; the norm is still formed
+// for the cosines of stage 2.
+template <typename T, int KMAX, int KFULL, int NB, bool VARIANCE>
 struct NormRows {
   typedef typename Raw4<T>::type raw_t;
   static constexpr int kStep = kNormThreads / kWave;   // row stride between a wave's rows
@@ -71,7 +76,7 @@ struct NormRows {
   // Norms and scores of the loaded rows (those below r1), and their unit vectors
   // into acc32 / wsum.
   static __device__ __forceinline__ void reduce(raw_t (&raw)[NB][KMAX], int lo, int rb, int r1, int ngroups,
-                                                int lane, int dynamic, double* __restrict__ norm64,
+                                                int D, int lane, int dynamic, double* __restrict__ norm64,
                                                 float* __restrict__ score, float* __restrict__ norms_out,
                                                 float (&acc32)[KMAX][4], double& wsum) {
 #pragma unroll
@@ -98,6 +103,42 @@ struct NormRows {
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) q[u] = wave_sum_dpp(q[u]);
+    double var[NB];
+    if (VARIANCE) {
+      double mean[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        double a = 0.0;
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+          float x[4];
+          unpack4(raw[u][k], x);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) a += static_cast<double>(x[e]);   // padding groups hold zeros
+        }
+        mean[u] = a;
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) mean[u] = wave_sum_dpp(mean[u]) / static_cast<double>(D);
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        double a = 0.0;
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+          float x[4];
+          unpack4(raw[u][k], x);
+          const bool inside = k < KFULL || lane + kWave * k < ngroups;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const double dev = static_cast<double>(x[e]) - mean[u];
+            a = inside ? fma(dev, dev, a) : a;
+          }
+        }
+        var[u] = a;
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) var[u] = wave_sum_dpp(var[u]) / static_cast<double>(D);
+    }
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int r = rb + kStep * u;
@@ -105,7 +146,7 @@ struct NormRows {
       const double nrm = sqrt(q[u]);
       if (lane == 0) {
         norm64[lo + r] = nrm;
-        score[lo + r] = static_cast<float>(q[u]);
+        score[lo + r] = static_cast<float>(VARIANCE ? var[u] : q[u]);
         if (norms_out) norms_out[lo + r] = static_cast<float>(nrm);
       }
       if (dynamic) {
@@ -125,7 +166,7 @@ struct NormRows {
   }
 };
 
-template <typename T, int KMAX, int KFULL>
+template <typename T, int KMAX, int KFULL, bool VARIANCE>
 __global__ __launch_bounds__(kNormThreads) void k_norms(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
     double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
@@ -157,7 +198,7 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
   // together (raw, still packed), their four squared norms go through the lane
   // butterfly interleaved, and only then are the unit vectors accumulated.
   constexpr int NB = KMAX <= 5 ? 4 : 1;
-  typedef NormRows<T, KMAX, KFULL, NB> Rows;
+  typedef NormRows<T, KMAX, KFULL, NB, VARIANCE> Rows;
   constexpr int kStride = Rows::kStep * NB;             // rows between a wave's successive groups
   constexpr int kGroups = kNormRowsPerChunk / kStride;  // groups per wave in a full chunk
   if (NB == 4 && kGroups >= 2 && r1 - r0 == kNormRowsPerChunk) {
@@ -170,14 +211,15 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
       if (i + 1 < kGroups)
         Rows::load((i & 1) ? bufa : bufb, tokens, lo, r0 + wave + kStride * (i + 1), r1 - 1, D, ngroups, lane);
       __builtin_amdgcn_sched_barrier(0);
-      Rows::reduce((i & 1) ? bufb : bufa, lo, r0 + wave + kStride * i, r1, ngroups, lane, dynamic, norm64, score,
+      Rows::reduce((i & 1) ? bufb : bufa, lo, r0 + wave + kStride * i, r1, ngroups, D, lane, dynamic, norm64,
+                   score,
                    norms_out, acc32, wsum);
     }
   } else {
     for (int rb = r0 + wave; rb < r1; rb += kStride) {
       typename Rows::raw_t raw[NB][KMAX];
       Rows::load(raw, tokens, lo, rb, r1 - 1, D, ngroups, lane);
-      Rows::reduce(raw, lo, rb, r1, ngroups, lane, dynamic, norm64, score, norms_out, acc32, wsum);
+      Rows::reduce(raw, lo, rb, r1, ngroups, D, lane, dynamic, norm64, score, norms_out, acc32, wsum);
     }
   }
   if (!dynamic) return;

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(HERE, "librtprune.so")
 
 RTP_OK, RTP_EINVAL, RTP_EUNSUPPORTED, RTP_EWORKSPACE, RTP_EHIP = range(5)
 RTP_F32, RTP_BF16 = 0, 1
+RTP_METRIC_L2NORM, RTP_METRIC_VARIANCE = 0, 1
 RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE = 1, 2, 4
 
 EXPORTS = (
@@ -38,6 +39,7 @@ class rtprune_params(ctypes.Structure):
         ("iters", ctypes.c_int32), ("dynamic", ctypes.c_int32),
         ("ratio", ctypes.c_float), ("ratio_min", ctypes.c_float), ("ratio_max", ctypes.c_float),
         ("phi_lo", ctypes.c_float), ("phi_hi", ctypes.c_float),
+        ("metric", ctypes.c_int32),
     ]
 
 
@@ -98,12 +100,13 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
 def make_params(d: Optional[Dict[str, float]] = None, **kw) -> rtprune_params:
     """Fill the C parameter struct from a dict / keywords (paper defaults otherwise)."""
     v = dict(z=0.2, alpha=0.1, eps=0.05, iters=100, dynamic=0, ratio=0.84,
-             ratio_min=0.6, ratio_max=1.0, phi_lo=0.0, phi_hi=1.0)
+             ratio_min=0.6, ratio_max=1.0, phi_lo=0.0, phi_hi=1.0, metric=RTP_METRIC_L2NORM)
     if d:
         v.update(d)
     v.update(kw)
     return rtprune_params(v["z"], v["alpha"], v["eps"], int(v["iters"]), int(v["dynamic"]),
-                          v["ratio"], v["ratio_min"], v["ratio_max"], v["phi_lo"], v["phi_hi"])
+                          v["ratio"], v["ratio_min"], v["ratio_max"], v["phi_lo"], v["phi_hi"],
+                          int(v["metric"]))
 
 
 def _addr(x) -> Optional[int]:

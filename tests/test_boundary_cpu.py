@@ -36,10 +36,30 @@ def test_library_exports_every_declared_symbol(lib):
         assert hasattr(lib, name), name
 
 
-def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(rt.rtprune_params) == 40
-    assert ctypes.sizeof(rt.rtprune_batch) == 40
-    assert rt.rtprune_batch.total_tokens.offset == 16 and rt.rtprune_batch.dtype.offset == 36
+def test_struct_layouts_match_the_header(tmp_path):
+    """Sizes and field offsets of the ctypes mirrors equal what a C compiler lays out from the header."""
+    import subprocess
+    fields = {"rtprune_params": [n for n, _ in rt.rtprune_params._fields_],
+              "rtprune_batch": [n for n, _ in rt.rtprune_batch._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rtprune.h"', 'int main(void) {']
+    for st, names in fields.items():
+        lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
+        for n in names:
+            lines.append(f'  printf("{st}.{n} %zu\\n", offsetof({st}, {n}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    for st, names in fields.items():
+        cls = getattr(rt, st)
+        assert int(got[st]) == ctypes.sizeof(cls), st
+        for n in names:
+            assert int(got[f"{st}.{n}"]) == getattr(cls, n).offset, (st, n)
+    assert ctypes.sizeof(rt.rtprune_params) == 44 and ctypes.sizeof(rt.rtprune_batch) == 40
 
 
 def test_status_strings(lib):
@@ -104,6 +124,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert call(b, rt.make_params(ratio=0.0)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(ratio=1.5)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(z=float("nan"))) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(metric=2)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(dynamic=1, ratio_min=0.0)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(dynamic=1, phi_lo=0.5, phi_hi=0.5)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(eps=0.001)) == rt.RTP_EUNSUPPORTED       # exp range

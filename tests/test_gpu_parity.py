@@ -151,6 +151,46 @@ def test_parameter_variants_c2_subset(override):
             np.testing.assert_array_equal(s["out"][o0:o0 + m], rows)
 
 
+# ------------------------------------------------ variance selection metric (Table 7)
+def _shifted_batch(dtype, seed, counts=(150, 64, 256, 1, 2), d=1152, **params):
+    """Tokens with per-token feature shifts of varying size, so that the l2 norm and
+    the variance rank them differently."""
+    rng = np.random.default_rng(seed)
+    imgs = []
+    for c in counts:
+        x = rng.standard_normal((c, d)) * rng.lognormal(0, 0.4, size=(c, 1))
+        x += rng.standard_normal((c, 1)) * rng.choice([0.0, 0.5, 3.0], size=(c, 1))
+        imgs.append(x.astype(np.float32))
+    dens = rng.uniform(0.1, 0.9, len(counts)).astype(np.float32)
+    p = dict(synth.DEFAULT_PARAMS, iters=20, metric=1)
+    p.update(params)
+    return synth.pack(0, dtype, imgs, dens, p)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 1152), ("f32", 1152), ("bf16", 72), ("f32", 2048)])
+def test_variance_metric_matches_the_oracle(dtype, d):
+    batch = _shifted_batch(dtype, 77, d=d, ratio=0.7)
+    s = hz.run_staged(batch, batch.params)
+    rep = hz.compare_batch(batch, s, batch.params, staged=True)
+    _log(rep, f"variance {dtype} D={d}")
+    f = hz.run_prune(batch)
+    for k in ("out_offsets", "keep", "sel", "pair"):
+        np.testing.assert_array_equal(f[k], s[k])
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    # the metric does change what is kept on this input
+    l2 = hz.run_staged(batch, dict(batch.params, metric=0))
+    assert not np.array_equal(l2["sel"], s["sel"])
+
+
+def test_variance_metric_with_dynamic_ratio_on_clustered_pages():
+    batch = synth.gen_batch(3, images=range(6))
+    params = dict(batch.params, metric=1)
+    f = hz.run_prune(batch, params)
+    rep = hz.compare_batch(batch, f, params, staged=False)
+    _log(rep, "c3 variance metric")
+
+
 # ------------------------------------------------------------------------ edge cases
 def _random_batch(counts, d, dtype, seed, dynamic=0, **params):
     rng = np.random.default_rng(seed)
