@@ -187,7 +187,8 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layou
                          dynamic, sq, sc, norms_out, part, L.chunks_per_image, st);                      \
   } while (0)
   if (in->D <= 1280) {
-    if (ngroups >= 64 * 4) RTP_LAUNCH_NORMS(5, 4);
+    if (ngroups == 64 * 5) RTP_LAUNCH_NORMS(5, 5);
+    else if (ngroups >= 64 * 4) RTP_LAUNCH_NORMS(5, 4);
     else RTP_LAUNCH_NORMS(5, 0);
   } else {
     RTP_LAUNCH_NORMS(16, 0);
