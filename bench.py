@@ -135,7 +135,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..5 (5 = 1024 x 400 tokens)")
+    ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..8 (5 = 1024 x 400 tokens, the default; 6-8 = 1083/2137/4512-token pages)")
     ap.add_argument("--cpu-images", type=int, default=192, help="images the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lib", default=None, help="path of an alternative build of librtprune.so")

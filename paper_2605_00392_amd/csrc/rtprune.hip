@@ -18,6 +18,7 @@
 #include "stage2_ref.hpp"
 #include "sinkhorn_team.hpp"
 #include "sinkhorn_dual.hpp"
+#include "sinkhorn_sweep.hpp"
 #include "scores_mfma.hpp"
 #include "merge_lds.hpp"
 #include "density.hpp"
@@ -32,8 +33,11 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 // Byte offsets of the workspace regions for a batch shape.
 struct Layout {
   size_t status, norm64, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
+  size_t sw_x, sw_y, sw_colpart, sw_xpart, sw_ysum, sw_ydust, sw_bestv, sw_besti;   // sweep Sinkhorn state
   int chunks_per_image;
+  int sweep;            // the batch may hold images beyond the register-resident Sinkhorn shapes
   long long plan_cap;   // entries available in kmat / plan
+  long long strip_cap;  // entries available in the per-strip arrays
 };
 
 Layout make_layout(int B, long long total, int max_tokens, int D) {
@@ -57,6 +61,21 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   L.work = take(sizeof(int32_t) * kWorkLists * (1 + static_cast<size_t>(B)));
   L.kmat = take(sizeof(double) * L.plan_cap);
   L.plan = take(sizeof(float) * L.plan_cap);
+  // more than 512 tokens: an image can have more kept tokens than any register shape holds
+  L.sweep = max_tokens > 512 ? 1 : 0;
+  L.strip_cap = L.plan_cap / kSweepRows + total + 1;
+  if (L.sweep) {
+    L.sw_x = take(sizeof(double) * total);
+    L.sw_y = take(sizeof(double) * total);
+    L.sw_colpart = take(sizeof(double) * L.strip_cap);
+    L.sw_xpart = take(sizeof(double) * total);
+    L.sw_ysum = take(sizeof(double) * 2 * total);
+    L.sw_ydust = take(sizeof(double) * 2 * B);
+    L.sw_bestv = take(sizeof(float) * L.strip_cap);
+    L.sw_besti = take(sizeof(int32_t) * L.strip_cap);
+  } else {
+    L.sw_x = L.sw_y = L.sw_colpart = L.sw_xpart = L.sw_ysum = L.sw_ydust = L.sw_bestv = L.sw_besti = 0;
+  }
   L.total = at;
   return L;
 }
@@ -277,7 +296,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
   int32_t* work = at<int32_t>(ws, L.work);
   {
     ProfScope prof(KID_CLASSIFY, s);
-    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, st);
+    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, L.sweep, st);
   }
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
@@ -287,7 +306,26 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
   RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);
   hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
-                     L.plan_cap, plan, pair, 1, st);
+                     L.plan_cap, plan, pair, 1, L.sweep, st);
+  RTP_TRY(launched());
+  if (L.sweep) {
+    // large images: two launches per iteration over all of them, then plan and pairing
+    SweepArgs A{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
+                at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<double>(ws, L.sw_colpart),
+                at<double>(ws, L.sw_xpart), at<double>(ws, L.sw_ysum), at<double>(ws, L.sw_ydust),
+                at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair};
+    const int strips = (in->max_tokens + kSweepRows - 1) / kSweepRows;
+    const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepColBlock - 1) / kSweepColBlock;
+    const dim3 grows(strips, in->B), gcols(cols, in->B);
+    hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColBlock), 0, s, A, st);
+    for (int it = 0; it < p.iters; ++it) {
+      hipLaunchKernelGGL((k_sweep_rows<false>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
+      hipLaunchKernelGGL((k_sweep_cols<false>), gcols, dim3(kSweepColBlock), 0, s, A, it & 1, 0, st);
+    }
+    hipLaunchKernelGGL((k_sweep_rows<true>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
+    hipLaunchKernelGGL((k_sweep_cols<true>), gcols, dim3(kSweepColBlock), 0, s, A,
+                       p.iters > 0 ? (p.iters - 1) & 1 : 0, p.iters == 0 ? 1 : 0, st);
+  }
   return launched();
 }
 

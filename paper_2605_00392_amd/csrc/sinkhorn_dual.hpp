@@ -296,7 +296,7 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
 // indices each.  One workgroup; list order follows image order.
 __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
                                                   const int32_t* __restrict__ keep, int B,
-                                                  int32_t* __restrict__ work,
+                                                  int32_t* __restrict__ work, int sweep,
                                                   const int32_t* __restrict__ status) {
   if (status[0]) return;
   constexpr int NV = kWorkLists;
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
-    const int v = sinkhorn_variant(m, n - m);
+    const int v = sinkhorn_variant(m, n - m, sweep);
     if (n > 0 && v < kGeneralVariant) {
 #pragma unroll
       for (int u = 0; u < NV; ++u) c[u] += (u == v);
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
-    const int v = sinkhorn_variant(m, n - m);
+    const int v = sinkhorn_variant(m, n - m, sweep);
     if (n > 0 && v < kGeneralVariant) {
 #pragma unroll
       for (int u = 0; u < NV; ++u)

@@ -62,18 +62,23 @@ constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 // or R + 1 <= 48.
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
-              kVariantPair = 5, kGeneralVariant = 6;
-constexpr int kWorkLists = 6;
+              kVariantPair = 5, kVariantSweep = 6, kGeneralVariant = 7;
+constexpr int kWorkLists = 7;
+// The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take what no register
+// shape fits, up to this many pruned tokens; they are only launched for batches
+// that can hold such images (`sweep`).
+constexpr int kSweepMaxPruned = 2048;
 
 // Which Sinkhorn kernel serves an image; every kernel evaluates this and takes
 // only its own images, so each image is processed exactly once.
-__host__ __device__ inline int sinkhorn_variant(int m, int r) {
+__host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
   if (WaveShape::fits(m, r)) return kVariantA;
   if (PairShape::fits(m, r)) return kVariantPair;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if (TeamC::fits(m, r)) return kVariantC;
+  if (sweep && r <= kSweepMaxPruned) return kVariantSweep;
   return kGeneralVariant;
 }
 

@@ -125,6 +125,20 @@ def test_c5_full_batch_sampled_against_oracle():
     np.testing.assert_array_equal(f["pair"], g["pair"])
 
 
+# ------------------------------------------- other OCR models' token counts (Table 6)
+@pytest.mark.parametrize("cfg,images,kept", [(6, 3, 560), (7, 2, 1238), (8, 1, 2783)])
+def test_large_pages(cfg, images, kept):
+    batch = synth.gen_batch(cfg, images=range(images))
+    f = hz.run_prune(batch)
+    assert (f["keep"] == kept).all()
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"c{cfg} {images} image(s)")
+    s = hz.run_staged(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+
+
 # ------------------------------------------------------------------ parameter sweeps
 @pytest.mark.parametrize("override", [
     dict(eps=1.0, iters=100),           # the literal text of Appendix C
