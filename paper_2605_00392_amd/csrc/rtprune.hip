@@ -123,6 +123,8 @@ int check_params(const rtprune_params* p, DevParams* d) {
   d->iters = p->iters;
   d->dynamic = p->dynamic ? 1 : 0;
   d->metric = p->metric;
+  d->sweep = 0;                                  // set per batch by launch_ot
+  d->k32 = (hi - lo) / eps <= 80.0 ? 1 : 0;      // exp(-80) is a normal fp32 number
   return RTP_OK;
 }
 
@@ -284,10 +286,13 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
   return launched();
 }
 
-int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
+int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel, const int32_t* keep,
               const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
               int32_t* pair, int max_pruned_hint, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
+  DevParams p = p_in;
+  p.sweep = L.sweep;
+  p.k32 = p.k32 && L.sweep;
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
@@ -315,15 +320,17 @@ int launch_ot(const rtprune_batch* in, const DevParams& p, const int32_t* sel, c
                 at<double>(ws, L.sw_xpart), at<double>(ws, L.sw_ysum), at<double>(ws, L.sw_ydust),
                 at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair};
     const int strips = (in->max_tokens + kSweepRows - 1) / kSweepRows;
-    const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepColBlock - 1) / kSweepColBlock;
+    const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepCols - 1) / kSweepCols;
     const dim3 grows(strips, in->B), gcols(cols, in->B);
-    hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColBlock), 0, s, A, st);
+    hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColThreads), 0, s, A, st);
     for (int it = 0; it < p.iters; ++it) {
-      hipLaunchKernelGGL((k_sweep_rows<false>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
-      hipLaunchKernelGGL((k_sweep_cols<false>), gcols, dim3(kSweepColBlock), 0, s, A, it & 1, 0, st);
+      if (p.k32) hipLaunchKernelGGL((k_sweep_rows<false, float>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
+      else hipLaunchKernelGGL((k_sweep_rows<false, double>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
+      hipLaunchKernelGGL((k_sweep_cols<false>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
     }
-    hipLaunchKernelGGL((k_sweep_rows<true>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
-    hipLaunchKernelGGL((k_sweep_cols<true>), gcols, dim3(kSweepColBlock), 0, s, A,
+    if (p.k32) hipLaunchKernelGGL((k_sweep_rows<true, float>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
+    else hipLaunchKernelGGL((k_sweep_rows<true, double>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
+    hipLaunchKernelGGL((k_sweep_cols<true>), gcols, dim3(kSweepColThreads), 0, s, A,
                        p.iters > 0 ? (p.iters - 1) & 1 : 0, p.iters == 0 ? 1 : 0, st);
   }
   return launched();

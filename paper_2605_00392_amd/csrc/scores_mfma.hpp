@@ -19,6 +19,7 @@
 // operands use the same assignment, which they do by construction.
 #pragma once
 #include "common.hpp"
+#include "sinkhorn_team.hpp"
 
 namespace rtp {
 
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
   if (r <= 0 || i0 >= m) return;
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
+  const bool k_f32 = kernel_is_f32(p, m, r);
   const int32_t* sel = sel_idx + lo;
   const int frow = lane & 15, fk = (lane >> 4) * 16;   // 16 elements = 32 bytes per lane and step
   const double inv_eps = 1.0 / p.eps;
@@ -153,9 +155,9 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
           if (i < m) {
             const double ni = norm64[lo + clamp_index(sel[i], n)];
             const double s = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
-            const long long at = po + static_cast<long long>(i) * r + j;
-            kmat[at] = exp((s - p.shift) * inv_eps);
-            if (scores_out) scores_out[at] = s;
+            const long long at = static_cast<long long>(i) * r + j;
+            store_kernel(kmat, po, at, exp((s - p.shift) * inv_eps), k_f32);
+            if (scores_out) scores_out[po + at] = s;
           }
         }
     }

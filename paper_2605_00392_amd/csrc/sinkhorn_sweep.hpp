@@ -29,7 +29,9 @@ constexpr int kSweepThreads = 512;
 constexpr int kSweepChunks = 4;         // columns per thread
 constexpr int kSweepMaxR = kSweepThreads * kSweepChunks;
 static_assert(kSweepMaxR == kSweepMaxPruned, "shape limit");
-constexpr int kSweepColBlock = 256;     // columns per workgroup of k_sweep_cols
+constexpr int kSweepCols = 64;          // columns per workgroup of k_sweep_cols
+constexpr int kSweepColGroups = 4;      // waves of that workgroup, each with a share of the strips
+constexpr int kSweepColThreads = 64 * kSweepColGroups;
 
 struct SweepArgs {
   const int32_t* offsets;
@@ -74,20 +76,20 @@ __device__ __forceinline__ bool sweep_image(const SweepArgs& A, int idx, SweepIm
 }
 
 // u = v = 0: x = exp(shift/eps) (so that x K y = exp(S/eps)), y = 1.
-__global__ __launch_bounds__(kSweepColBlock) void k_sweep_init(SweepArgs A, const int32_t* __restrict__ status) {
+__global__ __launch_bounds__(kSweepColThreads) void k_sweep_init(SweepArgs A, const int32_t* __restrict__ status) {
   if (status[0]) return;
   SweepImage I;
   if (!sweep_image(A, blockIdx.y, I)) return;
   const int tid = threadIdx.x;
   const double x_init = exp(A.p.shift / A.p.eps);
-  for (int i = blockIdx.x * kSweepColBlock + tid; i < I.m; i += gridDim.x * kSweepColBlock) {
+  for (int i = blockIdx.x * kSweepColThreads + tid; i < I.m; i += gridDim.x * kSweepColThreads) {
     A.x[I.lo + i] = x_init;
     if (A.pair_out) A.pair_out[I.lo + i] = i;
   }
-  const int j0 = blockIdx.x * kSweepColBlock;
+  const int j0 = blockIdx.x * kSweepCols;
   if (j0 < I.r) {
-    if (j0 + tid < I.r) A.y[I.lo + j0 + tid] = 1.0;
-    if (tid == 0) A.ysum[I.lo + blockIdx.x] = static_cast<double>(min(kSweepColBlock, I.r - j0));
+    if (tid < kSweepCols && j0 + tid < I.r) A.y[I.lo + j0 + tid] = 1.0;
+    if (tid == 0) A.ysum[I.lo + blockIdx.x] = static_cast<double>(min(kSweepCols, I.r - j0));
   }
   if (blockIdx.x == 0 && tid == 0) A.ydust[I.b] = 1.0;
 }
@@ -95,7 +97,8 @@ __global__ __launch_bounds__(kSweepColBlock) void k_sweep_init(SweepArgs A, cons
 // FINAL = false: one u-update and the strips' column shares.  `parity` is that
 // of the values to read (the previous iteration's).
 // FINAL = true: plan entries of the strip and, per column, its largest entry.
-template <bool FINAL>
+// KT: storage type of the kernel matrix (float when A.p.k32).
+template <bool FINAL, typename KT>
 __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int parity,
                                                              const int32_t* __restrict__ status) {
   if (status[0]) return;
@@ -105,17 +108,28 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
   if (i0 >= I.m) return;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m = I.m, r = I.r;
-  const double* __restrict__ Kg = A.kmat + I.po;
+  const KT* __restrict__ Kg = reinterpret_cast<const KT*>(A.kmat + I.po);
   const double kz = exp((A.p.z - A.p.shift) / A.p.eps);
 
-  double K[kSweepRows][kSweepChunks], yv[kSweepChunks];
+  // The strip stays in registers in its storage type.  Every load is issued
+  // unconditionally from a clamped address (all of them in flight at once) and
+  // out-of-range entries are zeroed afterwards.
+  KT K[kSweepRows][kSweepChunks];
+  double yv[kSweepChunks];
+#pragma unroll
+  for (int c = 0; c < kSweepChunks; ++c) {
+    const int j = min(tid + kSweepThreads * c, r - 1);
+#pragma unroll
+    for (int a = 0; a < kSweepRows; ++a)
+      K[a][c] = Kg[static_cast<long long>(min(i0 + a, m - 1)) * r + j];
+  }
 #pragma unroll
   for (int c = 0; c < kSweepChunks; ++c) {
     const int j = tid + kSweepThreads * c;
     yv[c] = j < r ? A.y[I.lo + j] : 0.0;
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a)
-      K[a][c] = (i0 + a < m && j < r) ? Kg[static_cast<long long>(i0 + a) * r + j] : 0.0;
+      if (!(i0 + a < m && j < r)) K[a][c] = KT(0);
   }
   __shared__ double red[kSweepThreads / 64][kSweepRows];
   __shared__ double xs[kSweepRows];
@@ -125,7 +139,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
     for (int a = 0; a < kSweepRows; ++a) {
       double acc = 0.0;
 #pragma unroll
-      for (int c = 0; c < kSweepChunks; ++c) acc = fma(K[a][c], yv[c], acc);
+      for (int c = 0; c < kSweepChunks; ++c) acc = fma(static_cast<double>(K[a][c]), yv[c], acc);
       s[a] = acc;
     }
     const double mine = reduce_scatter<kSweepRows>(s, lane);     // row wave_column(lane) of this wave
@@ -155,7 +169,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
       const int j = tid + kSweepThreads * c;
       double acc = 0.0;
 #pragma unroll
-      for (int a = 0; a < kSweepRows; ++a) acc = fma(K[a][c], xa[a], acc);
+      for (int a = 0; a < kSweepRows; ++a) acc = fma(static_cast<double>(K[a][c]), xa[a], acc);
       if (j < r) out[j] = acc;
     }
   } else {
@@ -171,7 +185,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a) {
         if (i0 + a < m && j < r) {
-          const float v = static_cast<float>(xs[a] * K[a][c] * yv[c]);
+          const float v = static_cast<float>(xs[a] * static_cast<double>(K[a][c]) * yv[c]);
           if (P) P[static_cast<long long>(i0 + a) * r + j] = v;
           if (v > bv) { bv = v; bi = i0 + a; }
         }
@@ -181,23 +195,27 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
   }
 }
 
+// Workgroup = 64 columns x 4 waves; wave g takes the strips s = g, g + 4, ...
 // FINAL = false: the v-update from the strips' shares; reads scalars of
 // `parity`, writes those of parity ^ 1.
 // FINAL = true: the pairing - largest plan entry of each column over all strips
 // (the lowest row wins ties) against the dustbin row's entry.
 template <bool FINAL>
-__global__ __launch_bounds__(kSweepColBlock) void k_sweep_cols(SweepArgs A, int parity, int first,
-                                                              const int32_t* __restrict__ status) {
+__global__ __launch_bounds__(kSweepColThreads) void k_sweep_cols(SweepArgs A, int parity, int first,
+                                                                const int32_t* __restrict__ status) {
   if (status[0]) return;
   SweepImage I;
   if (!sweep_image(A, blockIdx.y, I)) return;
-  const int j0 = blockIdx.x * kSweepColBlock;
+  const int j0 = blockIdx.x * kSweepCols;
   if (j0 >= I.r) return;
-  const int tid = threadIdx.x, j = j0 + tid;
+  const int tid = threadIdx.x, lane = tid & 63, g = tid >> 6, j = j0 + lane;
   const int m = I.m, r = I.r;
-  const int nstrips = (m + kSweepRows - 1) / kSweepRows, nblocks = (r + kSweepColBlock - 1) / kSweepColBlock;
+  const int nstrips = (m + kSweepRows - 1) / kSweepRows, nblocks = (r + kSweepCols - 1) / kSweepCols;
   const double kz = exp((A.p.z - A.p.shift) / A.p.eps);
-  __shared__ double red[kSweepColBlock / 64];
+  __shared__ double red[kSweepColThreads / 64];
+  __shared__ double part[kSweepColGroups][kSweepCols];
+  __shared__ float pv[kSweepColGroups][kSweepCols];
+  __shared__ int pi[kSweepColGroups][kSweepCols];
   // x_d of the iteration just swept: from the previous iteration's sy and y_d
   double x_dust;
   if (first) {
@@ -210,37 +228,56 @@ __global__ __launch_bounds__(kSweepColBlock) void k_sweep_cols(SweepArgs A, int 
   const long long sb = strip_base(I.po, I.lo);
   if (!FINAL) {
     double sx = 0.0;
-    for (int s = tid; s < nstrips; s += kSweepColBlock) sx += A.xpart[I.lo + s];
-    sx = block_sum<kSweepColBlock>(sx, red);
-    double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+    for (int s = tid; s < nstrips; s += kSweepColThreads) sx += A.xpart[I.lo + s];
+    sx = block_sum<kSweepColThreads>(sx, red);
+    double t0 = 0.0, t1 = 0.0;
     if (j < r) {
       const double* cp = A.colpart + sb + j;
-      int s = 0;
-      for (; s + 4 <= nstrips; s += 4) {
+      int s = g;
+      for (; s + kSweepColGroups < nstrips; s += 2 * kSweepColGroups) {
         t0 += cp[static_cast<long long>(s) * r];
-        t1 += cp[static_cast<long long>(s + 1) * r];
-        t2 += cp[static_cast<long long>(s + 2) * r];
-        t3 += cp[static_cast<long long>(s + 3) * r];
+        t1 += cp[static_cast<long long>(s + kSweepColGroups) * r];
       }
-      for (; s < nstrips; ++s) t0 += cp[static_cast<long long>(s) * r];
+      if (s < nstrips) t0 += cp[static_cast<long long>(s) * r];
     }
-    const double yj = j < r ? rcp64((t0 + t1) + (t2 + t3) + kz * x_dust) : 0.0;
-    if (j < r) A.y[I.lo + j] = yj;
-    const double ys = block_sum<kSweepColBlock>(yj, red);
+    part[g][lane] = t0 + t1;
+    __syncthreads();
+    double yj = 0.0;
+    if (g == 0 && j < r) {
+      double t = part[0][lane];
+#pragma unroll
+      for (int k = 1; k < kSweepColGroups; ++k) t += part[k][lane];
+      yj = rcp64(t + kz * x_dust);
+      A.y[I.lo + j] = yj;
+    }
+    const double ys = block_sum<kSweepColThreads>(yj, red);
     if (tid == 0) {
       A.ysum[(parity ^ 1) * A.total + I.lo + blockIdx.x] = ys;
       if (blockIdx.x == 0) A.ydust[(parity ^ 1) * A.B + I.b] = static_cast<double>(m) * rcp64(kz * (sx + x_dust));
     }
   } else {
-    if (j >= r || !A.pair_out) return;
+    if (!A.pair_out) return;
     float bv = -1.f;
     int bi = 0x7fffffff;
-    for (int s = 0; s < nstrips; ++s) {
-      const float v = A.bestv[sb + static_cast<long long>(s) * r + j];
-      if (v > bv) { bv = v; bi = A.besti[sb + static_cast<long long>(s) * r + j]; }
+    if (j < r) {
+      for (int s = g; s < nstrips; s += kSweepColGroups) {
+        const float v = A.bestv[sb + static_cast<long long>(s) * r + j];
+        if (v > bv) { bv = v; bi = A.besti[sb + static_cast<long long>(s) * r + j]; }
+      }
     }
-    const float dust = static_cast<float>(x_dust * kz * A.y[I.lo + j]);
-    A.pair_out[I.lo + m + j] = dust > bv ? -1 : bi;
+    pv[g][lane] = bv;
+    pi[g][lane] = bi;
+    __syncthreads();
+    if (g == 0 && j < r) {
+#pragma unroll
+      for (int k = 1; k < kSweepColGroups; ++k) {
+        const float ov = pv[k][lane];
+        const int oi = pi[k][lane];
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      const float dust = static_cast<float>(x_dust * kz * A.y[I.lo + j]);
+      A.pair_out[I.lo + m + j] = dust > bv ? -1 : bi;
+    }
   }
 }
 

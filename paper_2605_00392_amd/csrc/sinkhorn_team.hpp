@@ -82,6 +82,20 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
   return kGeneralVariant;
 }
 
+// The kernel matrix of an image the sweep kernels take is stored in fp32 when
+// its range allows (p.k32): a relative rounding of 6e-8 on K = exp((S - shift)/eps)
+// is an absolute perturbation of eps * 6e-8 on the score S, below the scores' own
+// error, and it halves the bytes every iteration streams.  The fp32 entries of
+// image b occupy the start of its fp64 slot.
+__device__ __forceinline__ bool kernel_is_f32(const DevParams& p, int m, int r) {
+  return p.k32 && sinkhorn_variant(m, r, p.sweep) == kVariantSweep;
+}
+__device__ __forceinline__ void store_kernel(double* __restrict__ kmat, long long po, long long idx, double v,
+                                             bool as_f32) {
+  if (as_f32) reinterpret_cast<float*>(kmat + po)[idx] = static_cast<float>(v);
+  else kmat[po + idx] = v;
+}
+
 // What every register-resident Sinkhorn body needs.
 struct SinkhornArgs {
   const int32_t* offsets;

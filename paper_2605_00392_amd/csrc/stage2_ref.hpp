@@ -38,6 +38,7 @@ __global__ __launch_bounds__(256) void k_scores(
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ngroups = D >> 2;
   const long long po = plan_offsets[b];
+  const bool k_f32 = kernel_is_f32(p, m, r);
   const int32_t* sel = sel_idx + lo;
   const double inv_eps = 1.0 / p.eps;
 
@@ -71,9 +72,9 @@ __global__ __launch_bounds__(256) void k_scores(
       if (lane == 0) {
         const double nj = norm64[lo + tj];
         const double s = dot / fmax(ni * nj, kTinyNorm * kTinyNorm);
-        const long long at = po + static_cast<long long>(i) * r + j;
-        kmat[at] = exp((s - p.shift) * inv_eps);
-        if (scores_out) scores_out[at] = s;
+        const long long at = static_cast<long long>(i) * r + j;
+        store_kernel(kmat, po, at, exp((s - p.shift) * inv_eps), k_f32);
+        if (scores_out) scores_out[po + at] = s;
       }
     }
   }
