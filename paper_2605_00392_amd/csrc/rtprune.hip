@@ -323,13 +323,31 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepCols - 1) / kSweepCols;
     const dim3 grows(strips, in->B), gcols(cols, in->B);
     hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColThreads), 0, s, A, st);
+    // columns per thread: enough for the largest pruned set the batch can hold
+    const int rmax = std::min(max_pruned_hint >= 0 ? max_pruned_hint : in->max_tokens - 1, kSweepMaxR);
+    const int ch = (std::max(rmax, 1) + kSweepThreads - 1) / kSweepThreads;
+    auto rows = [&](auto final_tag, int parity) {
+      constexpr bool kFinal = decltype(final_tag)::value;
+#define RTP_SWEEP_ROWS(KT, CH) \
+  hipLaunchKernelGGL((k_sweep_rows<kFinal, KT, CH>), grows, dim3(kSweepThreads), 0, s, A, parity, st)
+      if (p.k32) {
+        if (ch <= 1) RTP_SWEEP_ROWS(float, 1);
+        else if (ch == 2) RTP_SWEEP_ROWS(float, 2);
+        else if (ch == 3) RTP_SWEEP_ROWS(float, 3);
+        else RTP_SWEEP_ROWS(float, 4);
+      } else {
+        if (ch <= 1) RTP_SWEEP_ROWS(double, 1);
+        else if (ch == 2) RTP_SWEEP_ROWS(double, 2);
+        else if (ch == 3) RTP_SWEEP_ROWS(double, 3);
+        else RTP_SWEEP_ROWS(double, 4);
+      }
+#undef RTP_SWEEP_ROWS
+    };
     for (int it = 0; it < p.iters; ++it) {
-      if (p.k32) hipLaunchKernelGGL((k_sweep_rows<false, float>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
-      else hipLaunchKernelGGL((k_sweep_rows<false, double>), grows, dim3(kSweepThreads), 0, s, A, it & 1, st);
+      rows(std::false_type{}, it & 1);
       hipLaunchKernelGGL((k_sweep_cols<false>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
     }
-    if (p.k32) hipLaunchKernelGGL((k_sweep_rows<true, float>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
-    else hipLaunchKernelGGL((k_sweep_rows<true, double>), grows, dim3(kSweepThreads), 0, s, A, 0, st);
+    rows(std::true_type{}, 0);
     hipLaunchKernelGGL((k_sweep_cols<true>), gcols, dim3(kSweepColThreads), 0, s, A,
                        p.iters > 0 ? (p.iters - 1) & 1 : 0, p.iters == 0 ? 1 : 0, st);
   }

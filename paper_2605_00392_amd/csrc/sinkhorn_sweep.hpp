@@ -96,96 +96,111 @@ __global__ __launch_bounds__(kSweepColThreads) void k_sweep_init(SweepArgs A, co
 
 // FINAL = false: one u-update and the strips' column shares.  `parity` is that
 // of the values to read (the previous iteration's).
-// FINAL = true: plan entries of the strip and, per column, its largest entry.
+// FINAL = true: plan entries of the strips and, per column, their largest entry.
+//
+// The 512 threads form RG row groups of CG column threads (CG RG = 512); a row
+// group owns one 16-row strip, its thread ct holds columns ct, ct + CG, ... (CH
+// of them).  Narrow images put four strips into a workgroup (CG = 128), wide
+// ones a single strip (CG = 512, up to 2048 columns).
 // KT: storage type of the kernel matrix (float when A.p.k32).
-template <bool FINAL, typename KT>
-__global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int parity,
-                                                             const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  SweepImage I;
-  if (!sweep_image(A, blockIdx.y, I)) return;
-  const int i0 = blockIdx.x * kSweepRows;
-  if (i0 >= I.m) return;
+template <bool FINAL, typename KT, int CG, int RG, int CH>
+__device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepImage& I, int parity) {
+  static_assert(CG * RG == kSweepThreads && CG % 64 == 0, "workgroup shape");
+  constexpr int kGroupWaves = CG / 64;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int rg = tid / CG, ct = tid - rg * CG;
   const int m = I.m, r = I.r;
+  const int nstrips = (m + kSweepRows - 1) / kSweepRows;
+  if (static_cast<int>(blockIdx.x) * RG >= nstrips) return;
+  const int strip = blockIdx.x * RG + rg;              // may be past the last strip: then all rows are masked
+  const int i0 = strip * kSweepRows;
   const KT* __restrict__ Kg = reinterpret_cast<const KT*>(A.kmat + I.po);
   const double kz = exp((A.p.z - A.p.shift) / A.p.eps);
+  const double y_dust = FINAL ? 0.0 : A.ydust[parity * A.B + I.b];   // early: not on the critical path
 
   // The strip stays in registers in its storage type.  Every load is issued
   // unconditionally from a clamped address (all of them in flight at once) and
   // out-of-range entries are zeroed afterwards.
-  KT K[kSweepRows][kSweepChunks];
-  double yv[kSweepChunks];
+  KT K[kSweepRows][CH];
+  double yv[CH];
 #pragma unroll
-  for (int c = 0; c < kSweepChunks; ++c) {
-    const int j = min(tid + kSweepThreads * c, r - 1);
+  for (int c = 0; c < CH; ++c) {
+    const int j = min(ct + CG * c, r - 1);
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a)
       K[a][c] = Kg[static_cast<long long>(min(i0 + a, m - 1)) * r + j];
   }
 #pragma unroll
-  for (int c = 0; c < kSweepChunks; ++c) {
-    const int j = tid + kSweepThreads * c;
+  for (int c = 0; c < CH; ++c) {
+    const int j = ct + CG * c;
     yv[c] = j < r ? A.y[I.lo + j] : 0.0;
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a)
       if (!(i0 + a < m && j < r)) K[a][c] = KT(0);
   }
   __shared__ double red[kSweepThreads / 64][kSweepRows];
-  __shared__ double xs[kSweepRows];
+  __shared__ double xs[RG][kSweepRows];
   if (!FINAL) {
     double s[kSweepRows];
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a) {
       double acc = 0.0;
 #pragma unroll
-      for (int c = 0; c < kSweepChunks; ++c) acc = fma(static_cast<double>(K[a][c]), yv[c], acc);
+      for (int c = 0; c < CH; ++c) acc = fma(static_cast<double>(K[a][c]), yv[c], acc);
       s[a] = acc;
     }
     const double mine = reduce_scatter<kSweepRows>(s, lane);     // row wave_column(lane) of this wave
     if ((lane & 3) == 0) red[wave][wave_column<kSweepRows>(lane)] = mine;
     __syncthreads();
-    if (tid < kSweepRows) {
+    if (tid < kSweepRows * RG) {
+      const int g = tid / kSweepRows, a = tid - g * kSweepRows;
+      const int i = (blockIdx.x * RG + g) * kSweepRows + a;
       double t = 0.0;
 #pragma unroll
-      for (int w = 0; w < kSweepThreads / 64; ++w) t += red[w][tid];
-      const double xa = (i0 + tid < m) ? rcp64(t + kz * A.ydust[parity * A.B + I.b]) : 0.0;
-      xs[tid] = xa;
-      if (i0 + tid < m) A.x[I.lo + i0 + tid] = xa;
+      for (int w = 0; w < kGroupWaves; ++w) t += red[g * kGroupWaves + w][a];
+      const double xa = i < m ? rcp64(t + kz * y_dust) : 0.0;
+      xs[g][a] = xa;
+      if (i < m) A.x[I.lo + i] = xa;
     }
     __syncthreads();
+    if (strip >= nstrips) return;
     double xa[kSweepRows];
 #pragma unroll
-    for (int a = 0; a < kSweepRows; ++a) xa[a] = xs[a];
-    if (tid == 0) {
+    for (int a = 0; a < kSweepRows; ++a) xa[a] = xs[rg][a];
+    if (ct == 0) {
       double t = 0.0;
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a) t += xa[a];
-      A.xpart[I.lo + blockIdx.x] = t;
+      A.xpart[I.lo + strip] = t;
     }
-    double* out = A.colpart + strip_base(I.po, I.lo) + static_cast<long long>(blockIdx.x) * r;
+    double* out = A.colpart + strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
-    for (int c = 0; c < kSweepChunks; ++c) {
-      const int j = tid + kSweepThreads * c;
+    for (int c = 0; c < CH; ++c) {
+      const int j = ct + CG * c;
       double acc = 0.0;
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a) acc = fma(static_cast<double>(K[a][c]), xa[a], acc);
       if (j < r) out[j] = acc;
     }
   } else {
-    if (tid < kSweepRows) xs[tid] = (i0 + tid < m) ? A.x[I.lo + i0 + tid] : 0.0;
+    if (tid < kSweepRows * RG) {
+      const int g = tid / kSweepRows, a = tid - g * kSweepRows;
+      const int i = (blockIdx.x * RG + g) * kSweepRows + a;
+      xs[g][a] = i < m ? A.x[I.lo + i] : 0.0;
+    }
     __syncthreads();
+    if (strip >= nstrips) return;
     float* P = A.plan_out ? A.plan_out + I.po : nullptr;
-    const long long sb = strip_base(I.po, I.lo) + static_cast<long long>(blockIdx.x) * r;
+    const long long sb = strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
-    for (int c = 0; c < kSweepChunks; ++c) {
-      const int j = tid + kSweepThreads * c;
+    for (int c = 0; c < CH; ++c) {
+      const int j = ct + CG * c;
       float bv = -1.f;
       int bi = 0x7fffffff;
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a) {
         if (i0 + a < m && j < r) {
-          const float v = static_cast<float>(xs[a] * static_cast<double>(K[a][c]) * yv[c]);
+          const float v = static_cast<float>(xs[rg][a] * static_cast<double>(K[a][c]) * yv[c]);
           if (P) P[static_cast<long long>(i0 + a) * r + j] = v;
           if (v > bv) { bv = v; bi = i0 + a; }
         }
@@ -193,6 +208,22 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
       if (j < r && A.pair_out) { A.bestv[sb + j] = bv; A.besti[sb + j] = bi; }
     }
   }
+}
+
+// CH: columns per thread of the wide shape; the launch picks the smallest that
+// covers the batch's largest possible pruned set (512 CH columns).  (Separate
+// kernels for the narrow and the wide shapes, each with its own register
+// budget, were measured: the extra launch over a mostly idle grid costs what the
+// higher occupancy gains.)
+template <bool FINAL, typename KT, int CH>
+__global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int parity,
+                                                             const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  SweepImage I;
+  if (!sweep_image(A, blockIdx.y, I)) return;
+  if (I.r <= 128) sweep_rows_body<FINAL, KT, 128, 4, 1>(A, I, parity);
+  else if (I.r <= 256) sweep_rows_body<FINAL, KT, 256, 2, 1>(A, I, parity);
+  else if (I.r <= kSweepThreads * CH) sweep_rows_body<FINAL, KT, 512, 1, CH>(A, I, parity);
 }
 
 // Workgroup = 64 columns x 4 waves; wave g takes the strips s = g, g + 4, ...
@@ -221,26 +252,33 @@ __global__ __launch_bounds__(kSweepColThreads) void k_sweep_cols(SweepArgs A, in
   if (first) {
     x_dust = exp(A.p.shift / A.p.eps);                // no iteration yet (T = 0 pairing only)
   } else {
-    double sy = A.ydust[parity * A.B + I.b];
-    for (int k = 0; k < nblocks; ++k) sy += A.ysum[parity * A.total + I.lo + k];
+    // at most 32 block sums: one per lane, added by the wave (every wave of
+    // every workgroup forms the same total in the same order)
+    const double mine = lane < nblocks ? A.ysum[parity * A.total + I.lo + lane] : 0.0;
+    const double sy = wave_sum_dpp(mine) + A.ydust[parity * A.B + I.b];
     x_dust = static_cast<double>(r) * rcp64(kz * sy);
   }
   const long long sb = strip_base(I.po, I.lo);
   if (!FINAL) {
     double sx = 0.0;
-    for (int s = tid; s < nstrips; s += kSweepColThreads) sx += A.xpart[I.lo + s];
-    sx = block_sum<kSweepColThreads>(sx, red);
-    double t0 = 0.0, t1 = 0.0;
+    if (blockIdx.x == 0) {                              // only this workgroup writes y_d
+      for (int s = tid; s < nstrips; s += kSweepColThreads) sx += A.xpart[I.lo + s];
+      sx = block_sum<kSweepColThreads>(sx, red);
+    }
+    // this wave's strips g, g + 4, ...: eight loads in flight, eight running sums
+    double t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = 0.0;
     if (j < r) {
       const double* cp = A.colpart + sb + j;
       int s = g;
-      for (; s + kSweepColGroups < nstrips; s += 2 * kSweepColGroups) {
-        t0 += cp[static_cast<long long>(s) * r];
-        t1 += cp[static_cast<long long>(s + kSweepColGroups) * r];
+      for (; s + 7 * kSweepColGroups < nstrips; s += 8 * kSweepColGroups) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] += cp[static_cast<long long>(s + u * kSweepColGroups) * r];
       }
-      if (s < nstrips) t0 += cp[static_cast<long long>(s) * r];
+      for (; s < nstrips; s += kSweepColGroups) t[0] += cp[static_cast<long long>(s) * r];
     }
-    part[g][lane] = t0 + t1;
+    part[g][lane] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
     __syncthreads();
     double yj = 0.0;
     if (g == 0 && j < r) {
