@@ -27,6 +27,8 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP64_VECTOR_TFLOPS = 78.6      # 256 CU x 2.4 GHz x 128 flop/clk
+BF16_MFMA_TFLOPS = 2500.0       # dense bf16 matrix-core peak
+FP32_VECTOR_TFLOPS = 157.3      # fp32 vector peak
 FP32_VECTOR_TFLOPS = 157.3
 BF16_MFMA_TFLOPS = 2500.0
 
@@ -56,7 +58,8 @@ def generate(cfg: int, workers: int):
     return synth.Batch(cfg, w.dtype, tokens, offsets, dens, dict(w.params), list(range(w.batch)))
 
 
-def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, iters: int):
+def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, iters: int,
+                eps: float = 0.05, z: float = 0.2):
     """Algorithmic work of one launch of a kernel over the batch: (bound, amount, unit, peak).
 
     Bytes are the unavoidable HBM traffic of the step the kernel performs
@@ -64,15 +67,31 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     """
     r = n - m
     tok_bytes = float(n.sum()) * d * elt
+    # images beyond the register-resident Sinkhorn shapes, when the batch may hold any
+    # (more than 512 tokens): their kernel matrix is streamed once per iteration, in
+    # fp32 when exp's range allows
+    big = ((m + 1 > 512) | (r > 64)) & (r > 0) & (r <= 2048) if n.max(initial=0) > 512 else np.zeros(len(n), bool)
+    kbytes = 4.0 if (max(1.0, z) - min(-1.0, z)) / eps <= 80.0 else 8.0
     if kernel == "k_norms":
         # every token row read once; 4-byte score + 8-byte squared norm written
         return "hbm", tok_bytes + 12.0 * n.sum(), "GB/s", HBM_PEAK_GBS
     if kernel == "k_merge":
-        # kept and pruned rows read once, merged kept rows written once, plan read
-        return "hbm", tok_bytes + float(m.sum()) * d * elt + 4.0 * float((m * r).sum()), "GB/s", HBM_PEAK_GBS
+        # kept and pruned rows read once, merged kept rows written once, plan read;
+        # one fp32 multiply-add per (kept, pruned, d).  With many pruned tokens per image
+        # the arithmetic outweighs the traffic (ridge of the fp32 vector units: 20 flop/B)
+        nbytes = tok_bytes + float(m.sum()) * d * elt + 4.0 * float((m * r).sum())
+        flops = 2.0 * float((m * r).sum()) * d
+        if flops / nbytes > FP32_VECTOR_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            return "alu", flops, "TFLOP/s", FP32_VECTOR_TFLOPS
+        return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
     if kernel == "k_scores":
-        # fp64 vector arithmetic: one multiply-add per (kept, pruned, d)
+        if elt == 2 and d % 128 == 0:
+            # bf16 matrix cores: one multiply-add per (kept, pruned, d)
+            return "mfma", 2.0 * float((m * r).sum()) * d, "TFLOP/s", BF16_MFMA_TFLOPS
         return "alu", 2.0 * float((m * r).sum()) * d, "TFLOP/s", FP64_VECTOR_TFLOPS
+    if kernel == "k_sinkhorn" and big.any():
+        # sweep kernels: the kernel matrix read once per iteration (it does not fit on chip)
+        return "hbm", kbytes * iters * float((m * r)[big].sum()), "GB/s", HBM_PEAK_GBS
     if kernel in ("k_sinkhorn", "k_sinkhorn_regs"):
         # two sweeps of multiply-adds over the augmented matrix per iteration
         return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
@@ -130,6 +149,52 @@ def bench_density(rt, torch, steps: int, unique: int = 16, copies: int = 16):
             "cpu_oracle_pages_per_s": round(len(want) / (c1 - c0), 2), "bit_exact_vs_oracle": True}
 
 
+def bench_large_pages(rt, torch, synth, steps: int, cfg: int = 8):
+    """Time the fused call on the largest page size of the paper's other OCR models
+    (Table 6: 4512 -> 2783 tokens): the shapes whose Sinkhorn matrix does not fit a
+    workgroup and whose similarity product is a real GEMM."""
+    batch = synth.gen_batch(cfg)
+    w = synth.WORKLOADS[cfg]
+    dev = "cuda:0"
+    p = rt.make_params(batch.params)
+    db = rt.upload(batch, dev)
+    ws = rt.alloc_workspace(db)
+    B, total, D = db.B, db.total_tokens, db.D
+    out = torch.empty((total, D), dtype=db.tokens.dtype, device=dev)
+    out_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    keep = torch.empty(B, dtype=torch.int32, device=dev)
+    pair = torch.empty(total, dtype=torch.int32, device=dev)
+
+    def step():
+        rt.check(rt.rtprune_prune(db, None, p, out, out_off, keep, None, pair, None, ws))
+
+    step()
+    torch.cuda.synchronize()
+    rt.rtprune_profile_enable(1)
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    rc, prof = rt.rtprune_profile_summary()
+    rt.rtprune_profile_enable(0)
+    rt.check(rc)
+    ms = (t2 - t1) * 1e3 / steps
+    kernels = {r_["kernel"]: r_["total_ms"] / max(1, r_["launches"]) for r_ in prof}
+    n_h = np.diff(batch.offsets).astype(np.int64)
+    keep_h = keep.cpu().numpy().astype(np.int64)
+    roof = {}
+    for k_ in ("k_sinkhorn", "k_scores", "k_merge"):
+        bound, amount, unit, peak = kernel_work(k_, n_h, keep_h, D, 2, int(batch.params["iters"]),
+                                                float(batch.params["eps"]), float(batch.params["z"]))
+        ach = amount / (kernels[k_] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        roof[k_] = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
+    return dict(workload=w.name, images=B, total_tokens=int(total), kept_tokens=int(keep_h.sum()),
+                ms_per_step=round(ms, 3), images_per_s=round(B / (ms * 1e-3), 1),
+                tokens_per_s=round(total / (ms * 1e-3), 1),
+                kernels_ms={k_: round(v, 4) for k_, v in kernels.items()}, roofline=roof)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +205,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lib", default=None, help="path of an alternative build of librtprune.so")
     ap.add_argument("--no-density", action="store_true", help="skip the textual-density side measurement")
+    ap.add_argument("--no-large-pages", action="store_true",
+                    help="skip the side measurement on 4512-token pages")
     ap.add_argument("--gen-workers", type=int, default=16,
                     help="processes drawing the synthetic batch (1: in-process, for runs under a profiler)")
     args = ap.parse_args()
@@ -216,7 +283,8 @@ def main() -> int:
     dominant = max(kernels, key=kernels.get) if kernels else None
     roofline = None
     if dominant:
-        bound, amount, unit, peak = kernel_work(dominant, n_h, keep_h, D, elt, int(batch.params["iters"]))
+        bound, amount, unit, peak = kernel_work(dominant, n_h, keep_h, D, elt, int(batch.params["iters"]),
+                                                 float(batch.params["eps"]), float(batch.params["z"]))
         dur_s = kernels[dominant] * 1e-3
         achieved = amount / dur_s / (1e9 if unit == "GB/s" else 1e12)
         traffic = None
@@ -266,6 +334,12 @@ def main() -> int:
         torch.cuda.empty_cache()
         density = bench_density(rt, torch, max(3, args.steps // 2))
 
+    large = None
+    if not args.no_large_pages and args.workload == 5:
+        del db
+        torch.cuda.empty_cache()
+        large = bench_large_pages(rt, torch, synth, 3)
+
     line = {
         "metric": "images/s pruned (fused rtprune_prune, 400-token 1280-d bf16 pages)",
         "value": round(images_per_s, 2),
@@ -284,6 +358,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "text_density": density,
+        "large_pages": large,
     }
     print(json.dumps(line))
     return 0
