@@ -27,10 +27,8 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP64_VECTOR_TFLOPS = 78.6      # 256 CU x 2.4 GHz x 128 flop/clk
-BF16_MFMA_TFLOPS = 2500.0       # dense bf16 matrix-core peak
-FP32_VECTOR_TFLOPS = 157.3      # fp32 vector peak
-FP32_VECTOR_TFLOPS = 157.3
-BF16_MFMA_TFLOPS = 2500.0
+FP32_VECTOR_TFLOPS = 157.3     # fp32 vector peak
+BF16_MFMA_TFLOPS = 2500.0      # dense bf16 matrix-core peak
 
 
 def _gen_one(args):
