@@ -451,3 +451,36 @@ def text_density(rgb_u8: np.ndarray, patch_h: int, patch_w: int, tau: float):
     rho_k = (counts.astype(np.float64) / area).astype(np.float32).ravel()
     rho = np.float32(float(counts.sum()) / float(counts.size * area))
     return rho, rho_k
+
+
+# ---------------------------------------------------------------------------
+# sequence splice: pruned visual tokens into the language model's input
+# ---------------------------------------------------------------------------
+POSITIONS_CONSECUTIVE, POSITIONS_ORIGINAL = 0, 1
+
+
+def splice_sequence(prefix: np.ndarray, visual: np.ndarray, suffix: np.ndarray,
+                    kept: np.ndarray, n_visual: int, mode: int = POSITIONS_CONSECUTIVE):
+    """Input sequence of the language model's prefill after pruning (Sec. 4.3: the
+    pruning runs before the prefill stage): text embeddings before the image, the
+    merged kept visual tokens in ascending original index, text embeddings after it.
+
+    The paper does not say which position each token takes; both natural choices
+    are offered:
+      POSITIONS_CONSECUTIVE  0, 1, ..., L'-1 over the shortened sequence;
+      POSITIONS_ORIGINAL     the position the token had in the unpruned sequence:
+                             prefix k -> k, kept token with original index i ->
+                             P + i, suffix k -> P + N + k.
+    Returns (rows [P + M + S, D], position ids int32 [P + M + S]).
+    """
+    P, M, S = prefix.shape[0], visual.shape[0], suffix.shape[0]
+    assert len(kept) == M
+    rows = np.concatenate([prefix, visual, suffix], axis=0)
+    if mode == POSITIONS_CONSECUTIVE:
+        pos = np.arange(P + M + S, dtype=np.int32)
+    elif mode == POSITIONS_ORIGINAL:
+        pos = np.concatenate([np.arange(P), P + np.asarray(kept, dtype=np.int64),
+                              P + n_visual + np.arange(S)]).astype(np.int32)
+    else:
+        raise ValueError("unknown position mode")
+    return rows, pos
