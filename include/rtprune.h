@@ -198,6 +198,46 @@ int rtprune_prune(const rtprune_batch* in, const float* density,
                   float* ratio, void* workspace, size_t workspace_bytes,
                   void* stream);
 
+/* Text embeddings around each image of a batch, for rtprune_prune_splice.  All
+ * rows have the batch's dtype and width D.  A side with no rows anywhere may
+ * have NULL pointers and 0 rows. */
+typedef struct rtprune_text_spans {
+  const void* prefix;            /* device, [prefix_rows, D]: the rows before each image, packed */
+  const int32_t* prefix_offsets; /* device, [B + 1] exclusive prefix sum of per-image row counts */
+  int64_t prefix_rows;           /* host scalar, = prefix_offsets[B] */
+  const void* suffix;            /* device, [suffix_rows, D]: the rows after each image */
+  const int32_t* suffix_offsets; /* device, [B + 1] */
+  int64_t suffix_rows;           /* host scalar, = suffix_offsets[B] */
+} rtprune_text_spans;
+
+/* Position convention of rtprune_prune_splice (the paper does not fix one). */
+typedef enum rtp_positions {
+  RTP_POSITIONS_CONSECUTIVE = 0, /* 0 .. L'-1 over each shortened sequence */
+  RTP_POSITIONS_ORIGINAL = 1     /* the position each token had before pruning: prefix k -> k, kept
+                                    visual token with original index i -> P + i, suffix k -> P + N + k */
+} rtp_positions;
+
+/* rtprune_prune with its output spliced into the language model's prefill input
+ * (Sec. 4.3: the pruning runs before the prefill stage; Algorithm 1's output is
+ * what replaces the N visual tokens).  Sequence b is written at row
+ * seq_offsets[b] of `seq`: its P_b prefix rows, its M_b merged kept tokens in
+ * ascending original index (the rows rtprune_prune would write), its S_b suffix
+ * rows; sequences are packed in image order.
+ *   seq                [seq_capacity_rows, D] out, dtype of the batch, 16-byte aligned;
+ *                      seq_capacity_rows >= prefix_rows + suffix_rows + total_tokens
+ *                      (else RTP_EINVAL); rows beyond seq_offsets[B] are untouched
+ *   seq_offsets        [B + 1] int32 out
+ *   position_ids       [seq_capacity_rows] int32 out, one per written row (may be NULL)
+ *   keep_counts, sel_idx, pair, ratio   as in rtprune_prune (each may be NULL)
+ * Text offsets that decrease or do not end at the stated row counts set
+ * RTP_DEV_BAD_OFFSETS in the status word and nothing is written. */
+int rtprune_prune_splice(const rtprune_batch* in, const float* density,
+                         const rtprune_params* params, const rtprune_text_spans* text,
+                         int32_t position_mode, void* seq, int64_t seq_capacity_rows,
+                         int32_t* seq_offsets, int32_t* position_ids, int32_t* keep_counts,
+                         int32_t* sel_idx, int32_t* pair, float* ratio, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
 /* Textual density (Sec. 3.3.3, Eq. 8; Appendix B): for each page image,
  * grayscale I = (0.299 R + 0.587 G + 0.114 B) / 255, the two 3x3 Sobel responses
  * G_x, G_y (border pixels see their nearest neighbour repeated), an edge pixel

@@ -22,6 +22,7 @@
 #include "scores_mfma.hpp"
 #include "merge_lds.hpp"
 #include "density.hpp"
+#include "splice.hpp"
 
 using namespace rtp;
 
@@ -146,11 +147,11 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_SPLICE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
                                              "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn",
                                              "k_merge", "k_density_prepare", "k_density_sobel",
-                                             "k_density_finish"};
+                                             "k_density_finish", "k_splice"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
   std::mutex mu;
@@ -664,4 +665,64 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
   return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, status, s);
+}
+
+extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* density,
+                                    const rtprune_params* params, const rtprune_text_spans* text,
+                                    int32_t position_mode, void* seq, int64_t seq_capacity_rows,
+                                    int32_t* seq_offsets, int32_t* position_ids, int32_t* keep_counts,
+                                    int32_t* sel_idx, int32_t* pair, float* ratio, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  if (!seq || !seq_offsets || !text) return RTP_EINVAL;
+  if (p.dynamic && !density) return RTP_EINVAL;
+  if (position_mode != RTP_POSITIONS_CONSECUTIVE && position_mode != RTP_POSITIONS_ORIGINAL) return RTP_EINVAL;
+  if (text->prefix_rows < 0 || text->suffix_rows < 0) return RTP_EINVAL;
+  if ((text->prefix_rows > 0 && (!text->prefix || !text->prefix_offsets)) ||
+      (text->suffix_rows > 0 && (!text->suffix || !text->suffix_offsets)))
+    return RTP_EINVAL;
+  if (reinterpret_cast<uintptr_t>(text->prefix) % 16 != 0 || reinterpret_cast<uintptr_t>(text->suffix) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(seq) % 16 != 0)
+    return RTP_EINVAL;
+  // every image keeps at most all of its tokens
+  const long long need = text->prefix_rows + text->suffix_rows + in->total_tokens;
+  if (seq_capacity_rows < need) return RTP_EINVAL;
+  if (need > 0x7fffffffLL) return RTP_EUNSUPPORTED;
+  if (static_cast<long long>(in->D) * (in->dtype == RTP_BF16 ? 2 : 4) % 16 != 0) return RTP_EUNSUPPORTED;
+  Layout L;
+  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* status = at<int32_t>(workspace, L.status);
+  int32_t* keep = keep_counts ? keep_counts : at<int32_t>(workspace, L.keep);
+  int32_t* sel = sel_idx ? sel_idx : at<int32_t>(workspace, L.sel);
+  int32_t* visual_start = at<int32_t>(workspace, L.out_off);
+  long long* plan_off = at<long long>(workspace, L.plan_off);
+  float* plan = at<float>(workspace, L.plan);
+  const TextSpans t{text->prefix, text->prefix_offsets, text->prefix_rows,
+                    text->suffix, text->suffix_offsets, text->suffix_rows};
+  RTP_TRY(launch_prepare(in, status, s));
+  if (in->B > 0) hipLaunchKernelGGL(k_splice_check, dim3(1), dim3(256), 0, s, t, in->B, status);
+  RTP_TRY(launched());
+  RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
+  RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
+  RTP_TRY(launch_scan(in, keep, nullptr, plan_off, status, s));
+  hipLaunchKernelGGL(k_splice_scan, dim3(1), dim3(256), 0, s, t, keep, in->B, seq_offsets, visual_start, status);
+  RTP_TRY(launched());
+  const int max_pruned = p.dynamic ? -1
+                                   : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
+  // the merge writes image b's kept rows at visual_start[b], between its text spans
+  RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, status, s));
+  if (in->B == 0) return RTP_OK;
+  ProfScope prof(KID_SPLICE, s);
+  const dim3 grid(64, in->B);
+  if (in->dtype == RTP_BF16)
+    hipLaunchKernelGGL((k_splice_text<bf16_t>), grid, dim3(256), 0, s, t, in->offsets, keep, sel, in->D,
+                       position_mode, seq_offsets, static_cast<bf16_t*>(seq), position_ids, status);
+  else
+    hipLaunchKernelGGL((k_splice_text<float>), grid, dim3(256), 0, s, t, in->offsets, keep, sel, in->D,
+                       position_mode, seq_offsets, static_cast<float*>(seq), position_ids, status);
+  return launched();
 }

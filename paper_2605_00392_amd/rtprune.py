@@ -19,11 +19,12 @@ LIB_PATH = os.path.join(HERE, "librtprune.so")
 RTP_OK, RTP_EINVAL, RTP_EUNSUPPORTED, RTP_EWORKSPACE, RTP_EHIP = range(5)
 RTP_F32, RTP_BF16 = 0, 1
 RTP_METRIC_L2NORM, RTP_METRIC_VARIANCE = 0, 1
+RTP_POSITIONS_CONSECUTIVE, RTP_POSITIONS_ORIGINAL = 0, 1
 RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE = 1, 2, 4
 
 EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
-    "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune",
+    "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune", "rtprune_prune_splice",
     "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_copy_bytes",
     "rtprune_text_density_workspace_bytes", "rtprune_text_density",
 )
@@ -40,6 +41,13 @@ class rtprune_params(ctypes.Structure):
         ("ratio", ctypes.c_float), ("ratio_min", ctypes.c_float), ("ratio_max", ctypes.c_float),
         ("phi_lo", ctypes.c_float), ("phi_hi", ctypes.c_float),
         ("metric", ctypes.c_int32),
+    ]
+
+
+class rtprune_text_spans(ctypes.Structure):
+    _fields_ = [
+        ("prefix", ctypes.c_void_p), ("prefix_offsets", ctypes.c_void_p), ("prefix_rows", ctypes.c_int64),
+        ("suffix", ctypes.c_void_p), ("suffix_offsets", ctypes.c_void_p), ("suffix_rows", ctypes.c_int64),
     ]
 
 
@@ -81,6 +89,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_merge.argtypes = [pb, vp, vp, vp, vp, vp, pp, vp, vp]
     lib.rtprune_prune.restype = ctypes.c_int
     lib.rtprune_prune.argtypes = [pb, vp, pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.rtprune_prune_splice.restype = ctypes.c_int
+    lib.rtprune_prune_splice.argtypes = [pb, vp, pp, ctypes.POINTER(rtprune_text_spans), i32, vp, ctypes.c_int64,
+                                         vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.rtprune_profile_enable.restype = ctypes.c_int
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_summary.restype = ctypes.c_int
@@ -219,6 +230,24 @@ def rtprune_prune(batch: DeviceBatch, density, params: rtprune_params, out, out_
     return load_library().rtprune_prune(
         ctypes.byref(d), _addr(density), ctypes.byref(params), _addr(out), _addr(out_offsets),
         _addr(keep_counts), _addr(sel_idx), _addr(pair), _addr(ratio), _addr(workspace),
+        workspace.numel() if workspace is not None else 0, _stream(stream))
+
+
+def make_text_spans(prefix=None, prefix_offsets=None, prefix_rows: int = 0,
+                    suffix=None, suffix_offsets=None, suffix_rows: int = 0) -> rtprune_text_spans:
+    """Fill the C text-span struct from device arrays (or None for an absent side)."""
+    return rtprune_text_spans(_addr(prefix), _addr(prefix_offsets), int(prefix_rows),
+                              _addr(suffix), _addr(suffix_offsets), int(suffix_rows))
+
+
+def rtprune_prune_splice(batch: DeviceBatch, density, params: rtprune_params, text: rtprune_text_spans,
+                         position_mode: int, seq, seq_capacity_rows: int, seq_offsets, position_ids,
+                         keep_counts, sel_idx, pair, ratio, workspace, stream=None) -> int:
+    d = batch.desc()
+    return load_library().rtprune_prune_splice(
+        ctypes.byref(d), _addr(density), ctypes.byref(params), ctypes.byref(text), int(position_mode),
+        _addr(seq), int(seq_capacity_rows), _addr(seq_offsets), _addr(position_ids), _addr(keep_counts),
+        _addr(sel_idx), _addr(pair), _addr(ratio), _addr(workspace),
         workspace.numel() if workspace is not None else 0, _stream(stream))
 
 

@@ -40,7 +40,8 @@ def test_struct_layouts_match_the_header(tmp_path):
     """Sizes and field offsets of the ctypes mirrors equal what a C compiler lays out from the header."""
     import subprocess
     fields = {"rtprune_params": [n for n, _ in rt.rtprune_params._fields_],
-              "rtprune_batch": [n for n, _ in rt.rtprune_batch._fields_]}
+              "rtprune_batch": [n for n, _ in rt.rtprune_batch._fields_],
+              "rtprune_text_spans": [n for n, _ in rt.rtprune_text_spans._fields_]}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rtprune.h"', 'int main(void) {']
     for st, names in fields.items():
         lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
@@ -138,6 +139,15 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert rt.rtprune_norms_topk(b, None, ok, None, None, 0x6000, 0x7000, 0x8000, ws, stream=0) == rt.RTP_EINVAL
     assert rt.rtprune_ot_pair(b, None, 0x6000, 0x8000, ok, None, None, None, ws, stream=0) == rt.RTP_EINVAL
     assert rt.rtprune_merge(b, 0x6000, 0x6100, 0x6200, None, 0x8000, ok, 0x9000, stream=0) == rt.RTP_EINVAL
+    # splice: position mode, capacity (64 tokens + 10 prefix rows need 74), text pointers
+    txt = rt.make_text_spans(0xA000, 0xB000, 10)
+    sp = lambda text, mode, cap, seq=0x4000: rt.rtprune_prune_splice(b, None, ok, text, mode, seq, cap, 0x5000, None,
+                                                                      None, None, None, None, ws, stream=0)
+    assert sp(txt, 2, 100) == rt.RTP_EINVAL
+    assert sp(txt, 0, 73) == rt.RTP_EINVAL
+    assert sp(rt.make_text_spans(None, None, 10), 0, 100) == rt.RTP_EINVAL
+    assert sp(rt.make_text_spans(0xA004, 0xB000, 10), 0, 100) == rt.RTP_EINVAL
+    assert sp(txt, 0, 100, seq=None) == rt.RTP_EINVAL
 
 
 def test_missing_library_is_an_error_not_a_fallback(tmp_path):
