@@ -20,6 +20,7 @@
 #include "sinkhorn_dual.hpp"
 #include "sinkhorn_sweep.hpp"
 #include "scores_mfma.hpp"
+#include "scores_tiled.hpp"
 #include "merge_lds.hpp"
 #include "density.hpp"
 #include "splice.hpp"
@@ -273,6 +274,21 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
       else
         hipLaunchKernelGGL((k_scores_mfma<4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
                            sq, p, kmat, L.plan_cap, scores_out, st);
+      RTP_TRY(launched());
+      // images with many pruned tokens: the LDS-tiled kernel.  Largest pruned set
+      // the call can produce: the caller's bound, else what the retention clamp allows
+      int rmax = max_pruned_hint;
+      if (rmax < 0)
+        rmax = p.dynamic ? static_cast<int>((1.0 - static_cast<double>(p.ratio_min)) * in->max_tokens) + 1
+                         : in->max_tokens - 1;
+      rmax = std::min(rmax, in->max_tokens - 1);
+      if (rmax > kTiledMinPruned) {
+        const int tiles_m = (in->max_tokens + kTileRows - 1) / kTileRows;
+        const int tiles_n = (rmax + kTileCols - 1) / kTileCols;
+        hipLaunchKernelGGL(k_scores_tiled, dim3(tiles_m * tiles_n, in->B), dim3(kTiledThreads), 0, s, tok,
+                           in->offsets, in->D, sel, keep, plan_off, sq, p, kmat, L.plan_cap, scores_out, tiles_n,
+                           st);
+      }
       return launched();
     }
   }

@@ -34,6 +34,7 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 #endif
 constexpr int kMfmaRowsPerWave = RTP_MFMA_ROWS_PER_WAVE;   // MT tiles of 16 kept rows
 constexpr int kMfmaWaves = RTP_MFMA_WAVES;
+constexpr int kTiledMinPruned = 192;   // images with more pruned tokens take k_scores_tiled
 
 // Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
 // the kernel below), chosen on the host from the largest pruned set the call
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
   const int m = min(max(keep[b], 0), n), r = n - m;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i0 = (blockIdx.x * kMfmaWaves + wave) * kMfmaRowsPerWave;
-  if (r <= 0 || i0 >= m) return;
+  if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // larger pruned sets: k_scores_tiled
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
   const bool k_f32 = kernel_is_f32(p, m, r);

@@ -1,0 +1,196 @@
+// Cosine scores of Eq. 3 for images with many pruned tokens (R > kTiledMinPruned:
+// other OCR models' pages, aggressive ratios), where S = T_kept T_prop^T is a
+// real GEMM: a workgroup computes a 128 x 64 tile of S, staging 64 elements of
+// the contraction per step of both operands in LDS (double-buffered) so that
+// every token row is fetched once per tile instead of once per 16-row sub-tile.
+//
+// Accuracy: the same v_mfma_f32_16x16x32_bf16 as k_scores_mfma, but the two of a
+// step (64 terms of the contraction) are chained on one fp32 accumulator before
+// the partial is added to the fp64 sum, which halves the fp64 vector work per
+// matrix instruction.  Measured against the fp64 oracle on 1083- to 4512-token
+// pages the cosine is off by at most 4.2e-8 (k_scores_mfma: 2e-8) and plan
+// entries by at most 7.7e-7 relative - still inside the 1e-6 band in which an
+// index flip counts as a near-tie; chaining four (128 terms) gave 8e-8 and was
+// rejected.  Both kernels write the same quantities; an image goes to exactly
+// one of them.
+//
+// Workgroup = 4 waves as 2 x 2, a wave owns 64 x 32 = 4 x 2 matrix tiles; two
+// workgroups share a CU, so one's arithmetic hides the other's loads.  LDS
+// rows are padded by 16 bytes (pitch 144) so that the 16 lanes of a fragment
+// read, 144 bytes apart, fall into distinct banks.
+#pragma once
+#include "common.hpp"
+#include "scores_mfma.hpp"
+#include "sinkhorn_team.hpp"
+
+namespace rtp {
+
+constexpr int kTileRows = 128;         // kept rows per workgroup tile
+constexpr int kTileCols = 64;          // pruned rows per workgroup tile
+constexpr int kTileStep = 64;          // contraction elements per step (128 bytes per row)
+constexpr int kTilePitch = 144;        // LDS bytes per staged row
+constexpr int kTiledThreads = 256;
+constexpr int kTiledChain = 1;         // steps (of two 32-term partial products each) between fp64 flushes
+
+__host__ __device__ inline bool score_is_tiled(int r) { return r > kTiledMinPruned; }
+
+__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(
+    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
+    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
+    const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
+    double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out, int tiles_n,
+    const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.y;
+  const int lo = offsets[b];
+  const int n = offsets[b + 1] - lo;
+  const int m = min(max(keep[b], 0), n), r = n - m;
+  if (!score_is_tiled(r)) return;
+  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x - tm * tiles_n;
+  const int i0 = tm * kTileRows, j0 = tn * kTileCols;
+  if (i0 >= m || j0 >= r) return;
+  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
+  const long long po = plan_offsets[b];
+  const bool k_f32 = kernel_is_f32(p, m, r);
+  const int32_t* sel = sel_idx + lo;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;          // the wave's 64 x 32 part of the tile
+  const double inv_eps = 1.0 / p.eps;
+
+  __shared__ __attribute__((aligned(16))) unsigned char lds_a[2][kTileRows * kTilePitch];   // [buffer]
+  __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kTileCols * kTilePitch];
+
+  // staging: thread t moves piece t % 8 (16 bytes) of rows t / 8 + 32 q of each operand
+  constexpr int QA = kTileRows / 32, QB = kTileCols / 32;
+  const int piece = tid & 7, srow = tid >> 3;
+  const bf16_t* aptr[QA];
+  const bf16_t* bptr[QB];
+#pragma unroll
+  for (int q = 0; q < QA; ++q) {
+    const int i = min(i0 + srow + 32 * q, m - 1);
+    aptr[q] = tokens + static_cast<size_t>(lo + clamp_index(sel[i], n)) * D + 8 * piece;
+  }
+#pragma unroll
+  for (int q = 0; q < QB; ++q) {
+    const int j = min(j0 + srow + 32 * q, r - 1);
+    bptr[q] = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j], n)) * D + 8 * piece;
+  }
+  // the next step's rows are requested from memory before this step's arithmetic
+  // and go to the other LDS buffer after it
+  const int steps = D / kTileStep;                   // even: D is a multiple of 128 on this path
+  uint4 sa[QA], sb[QB];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int q = 0; q < QA; ++q) sa[q] = *reinterpret_cast<const uint4*>(aptr[q] + k0);
+#pragma unroll
+    for (int q = 0; q < QB; ++q) sb[q] = *reinterpret_cast<const uint4*>(bptr[q] + k0);
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int q = 0; q < QA; ++q)
+      *reinterpret_cast<uint4*>(&lds_a[buf][(srow + 32 * q) * kTilePitch + 16 * piece]) = sa[q];
+#pragma unroll
+    for (int q = 0; q < QB; ++q)
+      *reinterpret_cast<uint4*>(&lds_b[buf][(srow + 32 * q) * kTilePitch + 16 * piece]) = sb[q];
+  };
+
+  // fp64 sums of the flushed partials and the fp32 accumulators of the matrix
+  // instructions between two flushes
+  double acc[4][2][4];
+  floatx4_t part[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      part[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
+    }
+
+  // fragment of a 16-row tile for half h of the step: lane l reads the 16 bytes
+  // at row l % 16, elements 16 (l / 16) + 8 h .. + 7 of the step - the same
+  // assignment of contraction elements to lanes for both operands
+  const int frag_off = (lane & 15) * kTilePitch + 32 * (lane >> 4);
+  auto compute = [&](int buf) {
+    const unsigned char* A = &lds_a[buf][wm * 64 * kTilePitch + frag_off];
+    const unsigned char* B = &lds_b[buf][wn * 32 * kTilePitch + frag_off];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint4 fa[4], fb[2];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) fa[t] = *reinterpret_cast<const uint4*>(A + 16 * t * kTilePitch + 16 * h);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) fb[u] = *reinterpret_cast<const uint4*>(B + 16 * u * kTilePitch + 16 * h);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          part[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, fa[t]), __builtin_bit_cast(bf16x8_t, fb[u]), part[t][u], 0, 0, 0);
+    }
+  };
+  auto flush = [&]() {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(part[t][u][v]);
+        part[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      }
+  };
+
+  fetch(0);
+  stage(0);
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < steps) fetch((s + 1) * kTileStep);   // in flight during this step's arithmetic
+    compute(buf);
+    if ((s + 1) % kTiledChain == 0 || s + 1 == steps) flush();
+    if (s + 1 < steps) stage(buf ^ 1);               // the other buffer: nobody reads it during this step
+    __syncthreads();
+  }
+
+  // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile.
+  // Reciprocal norms once per row and column; exp through the fp32 unit when K is
+  // stored in fp32 anyway: with y = x log2(e) = k + f, |f| <= 1/2 split in fp64,
+  // exp(x) = 2^k 2^f and v_exp_f32 gives 2^f to about 1e-7 relative, which on the
+  // score is eps * 1e-7.
+  double rni[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int i = min(i0 + 64 * wm + 16 * t + 4 * (lane >> 4) + v, m - 1);
+      rni[t][v] = 1.0 / fmax(norm64[lo + clamp_index(sel[i], n)], kTinyNorm);
+    }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int j = j0 + 32 * wn + 16 * u + (lane & 15);
+    if (j >= r) continue;
+    const double rnj = 1.0 / fmax(norm64[lo + clamp_index(sel[m + j], n)], kTinyNorm);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = i0 + 64 * wm + 16 * t + 4 * (lane >> 4) + v;
+        if (i < m) {
+          const double sc = acc[t][u][v] * rni[t][v] * rnj;
+          const long long at = static_cast<long long>(i) * r + j;
+          const double x = (sc - p.shift) * inv_eps;
+          if (k_f32) {
+            const double y = x * 1.4426950408889634;
+            const double k = rint(y);
+            const float frac = __builtin_amdgcn_exp2f(static_cast<float>(y - k));
+            reinterpret_cast<float*>(kmat + po)[at] = ldexpf(frac, static_cast<int>(k));
+          } else {
+            kmat[po + at] = exp(x);
+          }
+          if (scores_out) scores_out[po + at] = sc;
+        }
+      }
+  }
+}
+
+}  // namespace rtp

@@ -21,7 +21,7 @@ MERGE_RTOL, MERGE_ATOL = 2e-3, 1e-3     # bf16 merged features, elementwise
 MERGE_ROW_REL = 3e-3       # per-token ||g - o|| / ||o||; bf16 rounding alone gives about 2^-8 / sqrt(3) = 2.3e-3
 MERGE_F32_REL = 1e-5       # fp32 in/out
 PLAN_REL = 1e-4            # plan entries above 1e-6
-SCORE_ATOL = 5e-8          # cosine scores: 32-term fp32 partial sums on the matrix cores, added in fp64
+SCORE_ATOL = 5e-8          # cosine scores: 32- or 128-term fp32 partial sums on the matrix cores, added in fp64
 RATIO_TOL = 1e-5
 
 
@@ -179,7 +179,7 @@ def compare_image(b: int, batch: synth.Batch, gpu: Dict, p: orc.Params, rep: Rep
             po = int(gpu["plan_offsets"][b])
             S_g = gpu["scores"][po:po + m * r].reshape(m, r)
             rep.max_score_abs = max(rep.max_score_abs, float(np.abs(S_g - ref.S).max()))
-            assert np.abs(S_g - ref.S).max() <= SCORE_ATOL
+            assert np.abs(S_g - ref.S).max() <= SCORE_ATOL, (b, float(np.abs(S_g - ref.S).max()))
             P_g = gpu["plan"][po:po + m * r].reshape(m, r).astype(np.float64)
             P_o = ref.P
             big = P_o > 1e-6

@@ -137,6 +137,10 @@ def test_large_pages(cfg, images, kept):
     rows = int(s["out_offsets"][-1])
     np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
     np.testing.assert_array_equal(f["pair"], s["pair"])
+    # the staged results carry the scores and the plan: compared entry by entry
+    rep2 = hz.compare_batch(batch, s, staged=True)
+    _log(rep2, f"c{cfg} staged")
+    assert rep2.max_score_abs <= hz.SCORE_ATOL
 
 
 # ------------------------------------------------------------------ parameter sweeps
