@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
             const double ni = norm64[lo + clamp_index(sel[i], n)];
             const double s = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
             const long long at = static_cast<long long>(i) * r + j;
-            store_kernel(kmat, po, at, exp((s - p.shift) * inv_eps), k_f32);
+            store_kernel(kmat, po, i, j, r, exp((s - p.shift) * inv_eps), k_f32);
             if (scores_out) scores_out[po + at] = s;
           }
         }

@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(
             const double y = x * 1.4426950408889634;
             const double k = rint(y);
             const float frac = __builtin_amdgcn_exp2f(static_cast<float>(y - k));
-            reinterpret_cast<float*>(kmat + po)[at] = ldexpf(frac, static_cast<int>(k));
+            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = ldexpf(frac, static_cast<int>(k));
           } else {
             kmat[po + at] = exp(x);
           }

@@ -99,13 +99,15 @@ __global__ __launch_bounds__(kSweepColThreads) void k_sweep_init(SweepArgs A, co
 // FINAL = true: plan entries of the strips and, per column, their largest entry.
 //
 // The 512 threads form RG row groups of CG column threads (CG RG = 512); a row
-// group owns one 16-row strip, its thread ct holds columns ct, ct + CG, ... (CH
-// of them).  Narrow images put four strips into a workgroup (CG = 128), wide
-// ones a single strip (CG = 512, up to 2048 columns).
-// KT: storage type of the kernel matrix (float when A.p.k32).
-template <bool FINAL, typename KT, int CG, int RG, int CH>
+// group owns one 16-row strip.  With the fp32 layout (VEC = 4: padded, aligned
+// rows) thread ct holds the four columns 4 ct .. 4 ct + 3, read 16 bytes at a
+// time: 64 column threads cover 256 columns, 512 cover 2048, and narrower images
+// put more strips into a workgroup.  With fp64 storage (VEC = 1) thread ct holds
+// columns ct, ct + CG, ... (CH of them).
+template <bool FINAL, typename KT, int CG, int RG, int CH, int VEC>
 __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepImage& I, int parity) {
   static_assert(CG * RG == kSweepThreads && CG % 64 == 0, "workgroup shape");
+  static_assert(VEC == 1 || (VEC == 4 && sizeof(KT) == 4 && CH == 1), "vector loads: fp32 layout only");
   constexpr int kGroupWaves = CG / 64;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int rg = tid / CG, ct = tid - rg * CG;
@@ -114,29 +116,48 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
   if (static_cast<int>(blockIdx.x) * RG >= nstrips) return;
   const int strip = blockIdx.x * RG + rg;              // may be past the last strip: then all rows are masked
   const int i0 = strip * kSweepRows;
-  const KT* __restrict__ Kg = reinterpret_cast<const KT*>(A.kmat + I.po);
   const double kz = exp((A.p.z - A.p.shift) / A.p.eps);
   const double y_dust = FINAL ? 0.0 : A.ydust[parity * A.B + I.b];   // early: not on the critical path
 
   // The strip stays in registers in its storage type.  Every load is issued
   // unconditionally from a clamped address (all of them in flight at once) and
   // out-of-range entries are zeroed afterwards.
-  KT K[kSweepRows][CH];
-  double yv[CH];
+  KT K[kSweepRows][CH * VEC];
+  double yv[CH * VEC];
+  auto column = [&](int cv) { return VEC == 4 ? 4 * ct + cv : ct + CG * cv; };   // of register slot cv
+  if (VEC == 4) {
+    const int pitch = k32_pitch(r);
+    const float* __restrict__ Kg = k32_base(A.kmat, I.po);
+    const int j4 = min(4 * ct, pitch - 4);             // a whole aligned group inside the padded row
 #pragma unroll
-  for (int c = 0; c < CH; ++c) {
-    const int j = min(ct + CG * c, r - 1);
+    for (int a = 0; a < kSweepRows; ++a) {
+      const float4 v = *reinterpret_cast<const float4*>(Kg + static_cast<long long>(min(i0 + a, m - 1)) * pitch + j4);
+      K[a][0] = static_cast<KT>(v.x);
+      K[a][1 % (CH * VEC)] = static_cast<KT>(v.y);
+      K[a][2 % (CH * VEC)] = static_cast<KT>(v.z);
+      K[a][3 % (CH * VEC)] = static_cast<KT>(v.w);
+    }
+  } else {
+    // fp32 storage of an image with fewer than eight columns comes here too: its
+    // rows are unpadded but start at the aligned base like every fp32 image
+    const KT* __restrict__ Kg = sizeof(KT) == 4 ? reinterpret_cast<const KT*>(k32_base(A.kmat, I.po))
+                                                : reinterpret_cast<const KT*>(A.kmat + I.po);
+    const int pitch = sizeof(KT) == 4 ? k32_pitch(r) : r;
 #pragma unroll
-    for (int a = 0; a < kSweepRows; ++a)
-      K[a][c] = Kg[static_cast<long long>(min(i0 + a, m - 1)) * r + j];
+    for (int c = 0; c < CH; ++c) {
+      const int j = min(ct + CG * c, r - 1);
+#pragma unroll
+      for (int a = 0; a < kSweepRows; ++a)
+        K[a][c] = Kg[static_cast<long long>(min(i0 + a, m - 1)) * pitch + j];
+    }
   }
 #pragma unroll
-  for (int c = 0; c < CH; ++c) {
-    const int j = ct + CG * c;
-    yv[c] = j < r ? A.y[I.lo + j] : 0.0;
+  for (int cv = 0; cv < CH * VEC; ++cv) {
+    const int j = column(cv);
+    yv[cv] = j < r ? A.y[I.lo + j] : 0.0;
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a)
-      if (!(i0 + a < m && j < r)) K[a][c] = KT(0);
+      if (!(i0 + a < m && j < r)) K[a][cv] = KT(0);
   }
   __shared__ double red[kSweepThreads / 64][kSweepRows];
   __shared__ double xs[RG][kSweepRows];
@@ -146,7 +167,7 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
     for (int a = 0; a < kSweepRows; ++a) {
       double acc = 0.0;
 #pragma unroll
-      for (int c = 0; c < CH; ++c) acc = fma(static_cast<double>(K[a][c]), yv[c], acc);
+      for (int cv = 0; cv < CH * VEC; ++cv) acc = fma(static_cast<double>(K[a][cv]), yv[cv], acc);
       s[a] = acc;
     }
     const double mine = reduce_scatter<kSweepRows>(s, lane);     // row wave_column(lane) of this wave
@@ -175,11 +196,11 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
     }
     double* out = A.colpart + strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int j = ct + CG * c;
+    for (int cv = 0; cv < CH * VEC; ++cv) {
+      const int j = column(cv);
       double acc = 0.0;
 #pragma unroll
-      for (int a = 0; a < kSweepRows; ++a) acc = fma(static_cast<double>(K[a][c]), xa[a], acc);
+      for (int a = 0; a < kSweepRows; ++a) acc = fma(static_cast<double>(K[a][cv]), xa[a], acc);
       if (j < r) out[j] = acc;
     }
   } else {
@@ -193,14 +214,14 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
     float* P = A.plan_out ? A.plan_out + I.po : nullptr;
     const long long sb = strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int j = ct + CG * c;
+    for (int cv = 0; cv < CH * VEC; ++cv) {
+      const int j = column(cv);
       float bv = -1.f;
       int bi = 0x7fffffff;
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a) {
         if (i0 + a < m && j < r) {
-          const float v = static_cast<float>(xs[rg][a] * static_cast<double>(K[a][c]) * yv[c]);
+          const float v = static_cast<float>(xs[rg][a] * static_cast<double>(K[a][cv]) * yv[cv]);
           if (P) P[static_cast<long long>(i0 + a) * r + j] = v;
           if (v > bv) { bv = v; bi = i0 + a; }
         }
@@ -210,20 +231,23 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
   }
 }
 
-// CH: columns per thread of the wide shape; the launch picks the smallest that
-// covers the batch's largest possible pruned set (512 CH columns).  (Separate
-// kernels for the narrow and the wide shapes, each with its own register
-// budget, were measured: the extra launch over a mostly idle grid costs what the
-// higher occupancy gains.)
+// One kernel for all widths (separate kernels for narrow and wide images, each
+// with its own register budget, were measured: the extra launch over a mostly
+// idle grid costs what the higher occupancy gains).  CH: columns per thread of
+// the wide shape, the smallest that covers the batch's largest possible pruned
+// set.  The 16-byte loads are used for the widest images only: measured, the
+// registers they take slow every narrower shape down.
 template <bool FINAL, typename KT, int CH>
 __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int parity,
                                                              const int32_t* __restrict__ status) {
   if (status[0]) return;
   SweepImage I;
   if (!sweep_image(A, blockIdx.y, I)) return;
-  if (I.r <= 128) sweep_rows_body<FINAL, KT, 128, 4, 1>(A, I, parity);
-  else if (I.r <= 256) sweep_rows_body<FINAL, KT, 256, 2, 1>(A, I, parity);
-  else if (I.r <= kSweepThreads * CH) sweep_rows_body<FINAL, KT, 512, 1, CH>(A, I, parity);
+  if (I.r <= 128) sweep_rows_body<FINAL, KT, 128, 4, 1, 1>(A, I, parity);
+  else if (I.r <= 256) sweep_rows_body<FINAL, KT, 256, 2, 1, 1>(A, I, parity);
+  else if (sizeof(KT) == 4 && CH == 4 && I.r > kSweepThreads * 2)
+    sweep_rows_body<FINAL, float, 512, 1, 1, 4>(A, I, parity);   // widest images: 16-byte loads pay
+  else if (I.r <= kSweepThreads * CH) sweep_rows_body<FINAL, KT, 512, 1, CH, 1>(A, I, parity);
 }
 
 // Workgroup = 64 columns x 4 waves; wave g takes the strips s = g, g + 4, ...

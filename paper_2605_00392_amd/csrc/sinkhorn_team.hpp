@@ -85,15 +85,22 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
 // The kernel matrix of an image the sweep kernels take is stored in fp32 when
 // its range allows (p.k32): a relative rounding of 6e-8 on K = exp((S - shift)/eps)
 // is an absolute perturbation of eps * 6e-8 on the score S, below the scores' own
-// error, and it halves the bytes every iteration streams.  The fp32 entries of
-// image b occupy the start of its fp64 slot.
+// error, and it halves the bytes every iteration streams.
 __device__ __forceinline__ bool kernel_is_f32(const DevParams& p, int m, int r) {
   return p.k32 && sinkhorn_variant(m, r, p.sweep) == kVariantSweep;
 }
-__device__ __forceinline__ void store_kernel(double* __restrict__ kmat, long long po, long long idx, double v,
-                                             bool as_f32) {
-  if (as_f32) reinterpret_cast<float*>(kmat + po)[idx] = static_cast<float>(v);
-  else kmat[po + idx] = v;
+// fp32 layout of image b's kernel matrix: rows padded to a multiple of four
+// entries (when there are at least eight columns) and the first row on a 16-byte
+// boundary, so that a lane can read four entries of a row at once.  It fits the
+// image's fp64 slot of m r doubles: one double of alignment plus m (r + 3) / 2.
+__host__ __device__ inline int k32_pitch(int r) { return r >= 8 ? (r + 3) & ~3 : r; }
+__device__ __forceinline__ float* k32_base(const double* kmat, long long po) {
+  return reinterpret_cast<float*>(const_cast<double*>(kmat) + ((po + 1) & ~1LL));
+}
+__device__ __forceinline__ void store_kernel(double* __restrict__ kmat, long long po, int i, int j, int r,
+                                             double v, bool as_f32) {
+  if (as_f32) k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(v);
+  else kmat[po + static_cast<long long>(i) * r + j] = v;
 }
 
 // What every register-resident Sinkhorn body needs.
