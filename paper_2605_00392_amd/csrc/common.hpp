@@ -14,6 +14,10 @@ typedef unsigned short bf16_t;     // raw bfloat16 bit pattern
 
 // Hyper-parameters widened once on the host; z, alpha, eps are the doubles of
 // the float32 values the caller passed.
+// Images with more pruned tokens than this take the LDS-tiled matrix-core
+// kernels for the scores and the merge (bf16 tokens, width a multiple of 128).
+constexpr int kTiledMinPruned = 192;
+
 struct DevParams {
   double z, alpha, eps;
   double shift;      // max(1, z): exp((s - shift) / eps) <= 1 for every score s

@@ -22,6 +22,7 @@
 #include "scores_mfma.hpp"
 #include "scores_tiled.hpp"
 #include "merge_lds.hpp"
+#include "merge_tiled.hpp"
 #include "density.hpp"
 #include "splice.hpp"
 
@@ -247,6 +248,19 @@ int launch_scan(const rtprune_batch* in, const int32_t* keep, int32_t* out_off, 
   return launched();
 }
 
+// Largest pruned set any image of the call can have.  `hint` >= 0: the caller's
+// bound (fixed retention); kPrunedFromClamp: the kept counts come from this
+// call's dynamic ratio, whose clamp bounds them; kPrunedUnknown: the kept counts
+// are the user's.
+constexpr int kPrunedFromClamp = -1, kPrunedUnknown = -2;
+int pruned_bound(const rtprune_batch* in, const DevParams& p, int hint) {
+  int rmax = in->max_tokens - 1;
+  if (hint >= 0) rmax = std::min(rmax, hint);
+  else if (hint == kPrunedFromClamp && p.dynamic)
+    rmax = std::min(rmax, static_cast<int>((1.0 - static_cast<double>(p.ratio_min)) * in->max_tokens) + 1);
+  return rmax;
+}
+
 template <typename T>
 int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
@@ -277,11 +291,7 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
       RTP_TRY(launched());
       // images with many pruned tokens: the LDS-tiled kernel.  Largest pruned set
       // the call can produce: the caller's bound, else what the retention clamp allows
-      int rmax = max_pruned_hint;
-      if (rmax < 0)
-        rmax = p.dynamic ? static_cast<int>((1.0 - static_cast<double>(p.ratio_min)) * in->max_tokens) + 1
-                         : in->max_tokens - 1;
-      rmax = std::min(rmax, in->max_tokens - 1);
+      const int rmax = pruned_bound(in, p, max_pruned_hint);
       if (rmax > kTiledMinPruned) {
         const int tiles_m = (in->max_tokens + kTileRows - 1) / kTileRows;
         const int tiles_n = (rmax + kTileCols - 1) / kTileCols;
@@ -374,41 +384,55 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
 template <typename T>
 int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                    const int32_t* keep, const int32_t* out_off, const float* plan,
-                   const long long* plan_off, void* out, const int32_t* status, hipStream_t s) {
+                   const long long* plan_off, void* out, int max_pruned_hint, const int32_t* status,
+                   hipStream_t s) {
   const int tiles = (in->max_tokens + kMergeRowsPerBlock - 1) / kMergeRowsPerBlock;
   const dim3 grid(tiles, in->B), block(256);
   const T* tok = static_cast<const T*>(in->tokens);
   const float alpha = static_cast<float>(p.alpha);
+  // images with many pruned tokens go to the matrix-core kernel (bf16, width a
+  // multiple of 128) when the call can produce any
+  const int rmax = pruned_bound(in, p, max_pruned_hint);
+  const int tiled = (std::is_same<T, bf16_t>::value && in->D % 128 == 0 && rmax > kTiledMinPruned) ? 1 : 0;
   ProfScope prof(KID_MERGE, s);
   if (in->D <= 1280) {
     const dim3 g2((in->max_tokens + kMergeBlockRows - 1) / kMergeBlockRows, in->B);
     if (in->D == 1280)
       hipLaunchKernelGGL((k_merge_lds<T, 5, true>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep,
-                         out_off, plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+                         out_off, plan, plan_off, alpha, in->max_tokens, tiled, static_cast<T*>(out), status);
     else
       hipLaunchKernelGGL((k_merge_lds<T, 5, false>), g2, block, 0, s, tok, in->offsets, in->D, sel, keep,
-                         out_off, plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
-    return launched();
-  }
-  if (in->D <= 1024)
+                         out_off, plan, plan_off, alpha, in->max_tokens, tiled, static_cast<T*>(out), status);
+  } else if (in->D <= 1024) {
     hipLaunchKernelGGL((k_merge<T, 1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
-                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
-  else if (in->D <= 2048)
+                       plan, plan_off, alpha, in->max_tokens, tiled, static_cast<T*>(out), status);
+  } else if (in->D <= 2048) {
     hipLaunchKernelGGL((k_merge<T, 2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
-                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
-  else
+                       plan, plan_off, alpha, in->max_tokens, tiled, static_cast<T*>(out), status);
+  } else {
     hipLaunchKernelGGL((k_merge<T, 4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, out_off,
-                       plan, plan_off, alpha, in->max_tokens, static_cast<T*>(out), status);
+                       plan, plan_off, alpha, in->max_tokens, tiled, static_cast<T*>(out), status);
+  }
+  RTP_TRY(launched());
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (tiled) {
+      const int tiles_i = (in->max_tokens + kMergeTileRows - 1) / kMergeTileRows;
+      const int tiles_d = in->D / kMergeTileCols;
+      hipLaunchKernelGGL(k_merge_tiled, dim3(tiles_i * tiles_d, in->B), dim3(kMergeTiledThreads), 0, s, tok,
+                         in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens, tiles_d,
+                         static_cast<bf16_t*>(out), status);
+    }
+  }
   return launched();
 }
 
 int launch_merge(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
                  const int32_t* out_off, const float* plan, const long long* plan_off, void* out,
-                 const int32_t* status, hipStream_t s) {
+                 int max_pruned_hint, const int32_t* status, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   return in->dtype == RTP_BF16
-             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, status, s)
-             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, status, s);
+             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, s)
+             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, s);
 }
 
 }  // namespace
@@ -639,7 +663,7 @@ extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(launch_norms(in, 0, RTP_METRIC_L2NORM, L, workspace, nullptr, s));
   // the kept counts live on the device: no host-side bound on the pruned sets
   return launch_ot(in, p, sel_idx, keep_counts, reinterpret_cast<const long long*>(plan_offsets), L,
-                   workspace, scores, plan, pair, -1, s);
+                   workspace, scores, plan, pair, kPrunedUnknown, s);
 }
 
 extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
@@ -651,7 +675,7 @@ extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(check_params(params, &p));
   if (!sel_idx || !keep_counts || !out_offsets || !plan || !plan_offsets || !out) return RTP_EINVAL;
   return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan,
-                      reinterpret_cast<const long long*>(plan_offsets), out, nullptr,
+                      reinterpret_cast<const long long*>(plan_offsets), out, kPrunedUnknown, nullptr,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -677,10 +701,10 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
   RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s));
   // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image
-  const int max_pruned = p.dynamic ? -1
+  const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
-  return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, status, s);
+  return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status, s);
 }
 
 extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* density,
@@ -726,11 +750,11 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   RTP_TRY(launch_scan(in, keep, nullptr, plan_off, status, s));
   hipLaunchKernelGGL(k_splice_scan, dim3(1), dim3(256), 0, s, t, keep, in->B, seq_offsets, visual_start, status);
   RTP_TRY(launched());
-  const int max_pruned = p.dynamic ? -1
+  const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
   // the merge writes image b's kept rows at visual_start[b], between its text spans
-  RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, status, s));
+  RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status, s));
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SPLICE, s);
   const dim3 grid(64, in->B);

@@ -34,7 +34,6 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 #endif
 constexpr int kMfmaRowsPerWave = RTP_MFMA_ROWS_PER_WAVE;   // MT tiles of 16 kept rows
 constexpr int kMfmaWaves = RTP_MFMA_WAVES;
-constexpr int kTiledMinPruned = 192;   // images with more pruned tokens take k_scores_tiled
 
 // Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
 // the kernel below), chosen on the host from the largest pruned set the call

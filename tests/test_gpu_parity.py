@@ -291,6 +291,27 @@ def test_explicit_keep_counts():
     assert list(s["keep"]) == [10, 50, 12]          # clamped to N
 
 
+def test_explicit_keep_counts_override_the_dynamic_bound():
+    """Kept counts given by the caller can prune far more than the dynamic clamp
+    would allow: the staged calls must not size anything from that clamp."""
+    batch = synth.gen_batch(3, images=range(2))          # 400 tokens, dynamic parameters
+    keep_in = [120, 150]                                 # 280 and 250 pruned tokens
+    s = hz.run_staged(batch, keep_counts_in=keep_in)
+    assert list(s["keep"][:2]) == keep_in
+    p = orc.Params.from_dict(batch.params)
+    for b in range(2):
+        lo, hi = int(batch.offsets[b]), int(batch.offsets[b + 1])
+        ref = orc.prune_image(orc.widen(batch.tokens[lo:hi], batch.dtype), float(batch.density[b]), p,
+                              keep_count=keep_in[b])
+        np.testing.assert_array_equal(s["sel"][lo:lo + keep_in[b]], ref.kept)
+        po = int(s["plan_offsets"][b])
+        S_g = s["scores"][po:po + ref.m * ref.r].reshape(ref.m, ref.r)
+        assert np.abs(S_g - ref.S).max() <= hz.SCORE_ATOL
+        o0 = int(s["out_offsets"][b])
+        got = synth.bf16_bits_to_f32(s["out"][o0:o0 + ref.m]).astype(np.float64)
+        assert np.abs(got - ref.merged).max() <= 0.5 * 2.0 ** -7 * np.abs(ref.merged).max() + 1e-6
+
+
 def test_largest_supported_image():
     batch = _random_batch([8192], 64, "bf16", seed=9, ratio=0.97, iters=3)
     f = hz.run_prune(batch)
