@@ -80,6 +80,10 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
         nbytes = tok_bytes + float(m.sum()) * d * elt + 4.0 * float((m * r).sum())
         flops = 2.0 * float((m * r).sum()) * d
         if flops / nbytes > FP32_VECTOR_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            if elt == 2 and d % 128 == 0:
+                # large pruned sets go to the matrix cores (useful flops: the plan's two bf16
+                # terms double the executed ones)
+                return "mfma", flops, "TFLOP/s", BF16_MFMA_TFLOPS
             return "alu", flops, "TFLOP/s", FP32_VECTOR_TFLOPS
         return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
     if kernel == "k_scores":
