@@ -271,7 +271,10 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
   const int32_t* st = at<int32_t>(ws, L.status);
   ProfScope prof(KID_SCORES, s);
   if constexpr (std::is_same<T, bf16_t>::value) {
-    if (in->D % 128 == 0) {
+    // matrix-core path: its 32-term fp32 partial sums leave an error of about
+    // 6e-8 sqrt(32 / D) of the cosine, which the pairing's near-tie band covers from
+    // D = 1024 up; narrower tokens take the fp64 vector kernel.
+    if (in->D % 128 == 0 && in->D >= kMfmaMinWidth) {
       // matrix-core path.  With a fixed retention the pruned-set size is known up
       // to rounding; with the dynamic ratio it is usually a few percent of the
       // image, so the leanest shape is used and larger sets take several passes.

@@ -34,6 +34,7 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 #endif
 constexpr int kMfmaRowsPerWave = RTP_MFMA_ROWS_PER_WAVE;   // MT tiles of 16 kept rows
 constexpr int kMfmaWaves = RTP_MFMA_WAVES;
+constexpr int kMfmaMinWidth = 1024;   // token widths below this take the fp64 vector score kernel
 
 // Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
 // the kernel below), chosen on the host from the largest pruned set the call

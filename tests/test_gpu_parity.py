@@ -143,6 +143,68 @@ def test_large_pages(cfg, images, kept):
     assert rep2.max_score_abs <= hz.SCORE_ATOL
 
 
+def _clustered(counts, d, dtype, seed, **params):
+    """Small clustered images (near-duplicates exist, so stage 2 has something to do)."""
+    rng = np.random.default_rng(seed)
+    imgs = []
+    for c in counts:
+        k = max(2, c // 12)
+        centres = rng.standard_normal((k, d))
+        centres /= np.linalg.norm(centres, axis=1, keepdims=True)
+        x = centres[rng.integers(0, k, size=c)] + rng.standard_normal((c, d)) * (0.2 / np.sqrt(d))
+        x *= rng.lognormal(0, 0.3, size=(c, 1))
+        imgs.append(x.astype(np.float32))
+    dens = rng.uniform(0.1, 0.9, len(counts)).astype(np.float32)
+    p = dict(synth.DEFAULT_PARAMS, iters=30)
+    p.update(params)
+    return synth.pack(0, dtype, imgs, dens, p)
+
+
+@pytest.mark.parametrize("override", [
+    dict(ratio=0.9),                     # tall and narrow: more kept tokens than a workgroup's registers hold
+    dict(ratio=0.9, iters=0),
+    dict(ratio=0.9, iters=1),
+    dict(ratio=0.995),                   # a handful of pruned tokens per image (fewer than eight columns)
+    dict(ratio=0.6, eps=1.0),            # wide pruned sets, the literal Appendix C
+    dict(ratio=0.6, eps=0.02),           # exp range beyond fp32: the kernel matrix stays fp64
+    dict(ratio=0.6, z=1.0),
+    dict(ratio=0.45, alpha=0.5),         # more pruned than kept
+])
+def test_multi_workgroup_sinkhorn_variants(override):
+    """Images beyond the register-resident shapes (600-900 tokens), bf16 width 1024."""
+    batch = _clustered([600, 777, 900, 64, 513], 1024, "bf16", 21, **override)
+    f = hz.run_prune(batch)
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"sweep {override}")
+    s = hz.run_staged(batch)
+    rep2 = hz.compare_batch(batch, s, staged=True)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 72), ("bf16", 256), ("f32", 1280)])
+def test_multi_workgroup_sinkhorn_other_widths(dtype, d):
+    """The same images through the general score and merge kernels (fp32 tokens, odd widths)."""
+    batch = _clustered([640, 530], d, dtype, 22, ratio=0.7)
+    f = hz.run_prune(batch)
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"sweep {dtype} D={d}")
+
+
+@pytest.mark.parametrize("counts,ratio", [([260], 0.25), ([200, 7 + 193], 0.0174), ([321, 450], 0.4)])
+def test_matrix_core_tiles_at_their_edges(counts, ratio):
+    """Pruned sets just above the tiled kernels' threshold, tiles cut by both edges."""
+    batch = _clustered(counts, 1024, "bf16", 23, ratio=ratio, iters=10)
+    s = hz.run_staged(batch)
+    rep = hz.compare_batch(batch, s, staged=True)
+    _log(rep, f"tiles {counts} {ratio}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+    f = hz.run_prune(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+
+
 # ------------------------------------------------------------------ parameter sweeps
 @pytest.mark.parametrize("override", [
     dict(eps=1.0, iters=100),           # the literal text of Appendix C
