@@ -234,9 +234,15 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SELECT, s);
   const size_t lds = 9 * static_cast<size_t>((in->max_tokens + 1) & ~1);   // 8-byte key + flag per token
-  hipLaunchKernelGGL(k_select, dim3(in->B), dim3(256), lds, s, in->offsets, in->D, p, density, keep_in,
-                     at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
-                     in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+  // long images: the rank counting is quadratic in the token count, so the workgroup grows with it
+  if (in->max_tokens > 2048)
+    hipLaunchKernelGGL(k_select<1024>, dim3(in->B), dim3(1024), lds, s, in->offsets, in->D, p, density, keep_in,
+                       at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
+                       in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+  else
+    hipLaunchKernelGGL(k_select<256>, dim3(in->B), dim3(256), lds, s, in->offsets, in->D, p, density, keep_in,
+                       at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
+                       in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
   return launched();
 }
 

@@ -263,7 +263,8 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
 // of token k is the number of tokens that precede it in (score descending,
 // index ascending) order; it is kept iff rank < M.  Kept and pruned indices
 // are then written in ascending order.
-__global__ __launch_bounds__(256) void k_select(
+template <int NT>
+__global__ __launch_bounds__(NT) void k_select(
     const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
     const int32_t* __restrict__ keep_in, const float* __restrict__ score,
     const double* __restrict__ partial, int chunks_per_image, int do_select, int max_tokens,
@@ -274,8 +275,8 @@ __global__ __launch_bounds__(256) void k_select(
   extern __shared__ __attribute__((aligned(16))) unsigned char select_lds[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(select_lds);
   unsigned char* kept_flag = select_lds + 8 * static_cast<size_t>((max_tokens + 1) & ~1);
-  __shared__ double red[4];
-  __shared__ int counts[256];
+  __shared__ double red[NT / 64];
+  __shared__ int counts[NT];
   __shared__ int s_m;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int lo = offsets[b];
@@ -288,12 +289,12 @@ __global__ __launch_bounds__(256) void k_select(
       const int nchunks = (n + kNormRowsPerChunk - 1) / kNormRowsPerChunk;
       const double* base = partial + static_cast<size_t>(b) * chunks_per_image * (D + 1);
       double local = 0.0;
-      for (int d = tid; d < D; d += 256) {
+      for (int d = tid; d < D; d += NT) {
         double s = 0.0;
         for (int c = 0; c < nchunks; ++c) s += base[static_cast<size_t>(c) * (D + 1) + d];
         local = fma(s, s, local);
       }
-      const double ss = block_sum<256>(local, red);
+      const double ss = block_sum<NT>(local, red);
       double w = 0.0;
       for (int c = 0; c < nchunks; ++c) w += base[static_cast<size_t>(c) * (D + 1) + D];
       phi = (ss - w) / (static_cast<double>(n) * static_cast<double>(n - 1));
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(256) void k_select(
   // 64-bit key = (score bits, ~index): token l precedes token k in (score
   // descending, index ascending) order exactly when key_l > key_k.
   const int n_pad = (n + 1) & ~1;
-  for (int k = tid; k < n_pad; k += 256)
+  for (int k = tid; k < n_pad; k += NT)
     keys[k] = k < n ? (static_cast<unsigned long long>(__float_as_uint(score[lo + k])) << 32) |
                           (0xffffffffu - static_cast<uint32_t>(k))
                     : 0ull;                                   // padding precedes nothing
@@ -325,12 +326,12 @@ __global__ __launch_bounds__(256) void k_select(
   const int m = s_m;
 
   const ulonglong2* keys2 = reinterpret_cast<const ulonglong2*>(keys);
-  for (int kb = tid; kb < n; kb += 4 * 256) {
+  for (int kb = tid; kb < n; kb += 4 * NT) {
     unsigned long long mine[4];
     int rank[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      mine[u] = keys[min(kb + 256 * u, n - 1)];
+      mine[u] = keys[min(kb + NT * u, n - 1)];
       rank[u] = 0;
     }
     for (int l2 = 0; l2 < n_pad / 2; ++l2) {
@@ -340,19 +341,19 @@ __global__ __launch_bounds__(256) void k_select(
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (kb + 256 * u < n) kept_flag[kb + 256 * u] = rank[u] < m;
+      if (kb + NT * u < n) kept_flag[kb + NT * u] = rank[u] < m;
   }
   __syncthreads();
 
   // Each thread owns a contiguous span of tokens; exclusive scan of the spans'
   // kept counts gives every token its position in the ascending kept / pruned lists.
-  const int span = (n + 255) / 256;
+  const int span = (n + NT - 1) / NT;
   const int k0 = min(n, tid * span), k1 = min(n, k0 + span);
   int c = 0;
   for (int k = k0; k < k1; ++k) c += kept_flag[k];
   counts[tid] = c;
   __syncthreads();
-  for (int o = 1; o < 256; o <<= 1) {
+  for (int o = 1; o < NT; o <<= 1) {
     const int v = tid >= o ? counts[tid - o] : 0;
     __syncthreads();
     counts[tid] += v;
