@@ -360,7 +360,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     const dim3 grows(strips, in->B), gcols(cols, in->B);
     hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColThreads), 0, s, A, st);
     // columns per thread: enough for the largest pruned set the batch can hold
-    const int rmax = std::min(max_pruned_hint >= 0 ? max_pruned_hint : in->max_tokens - 1, kSweepMaxR);
+    const int rmax = std::min(pruned_bound(in, p, max_pruned_hint), kSweepMaxR);
     const int ch = (std::max(rmax, 1) + kSweepThreads - 1) / kSweepThreads;
     auto rows = [&](auto final_tag, int parity) {
       constexpr bool kFinal = decltype(final_tag)::value;
