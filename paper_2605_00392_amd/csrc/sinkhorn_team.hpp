@@ -75,10 +75,13 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
   if (WaveShape::fits(m, r)) return kVariantA;
   if (PairShape::fits(m, r)) return kVariantPair;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
+  // when the sweep kernels run anyway (their launches are paid for) they also
+  // take the images of the slowest register shapes, which otherwise set the
+  // duration of the register-resident launch
+  if (sweep && r <= kSweepMaxPruned) return kVariantSweep;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if (TeamC::fits(m, r)) return kVariantC;
-  if (sweep && r <= kSweepMaxPruned) return kVariantSweep;
   return kGeneralVariant;
 }
 
