@@ -253,15 +253,21 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     rt.rtprune_profile_enable(1)
+    # one event pair per step on the launch stream (torch's current stream): median and
+    # minimum of the steps beside the wall-clock mean
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     rc, prof = rt.rtprune_profile_summary()
     rt.rtprune_profile_enable(0)
     rt.check(rc)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     status = int(ws[:4].view(torch.int32).item())
     assert status == 0, f"device status {status}"
     # one plain copy of the input's size, outside the timed region: the
@@ -350,6 +356,8 @@ def main() -> int:
         "kept_tokens": int(keep_h.sum()),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4) if per_step else None,
+        "ms_per_step_min": round(per_step[0], 4) if per_step else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": w.name, "images": B, "total_tokens": int(total), "D": D,
