@@ -144,7 +144,7 @@ def bench_density(rt, torch, steps: int, unique: int = 16, copies: int = 16):
     assert all(got[i] == want[i] for i in range(len(want))), "text density differs from the oracle"
     return {"pages": B, "page": f"{side}x{side}x3 u8", "ms_per_call": round(ms, 4),
             "pages_per_s": round(B / (ms * 1e-3), 1),
-            "kernel": "k_density_sobel", "kernel_ms": None if sobel is None else round(sobel, 4),
+            "kernel": "k_density_sobel (register-window variant for 64-pixel patches)", "kernel_ms": None if sobel is None else round(sobel, 4),
             "bound": "hbm", "achieved_GBs": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9, 1),
             "peak_GBs": HBM_PEAK_GBS,
             "frac": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

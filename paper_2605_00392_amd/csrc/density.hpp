@@ -150,6 +150,112 @@ __global__ __launch_bounds__(kDensityThreads) void k_density_sobel(
     if (pcount[i]) atomicAdd(&counts[static_cast<long long>(b) * patches_max + prow * pcols + i], pcount[i]);
 }
 
+// The same count without LDS, for patch widths that are a multiple of four (every
+// native mode: 64 x 64 pixels per token).  A wave walks one patch row of a
+// 248-column band: lane l owns the four columns 4 (g0 - 1 + l) .. + 3, reads its
+// 12 bytes of each image row straight from memory (three dwords; byte by byte
+// when the image does not start on a 4-byte boundary), forms the four lumas and
+// gets the two neighbouring columns from the adjacent lanes; lanes 0 and 63 only
+// serve as those neighbours.  The three-row window slides down in registers, the
+// loads of the next rows are issued four rows ahead.
+constexpr int kDensityBand = 62;          // column groups a wave produces
+constexpr int kDensityAhead = 4;          // rows in flight
+
+__global__ __launch_bounds__(256) void k_density_rows(
+    const unsigned char* __restrict__ pixels, const long long* __restrict__ pixel_offsets,
+    const int32_t* __restrict__ heights, const int32_t* __restrict__ widths, int patch_h, int patch_w,
+    int patches_max, float thr2_lo, float thr2_hi, double thr2, int32_t* __restrict__ counts,
+    const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.z;
+  const int h = heights[b], w = widths[b];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ngroups = w >> 2;                           // w is a multiple of patch_w, hence of 4
+  const int g0 = (blockIdx.x * 4 + wave) * kDensityBand;
+  const int y0 = blockIdx.y * patch_h;
+  if (g0 >= ngroups || y0 >= h) return;                 // uniform over the wave
+  const unsigned char* img = pixels + pixel_offsets[b];
+  const bool aligned = (reinterpret_cast<uintptr_t>(img) & 3u) == 0;
+  const int gl = g0 - 1 + lane;                         // this lane's column group (may lie outside)
+  const int gc = min(max(gl, 0), ngroups - 1);
+  const bool produces = lane >= 1 && lane <= kDensityBand && gl < ngroups;
+  const size_t pitch = static_cast<size_t>(3) * w;
+  const int nrows = patch_h + 2;                        // rows y0 - 1 .. y0 + patch_h, clamped into the image
+
+  auto load_row = [&](int k, uint32_t (&d)[3]) {
+    const int y = min(max(y0 - 1 + min(k, nrows - 1), 0), h - 1);
+    const unsigned char* p = img + y * pitch + 12 * static_cast<size_t>(gc);
+    if (aligned) {
+      const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+      d[0] = q[0]; d[1] = q[1]; d[2] = q[2];
+    } else {
+#pragma unroll
+      for (int t = 0; t < 3; ++t)
+        d[t] = p[4 * t] | (static_cast<uint32_t>(p[4 * t + 1]) << 8) | (static_cast<uint32_t>(p[4 * t + 2]) << 16) |
+               (static_cast<uint32_t>(p[4 * t + 3]) << 24);
+    }
+  };
+  // horizontal Sobel parts of one image row for the lane's four columns
+  auto row_parts = [&](const uint32_t (&d)[3], int (&hd)[4], int (&hs)[4]) {
+    int g[6];
+    g[1] = luma_milli(d[0] & 255u, (d[0] >> 8) & 255u, (d[0] >> 16) & 255u);
+    g[2] = luma_milli(d[0] >> 24, d[1] & 255u, (d[1] >> 8) & 255u);
+    g[3] = luma_milli((d[1] >> 16) & 255u, d[1] >> 24, d[2] & 255u);
+    g[4] = luma_milli((d[2] >> 8) & 255u, (d[2] >> 16) & 255u, d[2] >> 24);
+    const int from_left = __shfl_up(g[4], 1, 64), from_right = __shfl_down(g[1], 1, 64);
+    g[0] = gl <= 0 ? g[1] : from_left;                  // the image border repeats its pixel
+    g[5] = gl >= ngroups - 1 ? g[4] : from_right;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      hd[c] = g[c + 2] - g[c];
+      hs[c] = g[c] + 2 * g[c + 1] + g[c + 2];
+    }
+  };
+
+  uint32_t ring[kDensityAhead][3];
+#pragma unroll
+  for (int k = 0; k < kDensityAhead; ++k) load_row(k, ring[k]);
+  int hd0[4], hs0[4], hd1[4], hs1[4];
+  int active = 0;
+  // rows are taken four at a time so that the ring is indexed statically
+  for (int kb = 0; kb < nrows; kb += kDensityAhead) {
+#pragma unroll
+    for (int u = 0; u < kDensityAhead; ++u) {
+      const int k = kb + u;
+      uint32_t cur[3] = {ring[u][0], ring[u][1], ring[u][2]};
+      load_row(k + kDensityAhead, ring[u]);             // clamped: always a valid row
+      int hd2[4], hs2[4];
+      row_parts(cur, hd2, hs2);                         // every lane, also past the last row (shuffles)
+      if (k >= 2 && k < nrows && y0 + (k - 2) < h) {    // output row y0 + k - 2 has its three rows
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int gx = hd0[c] + 2 * hd1[c] + hd2[c];
+          const int gy = hs0[c] - hs2[c];
+          const float fx = static_cast<float>(gx), fy = static_cast<float>(gy);
+          const float f = fmaf(fx, fx, fy * fy);
+          bool on;
+          if (f > thr2_hi) on = true;
+          else if (f < thr2_lo) on = false;
+          else {
+            const double dx = static_cast<double>(gx), dy = static_cast<double>(gy);
+            on = (dx * dx + dy * dy) >= thr2;
+          }
+          active += on ? 1 : 0;
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        hd0[c] = hd1[c]; hs0[c] = hs1[c];
+        hd1[c] = hd2[c]; hs1[c] = hs2[c];
+      }
+    }
+  }
+  if (produces && active) {
+    const int pcols = w / patch_w;
+    atomicAdd(&counts[static_cast<long long>(b) * patches_max + blockIdx.y * pcols + (4 * gl) / patch_w], active);
+  }
+}
+
 // rho_k = count_k / (patch area) and rho = mean over patches, one workgroup per image.
 __global__ __launch_bounds__(256) void k_density_finish(
     const int32_t* __restrict__ heights, const int32_t* __restrict__ widths, int patch_h, int patch_w,

@@ -599,9 +599,17 @@ extern "C" int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_
     const double thr2 = t * t;
     const float lo = static_cast<float>(thr2 * (1.0 - 2e-6)), hi = static_cast<float>(thr2 * (1.0 + 2e-6));
     ProfScope prof(KID_DENSITY_SOBEL, s);
-    hipLaunchKernelGGL(k_density_sobel, dim3((max_height + strip - 1) / strip, B), dim3(kDensityThreads), lds, s,
-                       pixels, poff, heights, widths, strip, patch_h, patch_w, L.patches_max, lo, hi, thr2,
-                       counts, status);
+    if (patch_w % 4 == 0) {
+      // register-window kernel: a wave per 248-column band and patch row
+      const int bands = ((max_width / 4) + kDensityBand - 1) / kDensityBand;
+      hipLaunchKernelGGL(k_density_rows, dim3((bands + 3) / 4, (max_height + patch_h - 1) / patch_h, B), dim3(256), 0,
+                         s, pixels, poff, heights, widths, patch_h, patch_w, L.patches_max, lo, hi, thr2, counts,
+                         status);
+    } else {
+      hipLaunchKernelGGL(k_density_sobel, dim3((max_height + strip - 1) / strip, B), dim3(kDensityThreads), lds, s,
+                         pixels, poff, heights, widths, strip, patch_h, patch_w, L.patches_max, lo, hi, thr2,
+                         counts, status);
+    }
     RTP_TRY(launched());
   }
   ProfScope prof(KID_DENSITY_FINISH, s);
