@@ -54,6 +54,10 @@ __global__ __launch_bounds__(256) void k_density_prepare(
   if (threadIdx.x == 0) status[0] = bad;
 }
 
+// Byte N of a dword as fp32 (the compiler folds the extraction into v_cvt_f32_ubyteN).
+template <int N>
+__device__ __forceinline__ float byte_f32(uint32_t d) { return static_cast<float>((d >> (8 * N)) & 255u); }
+
 __device__ __forceinline__ int luma_milli(uint32_t r, uint32_t g, uint32_t b) {
   return static_cast<int>(299u * r + 587u * g + 114u * b);
 }
@@ -157,9 +161,10 @@ __global__ __launch_bounds__(kDensityThreads) void k_density_sobel(
 // when the image does not start on a 4-byte boundary), forms the four lumas and
 // gets the two neighbouring columns from the adjacent lanes; lanes 0 and 63 only
 // serve as those neighbours.  The three-row window slides down in registers, the
-// loads of the next rows are issued four rows ahead.
+// loads of the next rows are issued six rows ahead.
 constexpr int kDensityBand = 62;          // column groups a wave produces
-constexpr int kDensityAhead = 4;          // rows in flight
+constexpr int kDensityAhead = 6;          // rows in flight; a multiple of 3, so the three-row window
+                                          // rotates through statically named registers
 
 __global__ __launch_bounds__(256) void k_density_rows(
     const unsigned char* __restrict__ pixels, const long long* __restrict__ pixel_offsets,
@@ -195,58 +200,68 @@ __global__ __launch_bounds__(256) void k_density_rows(
                (static_cast<uint32_t>(p[4 * t + 3]) << 24);
     }
   };
-  // horizontal Sobel parts of one image row for the lane's four columns
-  auto row_parts = [&](const uint32_t (&d)[3], int (&hd)[4], int (&hs)[4]) {
-    int g[6];
-    g[1] = luma_milli(d[0] & 255u, (d[0] >> 8) & 255u, (d[0] >> 16) & 255u);
-    g[2] = luma_milli(d[0] >> 24, d[1] & 255u, (d[1] >> 8) & 255u);
-    g[3] = luma_milli((d[1] >> 16) & 255u, d[1] >> 24, d[2] & 255u);
-    g[4] = luma_milli((d[2] >> 8) & 255u, (d[2] >> 16) & 255u, d[2] >> 24);
-    const int from_left = __shfl_up(g[4], 1, 64), from_right = __shfl_down(g[1], 1, 64);
+  // Horizontal Sobel parts of one image row for the lane's four columns.  All in
+  // fp32: bytes are converted directly (v_cvt_f32_ubyte), and every value here is
+  // an integer below 2^24 (luma <= 255000, Sobel sums <= 4 x that), so the
+  // arithmetic is exact and equals the integer definition.
+  auto luma = [](float r, float g, float bl) { return fmaf(299.f, r, fmaf(587.f, g, 114.f * bl)); };
+  auto row_parts = [&](const uint32_t (&d)[3], float (&hd)[4], float (&hs)[4]) {
+    float g[6];
+    g[1] = luma(byte_f32<0>(d[0]), byte_f32<1>(d[0]),
+                byte_f32<2>(d[0]));
+    g[2] = luma(byte_f32<3>(d[0]), byte_f32<0>(d[1]),
+                byte_f32<1>(d[1]));
+    g[3] = luma(byte_f32<2>(d[1]), byte_f32<3>(d[1]),
+                byte_f32<0>(d[2]));
+    g[4] = luma(byte_f32<1>(d[2]), byte_f32<2>(d[2]),
+                byte_f32<3>(d[2]));
+    const float from_left = __shfl_up(g[4], 1, 64), from_right = __shfl_down(g[1], 1, 64);
     g[0] = gl <= 0 ? g[1] : from_left;                  // the image border repeats its pixel
     g[5] = gl >= ngroups - 1 ? g[4] : from_right;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       hd[c] = g[c + 2] - g[c];
-      hs[c] = g[c] + 2 * g[c + 1] + g[c + 2];
+      hs[c] = fmaf(2.f, g[c + 1], g[c]) + g[c + 2];
     }
   };
 
   uint32_t ring[kDensityAhead][3];
 #pragma unroll
   for (int k = 0; k < kDensityAhead; ++k) load_row(k, ring[k]);
-  int hd0[4], hs0[4], hd1[4], hs1[4];
+  float hd[3][4], hs[3][4];                             // window: row k sits in slot k % 3
   int active = 0;
-  // rows are taken four at a time so that the ring is indexed statically
+  // rows are taken six at a time so that ring and window are indexed statically
   for (int kb = 0; kb < nrows; kb += kDensityAhead) {
 #pragma unroll
     for (int u = 0; u < kDensityAhead; ++u) {
       const int k = kb + u;
-      uint32_t cur[3] = {ring[u][0], ring[u][1], ring[u][2]};
+      constexpr int kSlots = 3;
+      const int s2 = u % kSlots, s1 = (u + 2) % kSlots, s0 = (u + 1) % kSlots;   // rows k, k - 1, k - 2
+      row_parts(ring[u], hd[s2], hs[s2]);               // every lane, also past the last row (shuffles)
       load_row(k + kDensityAhead, ring[u]);             // clamped: always a valid row
-      int hd2[4], hs2[4];
-      row_parts(cur, hd2, hs2);                         // every lane, also past the last row (shuffles)
       if (k >= 2 && k < nrows && y0 + (k - 2) < h) {    // output row y0 + k - 2 has its three rows
+        float gx[4], gy[4];
+        bool unsure = false;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const int gx = hd0[c] + 2 * hd1[c] + hd2[c];
-          const int gy = hs0[c] - hs2[c];
-          const float fx = static_cast<float>(gx), fy = static_cast<float>(gy);
+          gx[c] = fmaf(2.f, hd[s1][c], hd[s0][c]) + hd[s2][c];
+          gy[c] = hs[s0][c] - hs[s2][c];
+          const float fx = gx[c], fy = gy[c];
           const float f = fmaf(fx, fx, fy * fy);
-          bool on;
-          if (f > thr2_hi) on = true;
-          else if (f < thr2_lo) on = false;
-          else {
-            const double dx = static_cast<double>(gx), dy = static_cast<double>(gy);
-            on = (dx * dx + dy * dy) >= thr2;
-          }
-          active += on ? 1 : 0;
+          active += f > thr2_hi ? 1 : 0;
+          unsure = unsure || (!(f > thr2_hi) && !(f < thr2_lo));
         }
-      }
+        if (unsure) {                                   // within 2e-6 of the threshold: exact, in fp64
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        hd0[c] = hd1[c]; hs0[c] = hs1[c];
-        hd1[c] = hd2[c]; hs1[c] = hs2[c];
+          for (int c = 0; c < 4; ++c) {
+            const float fx = gx[c], fy = gy[c];
+            const float f = fmaf(fx, fx, fy * fy);
+            if (!(f > thr2_hi) && !(f < thr2_lo)) {
+              const double dx = static_cast<double>(gx[c]), dy = static_cast<double>(gy[c]);
+              active += (dx * dx + dy * dy) >= thr2 ? 1 : 0;
+            }
+          }
+        }
       }
     }
   }
