@@ -85,6 +85,8 @@ __device__ __forceinline__ void unpack4(const float4& u, float (&x)[4]) {
 // Make the compiler forget where a register value came from (blocks common
 // subexpression elimination across the call; emits no instruction).
 __device__ __forceinline__ void forget_origin(uint2& u) { asm volatile("" : "+v"(u.x), "+v"(u.y)); }
+__device__ __forceinline__ void forget_origin(float& u) { asm volatile("" : "+v"(u)); }
+__device__ __forceinline__ void forget_origin(double& u) { asm volatile("" : "+v"(u)); }
 __device__ __forceinline__ void forget_origin(float4& u) {
   asm volatile("" : "+v"(u.x), "+v"(u.y), "+v"(u.z), "+v"(u.w));
 }

@@ -185,23 +185,30 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
     }
     __syncthreads();
     if (strip >= nstrips) return;
-    double xa[kSweepRows];
+    // the strip's x are read from LDS row by row (every lane the same address)
+    // rather than held: registers decide how many workgroups share a CU
+    double share[CH * VEC], xsum = 0.0;
 #pragma unroll
-    for (int a = 0; a < kSweepRows; ++a) xa[a] = xs[rg][a];
-    if (ct == 0) {
-      double t = 0.0;
+    for (int cv = 0; cv < CH * VEC; ++cv) share[cv] = 0.0;
+    // widen the entries again here rather than keep their fp64 copies of the row
+    // sums alive (twice the registers)
 #pragma unroll
-      for (int a = 0; a < kSweepRows; ++a) t += xa[a];
-      A.xpart[I.lo + strip] = t;
+    for (int a = 0; a < kSweepRows; ++a)
+#pragma unroll
+      for (int cv = 0; cv < CH * VEC; ++cv) forget_origin(K[a][cv]);
+#pragma unroll
+    for (int a = 0; a < kSweepRows; ++a) {
+      const double xa = xs[rg][a];
+      xsum += xa;
+#pragma unroll
+      for (int cv = 0; cv < CH * VEC; ++cv) share[cv] = fma(static_cast<double>(K[a][cv]), xa, share[cv]);
     }
+    if (ct == 0) A.xpart[I.lo + strip] = xsum;
     double* out = A.colpart + strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
     for (int cv = 0; cv < CH * VEC; ++cv) {
       const int j = column(cv);
-      double acc = 0.0;
-#pragma unroll
-      for (int a = 0; a < kSweepRows; ++a) acc = fma(static_cast<double>(K[a][cv]), xa[a], acc);
-      if (j < r) out[j] = acc;
+      if (j < r) out[j] = share[cv];
     }
   } else {
     if (tid < kSweepRows * RG) {
