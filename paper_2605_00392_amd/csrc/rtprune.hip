@@ -352,7 +352,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   if (L.sweep) {
     // large images: two launches per iteration over all of them, then plan and pairing
     SweepArgs A{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
-                at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<double>(ws, L.sw_colpart),
+                at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<void>(ws, L.sw_colpart),
                 at<double>(ws, L.sw_xpart), at<double>(ws, L.sw_ysum), at<double>(ws, L.sw_ydust),
                 at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair};
     const int strips = (in->max_tokens + kSweepRows - 1) / kSweepRows;
@@ -381,10 +381,11 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     };
     for (int it = 0; it < p.iters; ++it) {
       rows(std::false_type{}, it & 1);
-      hipLaunchKernelGGL((k_sweep_cols<false>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
+      if (p.k32) hipLaunchKernelGGL((k_sweep_cols<false, float>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
+      else hipLaunchKernelGGL((k_sweep_cols<false, double>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
     }
     rows(std::true_type{}, 0);
-    hipLaunchKernelGGL((k_sweep_cols<true>), gcols, dim3(kSweepColThreads), 0, s, A,
+    hipLaunchKernelGGL((k_sweep_cols<true, double>), gcols, dim3(kSweepColThreads), 0, s, A,
                        p.iters > 0 ? (p.iters - 1) & 1 : 0, p.iters == 0 ? 1 : 0, st);
   }
   return launched();

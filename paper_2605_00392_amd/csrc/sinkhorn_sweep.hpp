@@ -44,7 +44,8 @@ struct SweepArgs {
   long long plan_cap;
   double* x;        // [total] x of kept rank i of image b at offsets[b] + i
   double* y;        // [total] y of pruned rank j at offsets[b] + j
-  double* colpart;  // strips' column shares: image b, strip s, column j at strip_base(b) + s r + j
+  void* colpart;    // strips' column shares (stored like the kernel matrix: fp32 when p.k32, else fp64):
+                    // image b, strip s, column j at strip_base(b) + s r + j
   double* xpart;    // [total] strip sums of x at offsets[b] + strip
   double* ysum;     // [2][total] block sums of y at offsets[b] + block, by parity
   double* ydust;    // [2][B] by parity
@@ -204,11 +205,13 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
       for (int cv = 0; cv < CH * VEC; ++cv) share[cv] = fma(static_cast<double>(K[a][cv]), xa, share[cv]);
     }
     if (ct == 0) A.xpart[I.lo + strip] = xsum;
-    double* out = A.colpart + strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
+    // a share rounded to fp32 is off by 6e-8 of itself, so a column sum by at most
+    // that much: the same size as the rounding of the fp32 kernel matrix
+    KT* out = static_cast<KT*>(A.colpart) + strip_base(I.po, I.lo) + static_cast<long long>(strip) * r;
 #pragma unroll
     for (int cv = 0; cv < CH * VEC; ++cv) {
       const int j = column(cv);
-      if (j < r) out[j] = share[cv];
+      if (j < r) out[j] = static_cast<KT>(share[cv]);
     }
   } else {
     if (tid < kSweepRows * RG) {
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep_rows(SweepArgs A, int p
 // `parity`, writes those of parity ^ 1.
 // FINAL = true: the pairing - largest plan entry of each column over all strips
 // (the lowest row wins ties) against the dustbin row's entry.
-template <bool FINAL>
+template <bool FINAL, typename ST>
 __global__ __launch_bounds__(kSweepColThreads) void k_sweep_cols(SweepArgs A, int parity, int first,
                                                                 const int32_t* __restrict__ status) {
   if (status[0]) return;
@@ -301,13 +304,13 @@ __global__ __launch_bounds__(kSweepColThreads) void k_sweep_cols(SweepArgs A, in
 #pragma unroll
     for (int u = 0; u < 8; ++u) t[u] = 0.0;
     if (j < r) {
-      const double* cp = A.colpart + sb + j;
+      const ST* cp = static_cast<const ST*>(A.colpart) + sb + j;
       int s = g;
       for (; s + 7 * kSweepColGroups < nstrips; s += 8 * kSweepColGroups) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] += cp[static_cast<long long>(s + u * kSweepColGroups) * r];
+        for (int u = 0; u < 8; ++u) t[u] += static_cast<double>(cp[static_cast<long long>(s + u * kSweepColGroups) * r]);
       }
-      for (; s < nstrips; s += kSweepColGroups) t[0] += cp[static_cast<long long>(s) * r];
+      for (; s < nstrips; s += kSweepColGroups) t[0] += static_cast<double>(cp[static_cast<long long>(s) * r]);
     }
     part[g][lane] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
     __syncthreads();
