@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace rtp {
 
 constexpr int kWave = 64;
@@ -86,6 +88,7 @@ __device__ __forceinline__ void unpack4(const float4& u, float (&x)[4]) {
 // subexpression elimination across the call; emits no instruction).
 __device__ __forceinline__ void forget_origin(uint2& u) { asm volatile("" : "+v"(u.x), "+v"(u.y)); }
 __device__ __forceinline__ void forget_origin(float& u) { asm volatile("" : "+v"(u)); }
+__device__ __forceinline__ void forget_origin(int& u) { asm volatile("" : "+v"(u)); }
 __device__ __forceinline__ void forget_origin(double& u) { asm volatile("" : "+v"(u)); }
 __device__ __forceinline__ void forget_origin(float4& u) {
   asm volatile("" : "+v"(u.x), "+v"(u.y), "+v"(u.z), "+v"(u.w));
@@ -129,6 +132,55 @@ __device__ __forceinline__ double wave_sum_dpp(double v) {
     v = __hiloint2double(static_cast<int>(b[0]), static_cast<int>(a[0])) +
         __hiloint2double(static_cast<int>(b[1]), static_cast<int>(a[1]));
   }
+  return v;
+}
+// v + (the value of lane ^ MASK) for one lane bit.  Bits 0, 1 and 3 have an exact
+// register-to-register permutation (quad permutes, a rotation by 8 inside a row
+// of 16), bits 4 and 5 the swap instructions; bit 2 goes through the LDS crossbar.
+template <int MASK>
+__device__ __forceinline__ double add_xor_lane(double v) {
+  static_assert(MASK == 1 || MASK == 2 || MASK == 4 || MASK == 8 || MASK == 16 || MASK == 32, "one lane bit");
+  if constexpr (MASK == 1) return v + dpp_move<0xB1>(v);
+  else if constexpr (MASK == 2) return v + dpp_move<0x4E>(v);
+  else if constexpr (MASK == 4) return v + __shfl_xor(v, 4, kWave);
+  else if constexpr (MASK == 8) return v + dpp_move<0x128>(v);
+  else {
+    const unsigned lo = __double2loint(v), hi = __double2hiint(v);
+    if constexpr (MASK == 16) {
+      const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+      const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+      return __hiloint2double(static_cast<int>(b[0]), static_cast<int>(a[0])) +
+             __hiloint2double(static_cast<int>(b[1]), static_cast<int>(a[1]));
+    } else {
+      const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+      const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+      return __hiloint2double(static_cast<int>(b[0]), static_cast<int>(a[0])) +
+             __hiloint2double(static_cast<int>(b[1]), static_cast<int>(a[1]));
+    }
+  }
+}
+// Sum over each aligned group of 2^LOG lanes (every lane of the group gets it):
+// the first LOG steps of wave_sum_dpp, whose mirror steps rely on the lanes
+// below already agreeing.
+template <int LOG>
+__device__ __forceinline__ double group_sum(double v) {
+  if constexpr (LOG >= 1) v += dpp_move<0xB1>(v);
+  if constexpr (LOG >= 2) v += dpp_move<0x4E>(v);
+  if constexpr (LOG >= 3) v += dpp_move<0x141>(v);
+  if constexpr (LOG >= 4) v += dpp_move<0x140>(v);
+  if constexpr (LOG >= 5) v = add_xor_lane<16>(v);
+  if constexpr (LOG >= 6) v = add_xor_lane<32>(v);
+  return v;
+}
+// Sum over the lanes that share the low LOG lane bits (every one of them gets it).
+template <int LOG>
+__device__ __forceinline__ double cross_sum(double v) {
+  if constexpr (LOG <= 0) v = add_xor_lane<1>(v);
+  if constexpr (LOG <= 1) v = add_xor_lane<2>(v);
+  if constexpr (LOG <= 2) v = add_xor_lane<4>(v);
+  if constexpr (LOG <= 3) v = add_xor_lane<8>(v);
+  if constexpr (LOG <= 4) v = add_xor_lane<16>(v);
+  if constexpr (LOG <= 5) v = add_xor_lane<32>(v);
   return v;
 }
 // a + (the partner's b) on lanes whose bit is clear, (the partner's a) + b on

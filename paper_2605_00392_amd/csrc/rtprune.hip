@@ -327,8 +327,8 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
               int32_t* pair, int max_pruned_hint, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
-  p.sweep = L.sweep;
   p.k32 = p.k32 && L.sweep;
+  p.sweep = L.sweep ? (kSweepLaunched | (p.k32 ? kSweepF32 : 0)) : 0;
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
@@ -337,17 +337,18 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   int32_t* work = at<int32_t>(ws, L.work);
   {
     ProfScope prof(KID_CLASSIFY, s);
-    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, L.sweep, st);
+    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.sweep, st);
   }
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
     SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
     hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
+    if (L.sweep) hipLaunchKernelGGL(k_sinkhorn_tall, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
   }
   RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);
   hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
-                     L.plan_cap, plan, pair, 1, L.sweep, st);
+                     L.plan_cap, plan, pair, 1, p.sweep, st);
   RTP_TRY(launched());
   if (L.sweep) {
     // large images: two launches per iteration over all of them, then plan and pairing

@@ -359,15 +359,6 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   constexpr int kWavesPerBlock = kDualThreads / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int blk = blockIdx.x;
-#ifdef RTP_ONLY_ROLE   // timing aid: run one role only (0 = C, 1 = B, 2 = two-copy 48, 3 = one-wave, 4 = two-copy 32, 5 = two-wave)
-  {
-    const int n0 = work[kVariantC], n1 = work[kVariantB], n2 = work[kVariantDual48],
-              n3 = (work[kVariantA] + kWavesPerBlock - 1) / kWavesPerBlock, n4 = work[kVariantDual];
-    const int role = blk < n0 ? 0 : blk < n0 + n1 ? 1 : blk < n0 + n1 + n2 ? 2 : blk < n0 + n1 + n2 + n3 ? 3
-                     : blk < n0 + n1 + n2 + n3 + n4 ? 4 : 5;
-    if (role != RTP_ONLY_ROLE) return;
-  }
-#endif
   int cnt = work[kVariantC];
   if (blk < cnt) { sinkhorn_team_image<TeamC>(A, work[NV + kVariantC * B + blk], wave, lane); return; }
   blk -= cnt;
@@ -401,6 +392,23 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
     sinkhorn_waves_image<PairShape>(A, idx < nP ? work[NV + kVariantPair * B + idx] : -1, slot,
                                     wave % PairShape::kWaves, lane);
   }
+}
+
+// The tall shapes (more than 512 rows), one image per workgroup; launched only
+// for batches that can hold such images.  A kernel of its own so that its LDS
+// and registers do not count against the kernel above.
+__global__ __launch_bounds__(kDualThreads) void k_sinkhorn_tall(SinkhornArgs A,
+                                                               const int32_t* __restrict__ work, int B,
+                                                               const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  constexpr int NV = kWorkLists;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int blk = blockIdx.x;
+  int cnt = work[kVariantTeamTall];
+  if (blk < cnt) { sinkhorn_team_image<TeamTall, float>(A, work[NV + kVariantTeamTall * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantTall];
+  if (blk < cnt) sinkhorn_waves_image<TallShape>(A, work[NV + kVariantTall * B + blk], 0, wave, lane);
 }
 
 }  // namespace rtp

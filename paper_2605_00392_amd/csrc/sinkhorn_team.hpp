@@ -45,6 +45,10 @@ struct TeamShape {
 // to the general kernel (variant kGeneralVariant).
 using TeamB = TeamShape<8, 2, 4, 10>;    // M <= 512,  R <= 40
 using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
+// Tall images (tiled pages with a few pruned tokens): the kernel matrix is held
+// as fp32 values, which the same range condition as for the sweep kernels allows,
+// and widened at each use; all sums and both scaling vectors stay fp64.
+using TeamTall = TeamShape<8, 3, 19, 8>;  // M <= 1216, R <= 64
 // The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
 // lane, kCols augmented columns.
 struct WaveShape {
@@ -57,13 +61,22 @@ struct PairShape {
   static constexpr int kMaxRows = 64 * kWaves * kRows;
   __host__ __device__ static constexpr bool fits(int m, int r) { return m + 1 <= kMaxRows && r + 1 <= kCols; }
 };
+struct TallShape {   // a whole workgroup on one image
+  static constexpr int kWaves = 8, kRows = 3, kCols = 16;
+  static constexpr int kMaxRows = 64 * kWaves * kRows;
+  __host__ __device__ static constexpr bool fits(int m, int r) { return m + 1 <= kMaxRows && r + 1 <= kCols; }
+};
 constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 // The two-copy kernels (sinkhorn_dual.hpp) take M + 1 <= 512 and R + 1 <= 32
 // or R + 1 <= 48.
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
-              kVariantPair = 5, kVariantSweep = 6, kGeneralVariant = 7;
-constexpr int kWorkLists = 7;
+              kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kGeneralVariant = 9;
+constexpr int kWorkLists = 9;
+// `sweep` as the kernels receive it: bit 0, the call launches the sweep kernels
+// (the batch may hold images beyond the 512-row register shapes); bit 1, the
+// kernel matrix's range fits fp32.
+constexpr int kSweepLaunched = 1, kSweepF32 = 2;
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take what no register
 // shape fits, up to this many pruned tokens; they are only launched for batches
 // that can hold such images (`sweep`).
@@ -75,6 +88,8 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
   if (WaveShape::fits(m, r)) return kVariantA;
   if (PairShape::fits(m, r)) return kVariantPair;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
+  if (sweep && TallShape::fits(m, r)) return kVariantTall;
+  if ((sweep & kSweepF32) && TeamTall::fits(m, r)) return kVariantTeamTall;
   // when the sweep kernels run anyway (their launches are paid for) they also
   // take the images of the slowest register shapes, which otherwise set the
   // duration of the register-resident launch
@@ -120,7 +135,7 @@ struct SinkhornArgs {
 
 // One image on one team.  `tw` is the wave's index inside the team, `lane` the
 // lane; every wave of the team calls this with the same `b`.
-template <typename S>
+template <typename S, typename KT = double>
 __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b, int tw, int lane) {
   constexpr int W = S::W, TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T;
   constexpr int LOG_TC = S::LOG_TC;
@@ -146,15 +161,33 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
   const int cslot = tt & (TC - 1);
   const int rslot = tt >> LOG_TC;
 
-  double K[RPT][CPT];
+  // KT = float: the registers hold rounded entries, widened again at each use
+  // (the compiler must not keep the widened copies, hence `forget_origin`)
+  constexpr bool kNarrow = std::is_same<KT, float>::value;
+  KT K[RPT][CPT];
+  // Loads are unconditional (from a clamped position), so that a thread's loads
+  // overlap instead of each waiting inside its own branch; they go four rows at
+  // a time, and with KT = float each group is narrowed before the next is
+  // requested, so that the loads in flight need no more registers than the matrix.
 #pragma unroll
-  for (int a = 0; a < RPT; ++a) {
-    const int i = rslot + TR * a;
+  for (int a0 = 0; a0 < RPT; a0 += 4) {
+    double v[4][CPT];
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int j = cslot + TC * c;
-      K[a][c] = (i < m && j < r) ? Kg[static_cast<long long>(i) * r + j] : 0.0;
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(rslot + TR * (a0 + u), m - 1);
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * r + min(cslot + TC * c, r - 1)];
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+        if (a0 + u < RPT) {
+          KT k = (rslot + TR * (a0 + u) < m && cslot + TC * c < r) ? static_cast<KT>(v[u][c]) : KT(0);
+          if constexpr (kNarrow) forget_origin(k);
+          K[a0 + u][c] = k;
+        }
   }
 
   const double kz = exp((p.z - p.shift) / p.eps);
@@ -170,49 +203,76 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
   __shared__ double xw[W > 1 ? W : 1][TC][CPT + 1];
   __shared__ double xtot[TC][CPT + 1];
 
-  for (int it = 0; it < p.iters; ++it) {
-    // ---- u-update ----
-    double s[RPT];
+  // KT = float: the latest x, one value per row, kept here for the plan
+  __shared__ double xs[kNarrow ? TR : 1][kNarrow ? RPT : 1];
+  if constexpr (kNarrow) {
+    if (cslot == 0) {
 #pragma unroll
-    for (int a = 0; a < RPT; ++a) {
-      double acc = 0.0;
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) acc = fma(K[a][c], y[c], acc);
-      s[a] = acc;
+      for (int a = 0; a < RPT; ++a) xs[rslot][a] = x[a];   // what T = 0 leaves
     }
-#pragma unroll
-    for (int mask = 1; mask < TC; mask <<= 1)
-#pragma unroll
-      for (int a = 0; a < RPT; ++a) s[a] += __shfl_xor(s[a], mask, kWave);
-    const double row_dust = kz * y_dust;
-#pragma unroll
-    for (int a = 0; a < RPT; ++a) x[a] = (rslot + TR * a < m) ? rcp64(s[a] + row_dust) : 0.0;
-    x_dust = static_cast<double>(r) * rcp64(kz * sum_y);
+  }
 
-    // ---- v-update ----
+  for (int it = 0; it < p.iters; ++it) {
     double t[CPT + 1];
+    const double row_dust = kz * y_dust;
+    if constexpr (kNarrow) {
+      // one pass over the rows: a row is widened once, summed against y, and as
+      // soon as its x is known added into the column sums, so that neither the
+      // widened entries nor the x of other rows stay in registers
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      double acc = 0.0;
+      for (int c = 0; c <= CPT; ++c) t[c] = 0.0;
 #pragma unroll
-      for (int a = 0; a < RPT; ++a) acc = fma(K[a][c], x[a], acc);
-      t[c] = acc;
-    }
-    {
+      for (int a = 0; a < RPT; ++a) {
+        double kd[CPT];
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+          forget_origin(K[a][c]);
+          kd[c] = static_cast<double>(K[a][c]);
+        }
+        double acc = 0.0;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) acc = fma(kd[c], y[c], acc);
+        acc = group_sum<LOG_TC>(acc);
+        const double xa = (rslot + TR * a < m) ? rcp64(acc + row_dust) : 0.0;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) t[c] = fma(kd[c], xa, t[c]);
+        t[CPT] += xa;
+        xs[rslot][a] = xa;   // the lanes of a row slot write the same value; no branch in this loop
+        // rows are independent, and left alone the scheduler would widen all of
+        // them at once
+        if (a % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      // ---- u-update ----
+      double s[RPT];
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) {
+        double acc = 0.0;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) acc = fma(static_cast<double>(K[a][c]), y[c], acc);
+        s[a] = acc;
+      }
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) s[a] = group_sum<LOG_TC>(s[a]);
+#pragma unroll
+      for (int a = 0; a < RPT; ++a) x[a] = (rslot + TR * a < m) ? rcp64(s[a] + row_dust) : 0.0;
+
+      // ---- v-update ----
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        double acc = 0.0;
+#pragma unroll
+        for (int a = 0; a < RPT; ++a) acc = fma(static_cast<double>(K[a][c]), x[a], acc);
+        t[c] = acc;
+      }
       double acc = 0.0;
 #pragma unroll
       for (int a = 0; a < RPT; ++a) acc += x[a];
       t[CPT] = acc;
     }
-    if (TC == 1) {
+    x_dust = static_cast<double>(r) * rcp64(kz * sum_y);
 #pragma unroll
-      for (int c = 0; c <= CPT; ++c) t[c] = wave_sum_dpp(t[c]);
-    } else {
-#pragma unroll
-      for (int mask = TC; mask < kWave; mask <<= 1)
-#pragma unroll
-        for (int c = 0; c <= CPT; ++c) t[c] += __shfl_xor(t[c], mask, kWave);
-    }
+    for (int c = 0; c <= CPT; ++c) t[c] = cross_sum<LOG_TC>(t[c]);
     if (W > 1) {
       // wave totals -> LDS; one thread per (column slot, value) adds the W
       // partials; everybody reads back its CPT + 1 totals
@@ -240,25 +300,34 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
       ly += y[c];
     }
     y_dust = static_cast<double>(m) * rcp64(kz * (t[CPT] + x_dust));
-#pragma unroll
-    for (int mask = 1; mask < TC; mask <<= 1) ly += __shfl_xor(ly, mask, kWave);
+    ly = group_sum<LOG_TC>(ly);
     sum_y = ly + y_dust;
   }
 
   // ---- plan and pairing ----
+  if constexpr (kNarrow) {   // written by this row slot's first lane, a lane of this wave
+#pragma unroll
+    for (int a = 0; a < RPT; ++a) x[a] = xs[rslot][a];
+  }
   float bv[CPT];
   int bi[CPT];
 #pragma unroll
   for (int c = 0; c < CPT; ++c) { bv[c] = -1.f; bi[c] = 0x7fffffff; }
   float* P = plan_out ? plan_out + po : nullptr;
+  // the entries' offsets are recomputed from slots the compiler cannot relate to
+  // the ones the loads used: otherwise it keeps all RPT CPT offsets in registers
+  // across the iteration loop
+  int rslot_p = rslot, cslot_p = cslot;
+  forget_origin(rslot_p);
+  forget_origin(cslot_p);
 #pragma unroll
   for (int a = 0; a < RPT; ++a) {
-    const int i = rslot + TR * a;
+    const int i = rslot_p + TR * a;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      const int j = cslot + TC * c;
+      const int j = cslot_p + TC * c;
       if (i < m && j < r) {
-        const float v = static_cast<float>(x[a] * K[a][c] * y[c]);
+        const float v = static_cast<float>(x[a] * static_cast<double>(K[a][c]) * y[c]);
         if (P) P[static_cast<long long>(i) * r + j] = v;
         if (v > bv[c]) { bv[c] = v; bi[c] = i; }
       }

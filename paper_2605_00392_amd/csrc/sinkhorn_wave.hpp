@@ -163,9 +163,13 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
   for (int c = 0; c < C; ++c) { bv[c] = -1.f; bi[c] = 0x7fffffff; }
   if (active) {
     float* P = A.plan_out ? A.plan_out + po : nullptr;
+    // rows recomputed from a value the compiler cannot relate to the one the
+    // loads used, so that no entry offset stays in a register across the loop
+    int row0_p = row0;
+    forget_origin(row0_p);
 #pragma unroll
     for (int a = 0; a < RPT; ++a) {
-      const int i = row0 + TR * a;
+      const int i = row0_p + TR * a;
 #pragma unroll
       for (int c = 0; c < C; ++c) {
         if (i <= m && c < r) {

@@ -123,16 +123,19 @@ class Report:
 
 
 def compare_image(b: int, batch: synth.Batch, gpu: Dict, p: orc.Params, rep: Report,
-                  staged: bool = False) -> None:
-    """Compare image ``b`` of a device result with the oracle; raises AssertionError."""
+                  staged: bool = False, keep_count: Optional[int] = None) -> None:
+    """Compare image ``b`` of a device result with the oracle; raises AssertionError.
+    ``keep_count``: the kept count the caller gave the staged calls for this image."""
     lo, hi = int(batch.offsets[b]), int(batch.offsets[b + 1])
     n = hi - lo
     X = orc.widen(batch.tokens[lo:hi], batch.dtype)
     rho = float(batch.density[b]) if len(batch.density) else 0.0
-    ref = orc.prune_image(X, rho, p)
+    ref = orc.prune_image(X, rho, p, keep_count=keep_count)
     rep.images += 1
     m_gpu = int(gpu["keep"][b])
-    if p.dynamic:
+    if keep_count is not None:
+        assert m_gpu == min(max(keep_count, 0), n), (b, m_gpu, keep_count)
+    elif p.dynamic:
         err = abs(float(gpu["ratio"][b]) - float(ref.retention))
         rep.max_ratio_err = max(rep.max_ratio_err, err)
         assert err <= RATIO_TOL, (b, gpu["ratio"][b], ref.retention)
@@ -219,9 +222,11 @@ def compare_image(b: int, batch: synth.Batch, gpu: Dict, p: orc.Params, rep: Rep
 
 
 def compare_batch(batch: synth.Batch, gpu: Dict, params: Optional[Dict] = None,
-                  images: Optional[List[int]] = None, staged: bool = False) -> Report:
+                  images: Optional[List[int]] = None, staged: bool = False,
+                  keep_counts: Optional[List[int]] = None) -> Report:
     p = orc.Params.from_dict(batch.params if params is None else params)
     rep = Report()
     for b in (range(batch.batch) if images is None else images):
-        compare_image(b, batch, gpu, p, rep, staged=staged)
+        compare_image(b, batch, gpu, p, rep, staged=staged,
+                      keep_count=None if keep_counts is None else int(keep_counts[b]))
     return rep

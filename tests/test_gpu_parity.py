@@ -183,6 +183,34 @@ def test_multi_workgroup_sinkhorn_variants(override):
     np.testing.assert_array_equal(f["pair"], s["pair"])
 
 
+def test_tall_register_shapes_at_their_edges():
+    """Kept and pruned counts on both sides of the limits of the two shapes that hold
+    a tall image (more than 512 rows) in one workgroup's registers: 1535 x 15
+    (eight waves, all columns per lane) and 1216 x 64 (fp32-held matrix)."""
+    shapes = [(1216, 64), (1217, 64), (1216, 65), (1535, 15), (1536, 15), (700, 16), (512, 1), (1535, 16),
+              (600, 33), (1000, 1)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 24, iters=40)
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, "tall shapes")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
+@pytest.mark.parametrize("override", [dict(ratio=0.96), dict(ratio=0.99), dict(ratio=0.96, iters=0),
+                                      dict(ratio=0.96, eps=0.02)])
+def test_tall_images_fused(override):
+    """Tiled-page sized images with few pruned tokens through the fused call."""
+    batch = _clustered([1156, 1000, 800, 1300, 520, 1500], 1024, "bf16", 25, **override)
+    f = hz.run_prune(batch)
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"tall fused {override}")
+    s = hz.run_staged(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+
+
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 72), ("bf16", 256), ("f32", 1280)])
 def test_multi_workgroup_sinkhorn_other_widths(dtype, d):
     """The same images through the general score and merge kernels (fp32 tokens, odd widths)."""
