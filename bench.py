@@ -94,8 +94,9 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     if kernel == "k_sinkhorn" and big.any():
         # sweep kernels: the kernel matrix read once per iteration (it does not fit on chip)
         return "hbm", kbytes * iters * float((m * r)[big].sum()), "GB/s", HBM_PEAK_GBS
-    if kernel in ("k_sinkhorn", "k_sinkhorn_regs"):
-        # two sweeps of multiply-adds over the augmented matrix per iteration
+    if kernel in ("k_sinkhorn", "k_sinkhorn_regs", "k_sinkhorn_tall"):
+        # register-resident or single-workgroup kernels: two sweeps of multiply-adds over
+        # the augmented matrix per iteration (counted over the whole batch)
         return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
     return "hbm", 0.0, "GB/s", HBM_PEAK_GBS
 

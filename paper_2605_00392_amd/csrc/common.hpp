@@ -25,7 +25,7 @@ struct DevParams {
   double shift;      // max(1, z): exp((s - shift) / eps) <= 1 for every score s
   float ratio, ratio_min, ratio_max, phi_lo, phi_hi;
   int iters, dynamic, metric;
-  int sweep;   // the batch may hold images for the multi-workgroup Sinkhorn sweep
+  int mode;    // which Sinkhorn kernels the call launches (kMode... bits)
   int k32;     // those images' kernel matrix is stored in fp32 (its range allows it)
 };
 

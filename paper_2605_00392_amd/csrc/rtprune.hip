@@ -126,7 +126,7 @@ int check_params(const rtprune_params* p, DevParams* d) {
   d->iters = p->iters;
   d->dynamic = p->dynamic ? 1 : 0;
   d->metric = p->metric;
-  d->sweep = 0;                                  // set per batch by launch_ot
+  d->mode = 0;                                   // set per batch by launch_ot
   d->k32 = (hi - lo) / eps <= 80.0 ? 1 : 0;      // exp(-80) is a normal fp32 number
   return RTP_OK;
 }
@@ -149,9 +149,9 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_SPLICE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN_TALL, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_SPLICE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
-                                             "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn",
+                                             "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn_tall", "k_sinkhorn",
                                              "k_merge", "k_density_prepare", "k_density_sobel",
                                              "k_density_finish", "k_splice"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
@@ -328,7 +328,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
   p.k32 = p.k32 && L.sweep;
-  p.sweep = L.sweep ? (kSweepLaunched | (p.k32 ? kSweepF32 : 0)) : 0;
+  p.mode = L.sweep ? (kModeLarge | (p.k32 ? kModeF32 : 0)) : 0;
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
@@ -337,36 +337,39 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   int32_t* work = at<int32_t>(ws, L.work);
   {
     ProfScope prof(KID_CLASSIFY, s);
-    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.sweep, st);
+    hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.mode, st);
   }
+  SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
-    SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
     hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
-    if (L.sweep) hipLaunchKernelGGL(k_sinkhorn_tall, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
+  }
+  if (p.mode & kModeLarge) {
+    ProfScope prof(KID_SINKHORN_TALL, s);
+    hipLaunchKernelGGL(k_sinkhorn_tall, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
   }
   RTP_TRY(launched());
   ProfScope prof(KID_SINKHORN, s);
   hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
-                     L.plan_cap, plan, pair, 1, p.sweep, st);
+                     L.plan_cap, plan, pair, 1, p.mode, st);
   RTP_TRY(launched());
-  if (L.sweep) {
+  if (p.mode & kModeLarge) {
     // large images: two launches per iteration over all of them, then plan and pairing
-    SweepArgs A{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
+    SweepArgs SA{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
                 at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<void>(ws, L.sw_colpart),
                 at<double>(ws, L.sw_xpart), at<double>(ws, L.sw_ysum), at<double>(ws, L.sw_ydust),
                 at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair};
     const int strips = (in->max_tokens + kSweepRows - 1) / kSweepRows;
     const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepCols - 1) / kSweepCols;
     const dim3 grows(strips, in->B), gcols(cols, in->B);
-    hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColThreads), 0, s, A, st);
+    hipLaunchKernelGGL(k_sweep_init, gcols, dim3(kSweepColThreads), 0, s, SA, st);
     // columns per thread: enough for the largest pruned set the batch can hold
     const int rmax = std::min(pruned_bound(in, p, max_pruned_hint), kSweepMaxR);
     const int ch = (std::max(rmax, 1) + kSweepThreads - 1) / kSweepThreads;
     auto rows = [&](auto final_tag, int parity) {
       constexpr bool kFinal = decltype(final_tag)::value;
 #define RTP_SWEEP_ROWS(KT, CH) \
-  hipLaunchKernelGGL((k_sweep_rows<kFinal, KT, CH>), grows, dim3(kSweepThreads), 0, s, A, parity, st)
+  hipLaunchKernelGGL((k_sweep_rows<kFinal, KT, CH>), grows, dim3(kSweepThreads), 0, s, SA, parity, st)
       if (p.k32) {
         if (ch <= 1) RTP_SWEEP_ROWS(float, 1);
         else if (ch == 2) RTP_SWEEP_ROWS(float, 2);
@@ -382,11 +385,11 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     };
     for (int it = 0; it < p.iters; ++it) {
       rows(std::false_type{}, it & 1);
-      if (p.k32) hipLaunchKernelGGL((k_sweep_cols<false, float>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
-      else hipLaunchKernelGGL((k_sweep_cols<false, double>), gcols, dim3(kSweepColThreads), 0, s, A, it & 1, 0, st);
+      if (p.k32) hipLaunchKernelGGL((k_sweep_cols<false, float>), gcols, dim3(kSweepColThreads), 0, s, SA, it & 1, 0, st);
+      else hipLaunchKernelGGL((k_sweep_cols<false, double>), gcols, dim3(kSweepColThreads), 0, s, SA, it & 1, 0, st);
     }
     rows(std::true_type{}, 0);
-    hipLaunchKernelGGL((k_sweep_cols<true, double>), gcols, dim3(kSweepColThreads), 0, s, A,
+    hipLaunchKernelGGL((k_sweep_cols<true, double>), gcols, dim3(kSweepColThreads), 0, s, SA,
                        p.iters > 0 ? (p.iters - 1) & 1 : 0, p.iters == 0 ? 1 : 0, st);
   }
   return launched();

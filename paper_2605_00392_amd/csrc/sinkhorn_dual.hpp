@@ -296,7 +296,7 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
 // indices each.  One workgroup; list order follows image order.
 __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
                                                   const int32_t* __restrict__ keep, int B,
-                                                  int32_t* __restrict__ work, int sweep,
+                                                  int32_t* __restrict__ work, int mode,
                                                   const int32_t* __restrict__ status) {
   if (status[0]) return;
   constexpr int NV = kWorkLists;
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
-    const int v = sinkhorn_variant(m, n - m, sweep);
+    const int v = sinkhorn_variant(m, n - m, mode);
     if (n > 0 && v < kGeneralVariant) {
 #pragma unroll
       for (int u = 0; u < NV; ++u) c[u] += (u == v);
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
-    const int v = sinkhorn_variant(m, n - m, sweep);
+    const int v = sinkhorn_variant(m, n - m, mode);
     if (n > 0 && v < kGeneralVariant) {
 #pragma unroll
       for (int u = 0; u < NV; ++u)
@@ -394,9 +394,9 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   }
 }
 
-// The tall shapes (more than 512 rows), one image per workgroup; launched only
-// for batches that can hold such images.  A kernel of its own so that its LDS
-// and registers do not count against the kernel above.
+// The tall shapes (more than 512 rows), one image per workgroup, the longer-running
+// role first.  Launched only for batches that can hold such images.  A kernel of
+// its own so that its LDS and registers do not count against the kernel above.
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_tall(SinkhornArgs A,
                                                                const int32_t* __restrict__ work, int B,
                                                                const int32_t* __restrict__ status) {

@@ -73,27 +73,27 @@ constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
               kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kGeneralVariant = 9;
 constexpr int kWorkLists = 9;
-// `sweep` as the kernels receive it: bit 0, the call launches the sweep kernels
-// (the batch may hold images beyond the 512-row register shapes); bit 1, the
+// What a call launches besides the 512-row register shapes, as the kernels
+// receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
+// tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the
 // kernel matrix's range fits fp32.
-constexpr int kSweepLaunched = 1, kSweepF32 = 2;
-// The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take what no register
-// shape fits, up to this many pruned tokens; they are only launched for batches
-// that can hold such images (`sweep`).
+constexpr int kModeLarge = 1, kModeF32 = 2;
+// The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
+// pruned tokens.
 constexpr int kSweepMaxPruned = 2048;
 
 // Which Sinkhorn kernel serves an image; every kernel evaluates this and takes
 // only its own images, so each image is processed exactly once.
-__host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
+__host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   if (WaveShape::fits(m, r)) return kVariantA;
   if (PairShape::fits(m, r)) return kVariantPair;
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
-  if (sweep && TallShape::fits(m, r)) return kVariantTall;
-  if ((sweep & kSweepF32) && TeamTall::fits(m, r)) return kVariantTeamTall;
+  if ((mode & kModeLarge) && TallShape::fits(m, r)) return kVariantTall;
+  if ((mode & kModeLarge) && (mode & kModeF32) && TeamTall::fits(m, r)) return kVariantTeamTall;
   // when the sweep kernels run anyway (their launches are paid for) they also
   // take the images of the slowest register shapes, which otherwise set the
   // duration of the register-resident launch
-  if (sweep && r <= kSweepMaxPruned) return kVariantSweep;
+  if ((mode & kModeLarge) && r <= kSweepMaxPruned) return kVariantSweep;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if (TeamC::fits(m, r)) return kVariantC;
@@ -105,7 +105,7 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int sweep) {
 // is an absolute perturbation of eps * 6e-8 on the score S, below the scores' own
 // error, and it halves the bytes every iteration streams.
 __device__ __forceinline__ bool kernel_is_f32(const DevParams& p, int m, int r) {
-  return p.k32 && sinkhorn_variant(m, r, p.sweep) == kVariantSweep;
+  return p.k32 && sinkhorn_variant(m, r, p.mode) == kVariantSweep;
 }
 // fp32 layout of image b's kernel matrix: rows padded to a multiple of four
 // entries (when there are at least eight columns) and the first row on a 16-byte

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(1024) void k_sinkhorn(
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ keep,
     const long long* __restrict__ plan_offsets, DevParams p, const double* __restrict__ kmat,
     long long plan_cap, float* __restrict__ plan_out, int32_t* __restrict__ pair_out,
-    int skip_team_shapes, int sweep, const int32_t* __restrict__ status) {
+    int skip_team_shapes, int mode, const int32_t* __restrict__ status) {
   if (status[0]) return;
   __shared__ double xy[kMaxTokens + 2];
   __shared__ double part[16][kWave];
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(1024) void k_sinkhorn(
   const int n = offsets[b + 1] - lo;
   if (n <= 0) return;
   const int m = min(max(keep[b], 0), n), r = n - m;
-  if (skip_team_shapes && sinkhorn_variant(m, r, sweep) != kGeneralVariant) return;   // done elsewhere
+  if (skip_team_shapes && sinkhorn_variant(m, r, mode) != kGeneralVariant) return;   // done elsewhere
   if (pair_out)
     for (int i = tid; i < m; i += 1024) pair_out[lo + i] = i;
   if (r <= 0 || m <= 0) return;

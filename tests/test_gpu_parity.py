@@ -211,6 +211,36 @@ def test_tall_images_fused(override):
     np.testing.assert_array_equal(f["pair"], s["pair"])
 
 
+# (T = 0 goes with eps = 1: at eps = 0.05 the unnormalised exp(S / eps) of hundreds of
+# look-alike tokens sums to 1e4 and more per row, where fp32 accumulation noise alone
+# exceeds the absolute bar)
+@pytest.mark.parametrize("override", [dict(), dict(iters=0, eps=1.0), dict(iters=1), dict(eps=1.0),
+                                      dict(z=0.9, alpha=0.3)])
+def test_dynamic_ratio_on_tiled_page_sizes_with_many_pruned_tokens(override):
+    """Dynamic retention on images of 700-1150 tokens whose tokens resemble each other
+    (phi near 0.5), so that hundreds are pruned: the retention clamp's bound is reached,
+    and the sweep and tiled kernels serve a batch sized by that bound."""
+    rng = np.random.default_rng(26)
+    d, imgs = 1024, []
+    for c in [800, 1150, 700, 1000, 300, 1156]:
+        common = rng.standard_normal(d)
+        common /= np.linalg.norm(common)
+        x = common[None, :] + rng.standard_normal((c, d)) / np.sqrt(d)
+        dup = rng.integers(0, c, size=c // 5)                  # near-copies: clear partners
+        x[rng.permutation(c)[:c // 5]] = x[dup] + rng.standard_normal((c // 5, d)) * (0.05 / np.sqrt(d))
+        x *= rng.lognormal(0, 0.3, size=(c, 1))
+        imgs.append(x.astype(np.float32))
+    dens = np.array([0.05, 0.1, 0.3, 0.6, 0.2, 0.9], dtype=np.float32)
+    p = dict(synth.DEFAULT_PARAMS, dynamic=1, iters=30)
+    p.update(override)
+    batch = synth.pack(0, "bf16", imgs, dens, p)
+    f = hz.run_prune(batch)
+    pruned = np.diff(batch.offsets) - f["keep"]
+    assert (pruned[:4] > 64).all() and pruned.max() > 256, pruned   # beyond every register shape
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"clamped {override} pruned={list(pruned)}")
+
+
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 72), ("bf16", 256), ("f32", 1280)])
 def test_multi_workgroup_sinkhorn_other_widths(dtype, d):
     """The same images through the general score and merge kernels (fp32 tokens, odd widths)."""
