@@ -263,6 +263,8 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
 // of token k is the number of tokens that precede it in (score descending,
 // index ascending) order; it is kept iff rank < M.  Kept and pruned indices
 // are then written in ascending order.
+constexpr int kRankCountMaxTokens = 512;   // above this the selection threshold is found by radix passes
+
 template <int NT>
 __global__ __launch_bounds__(NT) void k_select(
     const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
@@ -325,23 +327,70 @@ __global__ __launch_bounds__(NT) void k_select(
   __syncthreads();
   const int m = s_m;
 
-  const ulonglong2* keys2 = reinterpret_cast<const ulonglong2*>(keys);
-  for (int kb = tid; kb < n; kb += 4 * NT) {
-    unsigned long long mine[4];
-    int rank[4];
+  if (n <= kRankCountMaxTokens) {
+    // few tokens: count every token's rank directly (n^2 / 2 comparisons of LDS keys)
+    const ulonglong2* keys2 = reinterpret_cast<const ulonglong2*>(keys);
+    for (int kb = tid; kb < n; kb += 4 * NT) {
+      unsigned long long mine[4];
+      int rank[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      mine[u] = keys[min(kb + NT * u, n - 1)];
-      rank[u] = 0;
+      for (int u = 0; u < 4; ++u) {
+        mine[u] = keys[min(kb + NT * u, n - 1)];
+        rank[u] = 0;
+      }
+      for (int l2 = 0; l2 < n_pad / 2; ++l2) {
+        const ulonglong2 o = keys2[l2];                         // same address in every lane
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rank[u] += (o.x > mine[u]) + (o.y > mine[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (kb + NT * u < n) kept_flag[kb + NT * u] = rank[u] < m;
     }
-    for (int l2 = 0; l2 < n_pad / 2; ++l2) {
-      const ulonglong2 o = keys2[l2];                         // same address in every lane
+  } else {
+    // many tokens: find the M-th largest key byte by byte from the top (keys are
+    // distinct).  Each pass histograms the next byte of the keys that share the
+    // bytes found so far and picks the bin that holds the M-th largest; it can
+    // stop as soon as that bin is needed whole.
+    __shared__ int hist[256];
+    __shared__ int s_bin, s_need, s_whole;
+    unsigned long long prefix = 0;     // the bytes found so far, right-aligned
+    int need = m, shift = 56;
+    for (;; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int k = tid; k < n; k += NT) {
+        const unsigned long long key = keys[k];
+        if (shift == 56 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid < 64) {
+        // lane l holds bins 4 l .. 4 l + 3; `above` = keys in bins higher than the lane's
+        const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+        const int mine = h0 + h1 + h2 + h3;
+        int above = mine;                                   // inclusive suffix sum over lanes >= l
 #pragma unroll
-      for (int u = 0; u < 4; ++u) rank[u] += (o.x > mine[u]) + (o.y > mine[u]);
+        for (int o = 1; o < 64; o <<= 1) {
+          const int v = __shfl_down(above, o, kWave);
+          if (tid + o < 64) above += v;
+        }
+        above -= mine;
+        if (above < need && need <= above + mine) {         // exactly one lane
+          int bin = 4 * tid + 3, cnt = h3, left = need - above;
+          if (left > cnt) { left -= cnt; bin = 4 * tid + 2; cnt = h2;
+            if (left > cnt) { left -= cnt; bin = 4 * tid + 1; cnt = h1;
+              if (left > cnt) { left -= cnt; bin = 4 * tid; cnt = h0; } } }
+          s_bin = bin;
+          s_need = left;
+          s_whole = left == cnt;
+        }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | static_cast<unsigned long long>(s_bin);
+      need = s_need;
+      if (s_whole || shift == 0) break;                     // at shift 0 a bin holds one key
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (kb + NT * u < n) kept_flag[kb + NT * u] = rank[u] < m;
+    for (int k = tid; k < n; k += NT) kept_flag[k] = (keys[k] >> shift) >= prefix;
   }
   __syncthreads();
 

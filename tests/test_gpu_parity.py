@@ -392,6 +392,25 @@ def test_identical_tokens_and_equal_norms():
     hz.compare_batch(batch, hz.run_prune(batch))
 
 
+@pytest.mark.parametrize("n,keep", [(600, 300), (600, 1), (600, 600), (600, 599), (1500, 777), (3000, 2048),
+                                    (513, 256)])
+def test_selection_on_long_images_with_many_equal_scores(n, keep):
+    """More than 512 tokens (the selection threshold is then found by radix passes over
+    the keys) with scores that repeat: groups of identical tokens, a few distinct ones.
+    Ties go to the lowest indices, exactly as the oracle's stable order does."""
+    rng = np.random.default_rng(n + keep)
+    protos = rng.standard_normal((7, 64)).astype(np.float32) * rng.lognormal(0, 0.5, size=(7, 1)).astype(np.float32)
+    x = protos[rng.integers(0, 7, size=n)]
+    x[rng.integers(0, n, size=5)] *= 3.0
+    batch = synth.pack(0, "bf16", [x], [0.5], dict(synth.DEFAULT_PARAMS, iters=2, ratio=0.5))
+    s = hz.run_staged(batch, keep_counts_in=[keep])
+    assert int(s["keep"][0]) == keep
+    X = orc.widen(batch.tokens, "bf16")
+    ref = orc.prune_image(X, 0.5, orc.Params.from_dict(batch.params), keep_count=keep)
+    np.testing.assert_array_equal(s["sel"][:keep], ref.kept)
+    np.testing.assert_array_equal(s["sel"][keep:], ref.prop)
+
+
 def test_zero_norm_tokens():
     rng = np.random.default_rng(7)
     x = rng.standard_normal((16, 64)).astype(np.float32)
