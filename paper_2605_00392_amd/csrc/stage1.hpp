@@ -263,7 +263,9 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
 // of token k is the number of tokens that precede it in (score descending,
 // index ascending) order; it is kept iff rank < M.  Kept and pruned indices
 // are then written in ascending order.
-constexpr int kRankCountMaxTokens = 512;   // above this the selection threshold is found by radix passes
+// Up to this many tokens every rank is counted directly; above it the selection
+// threshold is found by radix passes (measured: faster from a few hundred tokens on).
+constexpr int kRankCountMaxTokens = 128;
 
 template <int NT>
 __global__ __launch_bounds__(NT) void k_select(
@@ -328,7 +330,7 @@ __global__ __launch_bounds__(NT) void k_select(
   const int m = s_m;
 
   if (n <= kRankCountMaxTokens) {
-    // few tokens: count every token's rank directly (n^2 / 2 comparisons of LDS keys)
+    // few tokens: count every token's rank directly (n^2 comparisons of LDS keys)
     const ulonglong2* keys2 = reinterpret_cast<const ulonglong2*>(keys);
     for (int kb = tid; kb < n; kb += 4 * NT) {
       unsigned long long mine[4];

@@ -395,8 +395,8 @@ def test_identical_tokens_and_equal_norms():
 @pytest.mark.parametrize("n,keep", [(600, 300), (600, 1), (600, 600), (600, 599), (1500, 777), (3000, 2048),
                                     (513, 256)])
 def test_selection_on_long_images_with_many_equal_scores(n, keep):
-    """More than 512 tokens (the selection threshold is then found by radix passes over
-    the keys) with scores that repeat: groups of identical tokens, a few distinct ones.
+    """Long images (the selection threshold is then found by radix passes over the
+    keys) with scores that repeat: groups of identical tokens, a few distinct ones.
     Ties go to the lowest indices, exactly as the oracle's stable order does."""
     rng = np.random.default_rng(n + keep)
     protos = rng.standard_normal((7, 64)).astype(np.float32) * rng.lognormal(0, 0.5, size=(7, 1)).astype(np.float32)
