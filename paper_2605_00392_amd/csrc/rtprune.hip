@@ -246,11 +246,23 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
   return launched();
 }
 
+// Which Sinkhorn kernels a call on this batch launches, and whether the sweep
+// kernels' matrices are stored in fp32 (only batches that may hold images beyond
+// the 512-row register shapes have any).
+void set_sinkhorn_mode(DevParams& p, const Layout& L) {
+  p.k32 = p.k32 && L.sweep;
+  p.mode = L.sweep ? (kModeLarge | (p.k32 ? kModeF32 : 0)) : 0;
+}
+
+// `work` non-null: the same launch also builds the Sinkhorn work lists.
 int launch_scan(const rtprune_batch* in, const int32_t* keep, int32_t* out_off, long long* plan_off,
-                const int32_t* status, hipStream_t s) {
+                const int32_t* status, hipStream_t s, int32_t* work = nullptr, int mode = 0) {
   ProfScope prof(KID_SCAN, s);
-  hipLaunchKernelGGL(k_scan, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, out_off, plan_off,
-                     status);
+  if (work)
+    hipLaunchKernelGGL(k_scan_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, out_off, plan_off, work,
+                       mode, status);
+  else
+    hipLaunchKernelGGL(k_scan, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, out_off, plan_off, status);
   return launched();
 }
 
@@ -324,18 +336,17 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
 
 int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel, const int32_t* keep,
               const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
-              int32_t* pair, int max_pruned_hint, hipStream_t s) {
+              int32_t* pair, int max_pruned_hint, bool classified, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
-  p.k32 = p.k32 && L.sweep;
-  p.mode = L.sweep ? (kModeLarge | (p.k32 ? kModeF32 : 0)) : 0;
+  set_sinkhorn_mode(p, L);
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
               : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
   const double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   int32_t* work = at<int32_t>(ws, L.work);
-  {
+  if (!classified) {
     ProfScope prof(KID_CLASSIFY, s);
     hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.mode, st);
   }
@@ -685,7 +696,7 @@ extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(launch_norms(in, 0, RTP_METRIC_L2NORM, L, workspace, nullptr, s));
   // the kept counts live on the device: no host-side bound on the pruned sets
   return launch_ot(in, p, sel_idx, keep_counts, reinterpret_cast<const long long*>(plan_offsets), L,
-                   workspace, scores, plan, pair, kPrunedUnknown, s);
+                   workspace, scores, plan, pair, kPrunedUnknown, false, s);
 }
 
 extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
@@ -721,11 +732,13 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   RTP_TRY(launch_prepare(in, status, s));
   RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
   RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
-  RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s));
+  DevParams pm = p;
+  set_sinkhorn_mode(pm, L);
+  RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s, at<int32_t>(workspace, L.work), pm.mode));
   // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image
   const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
-  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
   return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status, s);
 }
 
@@ -769,12 +782,14 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   RTP_TRY(launched());
   RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
   RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
-  RTP_TRY(launch_scan(in, keep, nullptr, plan_off, status, s));
+  DevParams pm = p;
+  set_sinkhorn_mode(pm, L);
+  RTP_TRY(launch_scan(in, keep, nullptr, plan_off, status, s, at<int32_t>(workspace, L.work), pm.mode));
   hipLaunchKernelGGL(k_splice_scan, dim3(1), dim3(256), 0, s, t, keep, in->B, seq_offsets, visual_start, status);
   RTP_TRY(launched());
   const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
-  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, s));
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
   // the merge writes image b's kept rows at visual_start[b], between its text spans
   RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status, s));
   if (in->B == 0) return RTP_OK;

@@ -294,11 +294,9 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
 // Work lists for the register-resident kernels: `work` holds kWorkLists counts
 // (one per shape, indexed by variant id) followed by as many lists of B image
 // indices each.  One workgroup; list order follows image order.
-__global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
-                                                  const int32_t* __restrict__ keep, int B,
-                                                  int32_t* __restrict__ work, int mode,
-                                                  const int32_t* __restrict__ status) {
-  if (status[0]) return;
+__device__ __forceinline__ void classify_images(const int32_t* __restrict__ offsets,
+                                                const int32_t* __restrict__ keep, int B,
+                                                int32_t* __restrict__ work, int mode) {
   constexpr int NV = kWorkLists;
   __shared__ int cnt[NV][256];
   const int tid = threadIdx.x;
@@ -345,6 +343,26 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
 #pragma unroll
     for (int v = 0; v < NV; ++v) work[v] = cnt[v][255];
   }
+}
+
+__global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
+                                                  const int32_t* __restrict__ keep, int B,
+                                                  int32_t* __restrict__ work, int mode,
+                                                  const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  classify_images(offsets, keep, B, work, mode);
+}
+
+// Both of the above in one launch, for the fused calls.
+__global__ __launch_bounds__(256) void k_scan_classify(const int32_t* __restrict__ offsets,
+                                                       const int32_t* __restrict__ keep, int B,
+                                                       int32_t* __restrict__ out_offsets,
+                                                       long long* __restrict__ plan_offsets,
+                                                       int32_t* __restrict__ work, int mode,
+                                                       const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  scan_images(offsets, keep, B, out_offsets, plan_offsets);
+  classify_images(offsets, keep, B, work, mode);
 }
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are

@@ -422,13 +422,11 @@ __global__ __launch_bounds__(NT) void k_select(
 }
 
 // Exclusive prefix sums over the images: out_offsets = scan(M_b) (int32),
-// plan_offsets = scan(M_b * R_b) (int64).  One workgroup.
-__global__ __launch_bounds__(256) void k_scan(const int32_t* __restrict__ offsets,
-                                              const int32_t* __restrict__ keep, int B,
-                                              int32_t* __restrict__ out_offsets,
-                                              long long* __restrict__ plan_offsets,
-                                              const int32_t* __restrict__ status) {
-  if (status[0]) return;
+// plan_offsets = scan(M_b * R_b) (int64).  One workgroup of 256 threads.
+__device__ __forceinline__ void scan_images(const int32_t* __restrict__ offsets,
+                                            const int32_t* __restrict__ keep, int B,
+                                            int32_t* __restrict__ out_offsets,
+                                            long long* __restrict__ plan_offsets) {
   __shared__ long long sm[256];
   __shared__ long long sp[256];
   const int tid = threadIdx.x;
@@ -464,6 +462,15 @@ __global__ __launch_bounds__(256) void k_scan(const int32_t* __restrict__ offset
     if (out_offsets) out_offsets[B] = static_cast<int32_t>(sm[255]);
     if (plan_offsets) plan_offsets[B] = sp[255];
   }
+}
+
+__global__ __launch_bounds__(256) void k_scan(const int32_t* __restrict__ offsets,
+                                              const int32_t* __restrict__ keep, int B,
+                                              int32_t* __restrict__ out_offsets,
+                                              long long* __restrict__ plan_offsets,
+                                              const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  scan_images(offsets, keep, B, out_offsets, plan_offsets);
 }
 
 }  // namespace rtp
