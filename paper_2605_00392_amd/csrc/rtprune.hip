@@ -31,13 +31,14 @@ using namespace rtp;
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kNormMinWorkgroups = 1024;   // the norm pass keeps at least this many workgroups when it merges chunks
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 // Byte offsets of the workspace regions for a batch shape.
 struct Layout {
   size_t status, norm64, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
   size_t sw_x, sw_y, sw_colpart, sw_xpart, sw_ysum, sw_ydust, sw_bestv, sw_besti;   // sweep Sinkhorn state
-  int chunks_per_image;
+  int chunks_per_image, chunks_per_part, parts_per_image;
   int sweep;            // the batch may hold images beyond the register-resident Sinkhorn shapes
   long long plan_cap;   // entries available in kmat / plan
   long long strip_cap;  // entries available in the per-strip arrays
@@ -49,6 +50,12 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
   L.chunks_per_image = (max_tokens + kNormRowsPerChunk - 1) / kNormRowsPerChunk;
   if (L.chunks_per_image < 1) L.chunks_per_image = 1;
+  // A workgroup of the norm pass takes several chunks when the batch has images
+  // enough to fill the chip without splitting them: fewer partial vectors to
+  // write and to add up afterwards.
+  const long long all_chunks = static_cast<long long>(B) * L.chunks_per_image;
+  L.chunks_per_part = static_cast<int>(std::min<long long>(L.chunks_per_image, std::max<long long>(1, all_chunks / kNormMinWorkgroups)));
+  L.parts_per_image = (L.chunks_per_image + L.chunks_per_part - 1) / L.chunks_per_part;
   // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4
   L.plan_cap = total * static_cast<long long>(max_tokens) / 4 + 1;
   L.status = take(256);
@@ -191,7 +198,7 @@ int launch_prepare(const rtprune_batch* in, int32_t* status, hipStream_t s) {
 template <typename T>
 int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layout& L, void* ws,
                    float* norms_out, hipStream_t s) {
-  const dim3 grid(L.chunks_per_image, in->B), block(kNormThreads);
+  const dim3 grid(L.parts_per_image, in->B), block(kNormThreads);
   const T* tok = static_cast<const T*>(in->tokens);
   double* sq = at<double>(ws, L.norm64);
   float* sc = at<float>(ws, L.score);
@@ -205,10 +212,10 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layou
   do {                                                                                                   \
     if (metric == RTP_METRIC_VARIANCE)                                                                   \
       hipLaunchKernelGGL((k_norms<T, KMAX, KFULL, true>), grid, block, 0, s, tok, in->offsets, in->D,    \
-                         dynamic, sq, sc, norms_out, part, L.chunks_per_image, st);                      \
+                         dynamic, sq, sc, norms_out, part, L.parts_per_image, L.chunks_per_part, st);    \
     else                                                                                                 \
       hipLaunchKernelGGL((k_norms<T, KMAX, KFULL, false>), grid, block, 0, s, tok, in->offsets, in->D,   \
-                         dynamic, sq, sc, norms_out, part, L.chunks_per_image, st);                      \
+                         dynamic, sq, sc, norms_out, part, L.parts_per_image, L.chunks_per_part, st);    \
   } while (0)
   if (in->D <= 1280) {
     if (ngroups == 64 * 5) RTP_LAUNCH_NORMS(5, 5);
@@ -237,11 +244,13 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
   // long images: the rank counting is quadratic in the token count, so the workgroup grows with it
   if (in->max_tokens > 2048)
     hipLaunchKernelGGL(k_select<1024>, dim3(in->B), dim3(1024), lds, s, in->offsets, in->D, p, density, keep_in,
-                       at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
+                       at<float>(ws, L.score), at<double>(ws, L.partial), L.parts_per_image,
+                       L.chunks_per_part * kNormRowsPerChunk, do_select,
                        in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
   else
     hipLaunchKernelGGL(k_select<256>, dim3(in->B), dim3(256), lds, s, in->offsets, in->D, p, density, keep_in,
-                       at<float>(ws, L.score), at<double>(ws, L.partial), L.chunks_per_image, do_select,
+                       at<float>(ws, L.score), at<double>(ws, L.partial), L.parts_per_image,
+                       L.chunks_per_part * kNormRowsPerChunk, do_select,
                        in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
   return launched();
 }

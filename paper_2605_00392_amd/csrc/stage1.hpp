@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ off
 //
 // When `dynamic`, the workgroup also sums T_k / max(||T_k||, tiny) over its rows
 // and writes the D-vector (plus sum_k ||unit_k||^2 as element D) to
-// partial[(b * chunks_per_image + chunk) * (D + 1) ...].
+// partial[(b * parts_per_image + part) * (D + 1) ...].
 //
 // KFULL = number of k whose 64 groups all lie inside the row (their loads need
 // no guard); the remaining k read a clamped address and are zeroed by a select.
@@ -170,21 +170,22 @@ template <typename T, int KMAX, int KFULL, bool VARIANCE>
 __global__ __launch_bounds__(kNormThreads) void k_norms(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
     double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
-    double* __restrict__ partial, int chunks_per_image, const int32_t* __restrict__ status) {
+    double* __restrict__ partial, int parts_per_image, int chunks_per_part,
+    const int32_t* __restrict__ status) {
   if (status[0]) return;
-  const int b = blockIdx.y, chunk = blockIdx.x;
+  // a workgroup takes `chunks_per_part` consecutive chunks of kNormRowsPerChunk rows
+  // of its image and writes one partial vector for all of them
+  const int b = blockIdx.y, part = blockIdx.x;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
-  const int r0 = chunk * kNormRowsPerChunk;
-  if (r0 >= n) return;
-  const int r1 = min(n, r0 + kNormRowsPerChunk);
+  if (part * chunks_per_part * kNormRowsPerChunk >= n) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ngroups = D >> 2;
 
   // Unit vectors x / ||x|| are formed in fp32 (an exact 8- or 24-bit significand
   // times a rounded reciprocal) and a wave adds up those of its own rows - a
-  // quarter of the chunk, at most kNormRowsPerChunk / 4 - in fp32; across waves
-  // and chunks the sums continue in fp64.  The fp32 rounding errors are
+  // quarter of the workgroup's rows - in fp32; across waves and workgroups the
+  // sums continue in fp64.  The fp32 rounding errors are
   // independent, at most 2^-24 of a partial sum of a few units each, and far
   // below what moves the fp32 value of phi.
   float acc32[KMAX][4];
@@ -201,6 +202,10 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
   typedef NormRows<T, KMAX, KFULL, NB, VARIANCE> Rows;
   constexpr int kStride = Rows::kStep * NB;             // rows between a wave's successive groups
   constexpr int kGroups = kNormRowsPerChunk / kStride;  // groups per wave in a full chunk
+  for (int cc = 0; cc < chunks_per_part; ++cc) {
+  const int r0 = (part * chunks_per_part + cc) * kNormRowsPerChunk;
+  if (r0 >= n) break;
+  const int r1 = min(n, r0 + kNormRowsPerChunk);
   if (NB == 4 && kGroups >= 2 && r1 - r0 == kNormRowsPerChunk) {
     // Full chunk: straight-line code over two register buffers, the next group's
     // loads always in flight while the current one is reduced.
@@ -222,6 +227,7 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
       Rows::reduce(raw, lo, rb, r1, ngroups, D, lane, dynamic, norm64, score, norms_out, acc32, wsum);
     }
   }
+  }
   if (!dynamic) return;
 
   // The four waves' vectors meet in LDS, laid out by column; every thread then
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
     *reinterpret_cast<float4*>(&lds[wave][4 * (lane + kWave * k)]) =
         make_float4(acc32[k][0], acc32[k][1], acc32[k][2], acc32[k][3]);
   __syncthreads();
-  double* out = partial + (static_cast<size_t>(b) * chunks_per_image + chunk) * (D + 1);
+  double* out = partial + (static_cast<size_t>(b) * parts_per_image + part) * (D + 1);
   for (int c = threadIdx.x; c < D; c += kNormThreads) {
     double s = 0.0;
 #pragma unroll
@@ -271,7 +277,7 @@ template <int NT>
 __global__ __launch_bounds__(NT) void k_select(
     const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
     const int32_t* __restrict__ keep_in, const float* __restrict__ score,
-    const double* __restrict__ partial, int chunks_per_image, int do_select, int max_tokens,
+    const double* __restrict__ partial, int parts_per_image, int rows_per_part, int do_select, int max_tokens,
     float* __restrict__ phi_out, float* __restrict__ ratio_out, int32_t* __restrict__ keep_out,
     int32_t* __restrict__ sel_idx, const int32_t* __restrict__ status) {
   if (status[0]) return;
@@ -290,8 +296,8 @@ __global__ __launch_bounds__(NT) void k_select(
   float ret32 = p.ratio;
   if (p.dynamic) {
     if (n >= 2) {
-      const int nchunks = (n + kNormRowsPerChunk - 1) / kNormRowsPerChunk;
-      const double* base = partial + static_cast<size_t>(b) * chunks_per_image * (D + 1);
+      const int nchunks = (n + rows_per_part - 1) / rows_per_part;
+      const double* base = partial + static_cast<size_t>(b) * parts_per_image * (D + 1);
       double local = 0.0;
       for (int d = tid; d < D; d += NT) {
         double s = 0.0;
