@@ -146,6 +146,18 @@ int check_ws(const rtprune_batch* in, void* ws, size_t ws_bytes, Layout* L) {
 
 inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EHIP; }
 
+// Compute units of the current device (256 on MI355X; that value if the query fails).
+int compute_units() {
+  static int cached = 0;   // one kind of device per process; a repeated query gives the same value
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  cached = n;
+  return n;
+}
+
 #define RTP_TRY(expr)            \
   do {                           \
     const int rc_ = (expr);      \
@@ -362,7 +374,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
-    hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
+    hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, compute_units(), st);
   }
   if (p.mode & kModeLarge) {
     ProfScope prof(KID_SINKHORN_TALL, s);

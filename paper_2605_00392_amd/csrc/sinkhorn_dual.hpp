@@ -59,22 +59,29 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
   __shared__ int pi[kDualChunks][kDualCols];
 
   // row copy: row `tid` of the augmented kernel
+  // (loads are unconditional, from clamped positions, so that all of a thread's
+  // loads are in flight together; the dustbin row and column hold kz, everything
+  // outside the augmented matrix 0)
   double Kr[kDualCols];
+  {
+    const double* row = Kg + static_cast<long long>(min(tid, m - 1)) * r;
 #pragma unroll
-  for (int c = 0; c < kDualCols; ++c) {
-    double v = 0.0;
-    if (tid <= m && c <= r) v = (tid < m && c < r) ? Kg[static_cast<long long>(tid) * r + c] : kz;
-    Kr[c] = v;
+    for (int c = 0; c < kDualCols; ++c) {
+      const double v = row[min(c, r - 1)];
+      Kr[c] = (tid < m && c < r) ? v : ((tid <= m && c <= r) ? kz : 0.0);
+    }
   }
   // column copy: column j of rows 32 q .. 32 q + 31
   const int j = lane & 31, q = 2 * wave + (lane >> 5);
   double Kc[32];
+  {
+    const double* col = Kg + min(j, r - 1);
 #pragma unroll
-  for (int a = 0; a < 32; ++a) {
-    const int i = 32 * q + a;
-    double v = 0.0;
-    if (i <= m && j <= r) v = (i < m && j < r) ? Kg[static_cast<long long>(i) * r + j] : kz;
-    Kc[a] = v;
+    for (int a = 0; a < 32; ++a) {
+      const int i = 32 * q + a;
+      const double v = col[static_cast<long long>(min(i, m - 1)) * r];
+      Kc[a] = (i < m && j < r) ? v : ((i <= m && j <= r) ? kz : 0.0);
+    }
   }
   const double a_row = tid < m ? 1.0 : static_cast<double>(r);   // row marginal of row tid
   const double b_col = j < r ? 1.0 : static_cast<double>(m);     // column marginal of column j
@@ -196,20 +203,28 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
   __shared__ float pv[NW][kDual48Cols];
   __shared__ int pi[NW][kDual48Cols];
 
+  // Both copies are loaded unconditionally from clamped positions (all loads of a
+  // thread in flight together) and patched afterwards: the dustbin row and column
+  // hold kz, everything outside the augmented matrix 0.
   double Kr[kDual48Cols];
+  {
+    const double* row = Kg + static_cast<long long>(min(tid, m - 1)) * r;
 #pragma unroll
-  for (int c = 0; c < kDual48Cols; ++c) {
-    double v = 0.0;
-    if (tid <= m && c <= r) v = (tid < m && c < r) ? Kg[static_cast<long long>(tid) * r + c] : kz;
-    Kr[c] = v;
+    for (int c = 0; c < kDual48Cols; ++c) {
+      const double v = row[min(c, r - 1)];
+      Kr[c] = (tid < m && c < r) ? v : ((tid <= m && c <= r) ? kz : 0.0);
+    }
   }
+  __builtin_amdgcn_sched_barrier(0);   // the second copy's loads after the first's have landed: registers
   KcT Kc[CR];
+  {
+    const double* col = Kg + min(lane, r - 1);
 #pragma unroll
-  for (int a = 0; a < CR; ++a) {
-    const int i = CR * wave + a;
-    double v = 0.0;
-    if (i <= m && lane <= r) v = (i < m && lane < r) ? Kg[static_cast<long long>(i) * r + lane] : kz;
-    Kc[a] = static_cast<KcT>(v);
+    for (int a = 0; a < CR; ++a) {
+      const int i = CR * wave + a;
+      const double v = col[static_cast<long long>(min(i, m - 1)) * r];
+      Kc[a] = static_cast<KcT>((i < m && lane < r) ? v : ((i <= m && lane <= r) ? kz : 0.0));
+    }
   }
   const double a_row = tid < m ? 1.0 : static_cast<double>(r);
   const double b_col = lane < r ? 1.0 : static_cast<double>(m);
@@ -253,20 +268,40 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
   }
   __syncthreads();
 
-  // plan row and, per column, the wave's best (value, row): the dustbin is row m
-  float* P = (plan_out && tid < m) ? plan_out + po + static_cast<long long>(tid) * r : nullptr;
-  for (int c = 0; c < r; ++c) {
-    float v = -1.f;
-    int idx = 0x7fffffff;
-    if (tid <= m) {
-      double kc = 0.0;
+  // plan row t of P = x_t K_tj y_j from the row copy
+  if (plan_out && tid < m) {
+    float* P = plan_out + po + static_cast<long long>(tid) * r;
 #pragma unroll
-      for (int cc = 0; cc < kDual48Cols; ++cc) kc = (cc == c) ? Kr[cc] : kc;   // static register indexing
-      v = static_cast<float>(x * kc * ys[wave][c]);
-      idx = tid;
-      if (P) P[c] = v;
+    for (int c = 0; c < kDual48Cols; ++c)
+      if (c < r) P[c] = static_cast<float>(x * Kr[c] * ys[wave][c]);
+  }
+  if (!pair_out) return;
+  // per column, the wave's best (value, row): the dustbin is row m
+  if constexpr (std::is_same<KcT, double>::value) {
+    // the fp64 column copy gives the same products as the row copy: lane = column
+    const double* xq = xs + CR * wave;
+    float bv = -1.f;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int a = 0; a < CR; ++a) {
+      const int i = CR * wave + a;
+      const float v = static_cast<float>(xq[a] * Kc[a] * y);
+      if (i <= m && v > bv) { bv = v; bi = i; }
     }
-    if (pair_out) {
+    if (lane < kDual48Cols) { pv[wave][lane] = bv; pi[wave][lane] = bi; }
+  } else {
+    // the fp32 column copy is not exact: entries come from the row copy, one
+    // column at a time, and the wave's lanes (rows) are compared by shuffles
+    for (int c = 0; c < r; ++c) {
+      float v = -1.f;
+      int idx = 0x7fffffff;
+      if (tid <= m) {
+        double kc = 0.0;
+#pragma unroll
+        for (int cc = 0; cc < kDual48Cols; ++cc) kc = (cc == c) ? Kr[cc] : kc;   // static register indexing
+        v = static_cast<float>(x * kc * ys[wave][c]);
+        idx = tid;
+      }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) {
         const float ov = __shfl_xor(v, o, kWave);
@@ -276,7 +311,6 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
       if (lane == 0) { pv[wave][c] = v; pi[wave][c] = idx; }
     }
   }
-  if (!pair_out) return;
   __syncthreads();
   if (tid < r) {
     float bv = pv[0][tid];
@@ -367,10 +401,10 @@ __global__ __launch_bounds__(256) void k_scan_classify(const int32_t* __restrict
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
 // handed out longest-running role first: team C, team B, two-copy (48 columns),
-// one-wave (eight images per workgroup), two-copy (32 columns), two-wave (four
-// images per workgroup).
+// one-wave (eight images per workgroup), two-copy (32 columns), two-wave (two or
+// four images per workgroup).  `cus`: compute units of the device.
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
-                                                               const int32_t* __restrict__ work, int B,
+                                                               const int32_t* __restrict__ work, int B, int cus,
                                                                const int32_t* __restrict__ status) {
   if (status[0]) return;
   constexpr int NV = kWorkLists;
@@ -403,12 +437,20 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   cnt = work[kVariantDual];
   if (blk < cnt) { sinkhorn_dual_image(A, work[NV + kVariantDual * B + blk]); return; }
   blk -= cnt;
-  constexpr int kPairsPerBlock = kWavesPerBlock / PairShape::kWaves;
+  // Two-wave images: four per workgroup, or - when the whole launch then still has
+  // no more workgroups than the chip has CUs (a workgroup of this kernel fills a
+  // CU's registers, so a surplus one waits for a CU to come free) - two, on the
+  // first four waves, so that each wave has a SIMD to itself: the iteration is
+  // bound by instruction issue (1.3 -> 0.7 us).  Waves without an image end at
+  // once; a wave that has ended no longer counts at the workgroup's barriers.
   const int nP = work[kVariantPair];
-  if (blk < (nP + kPairsPerBlock - 1) / kPairsPerBlock) {
-    const int slot = wave / PairShape::kWaves, idx = blk * kPairsPerBlock + slot;
-    sinkhorn_waves_image<PairShape>(A, idx < nP ? work[NV + kVariantPair * B + idx] : -1, slot,
-                                    wave % PairShape::kWaves, lane);
+  const int others = work[kVariantC] + work[kVariantB] + work[kVariantDual48] +
+                     (nA + kWavesPerBlock - 1) / kWavesPerBlock + work[kVariantDual];
+  const int per_block = others + (nP + 1) / 2 <= cus ? 2 : kWavesPerBlock / PairShape::kWaves;
+  if (blk < (nP + per_block - 1) / per_block) {
+    const int slot = wave / PairShape::kWaves, idx = blk * per_block + slot;
+    if (slot >= per_block || idx >= nP) return;
+    sinkhorn_waves_image<PairShape>(A, work[NV + kVariantPair * B + idx], slot, wave % PairShape::kWaves, lane);
   }
 }
 

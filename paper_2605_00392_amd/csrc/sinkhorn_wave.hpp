@@ -102,10 +102,14 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
 #pragma unroll
   for (int a = 0; a < RPT; ++a) {
     const int i = row0 + TR * a;
+    // loads are unconditional (from a clamped position of a valid image, or the
+    // matrix's first entry otherwise) so that all of them are in flight together
+    const double* row = Kg + (active ? static_cast<long long>(min(i, m - 1)) * r : 0);
 #pragma unroll
     for (int c = 0; c < C; ++c) {
+      const double g = row[active ? min(c, r - 1) : 0];
       double v = 0.0;
-      if (active && i <= m && c <= r) v = (i < m && c < r) ? Kg[static_cast<long long>(i) * r + c] : kz;
+      if (active && i <= m && c <= r) v = (i < m && c < r) ? g : kz;
       if ((i > m || !active) && c == 0) v = 1.0;
       K[a][c] = v;
     }
