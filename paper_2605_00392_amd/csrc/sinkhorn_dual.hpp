@@ -465,7 +465,15 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_tall(SinkhornArgs A,
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int blk = blockIdx.x;
   int cnt = work[kVariantTeamTall];
-  if (blk < cnt) { sinkhorn_team_image<TeamTall, float>(A, work[NV + kVariantTeamTall * B + blk], wave, lane); return; }
+  if (blk < cnt) {
+    const int img = work[NV + kVariantTeamTall * B + blk];
+    const int n_img = A.offsets[img + 1] - A.offsets[img];
+    const int r_img = n_img - min(max(A.keep[img], 0), max(n_img, 0));
+    if (r_img <= TeamTall32::kMaxR) sinkhorn_team_image<TeamTall32, float>(A, img, wave, lane);
+    else if (r_img <= TeamTall48::kMaxR) sinkhorn_team_image<TeamTall48, float>(A, img, wave, lane);
+    else sinkhorn_team_image<TeamTall, float>(A, img, wave, lane);
+    return;
+  }
   blk -= cnt;
   cnt = work[kVariantTall];
   if (blk < cnt) sinkhorn_waves_image<TallShape>(A, work[NV + kVariantTall * B + blk], 0, wave, lane);

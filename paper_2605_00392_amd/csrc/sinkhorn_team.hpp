@@ -49,6 +49,10 @@ using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
 // as fp32 values, which the same range condition as for the sweep kernels allows,
 // and widened at each use; all sums and both scaling vectors stay fp64.
 using TeamTall = TeamShape<8, 3, 19, 8>;  // M <= 1216, R <= 64
+// The same rows with fewer column registers, for images whose pruned set leaves the
+// upper column slots empty (the iteration is bound by instruction issue).
+using TeamTall48 = TeamShape<8, 3, 19, 6>;  // R <= 48
+using TeamTall32 = TeamShape<8, 3, 19, 4>;  // R <= 32
 // The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
 // lane, kCols augmented columns.
 struct WaveShape {
@@ -223,6 +227,10 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
       for (int c = 0; c <= CPT; ++c) t[c] = 0.0;
 #pragma unroll
       for (int a = 0; a < RPT; ++a) {
+        if (TR * a >= m) {                   // no row of this pass exists (the same for every thread)
+          xs[rslot][a] = 0.0;
+          continue;
+        }
         double kd[CPT];
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
