@@ -271,8 +271,9 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
 // kernels' matrices are stored in fp32 (only batches that may hold images beyond
 // the 512-row register shapes have any).
 void set_sinkhorn_mode(DevParams& p, const Layout& L) {
-  p.k32 = p.k32 && L.sweep;
-  p.mode = L.sweep ? (kModeLarge | (p.k32 ? kModeF32 : 0)) : 0;
+  const int f32 = p.k32 ? kModeF32 : 0;   // exp's range fits fp32: registers may hold the matrix as fp32
+  p.k32 = p.k32 && L.sweep;               // and the sweep kernels' copy in memory is fp32
+  p.mode = (L.sweep ? kModeLarge : 0) | f32;
 }
 
 // `work` non-null: the same launch also builds the Sinkhorn work lists.

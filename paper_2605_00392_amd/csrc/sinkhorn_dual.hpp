@@ -400,7 +400,7 @@ __global__ __launch_bounds__(256) void k_scan_classify(const int32_t* __restrict
 }
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
-// handed out longest-running role first: team C, team B, two-copy (48 columns),
+// handed out longest-running role first: the wide teams, team C, team B, two-copy (48 columns),
 // one-wave (eight images per workgroup), two-copy (32 columns), two-wave (two or
 // four images per workgroup).  `cus`: compute units of the device.
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
@@ -411,7 +411,16 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   constexpr int kWavesPerBlock = kDualThreads / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int blk = blockIdx.x;
-  int cnt = work[kVariantC];
+  int cnt = work[kVariantWideC];
+  if (blk < cnt) { sinkhorn_team_image<TeamWideC, float>(A, work[NV + kVariantWideC * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantWideB];
+  if (blk < cnt) { sinkhorn_team_image<TeamWideB, float>(A, work[NV + kVariantWideB * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantWideA];
+  if (blk < cnt) { sinkhorn_team_image<TeamWideA, float>(A, work[NV + kVariantWideA * B + blk], wave, lane); return; }
+  blk -= cnt;
+  cnt = work[kVariantC];
   if (blk < cnt) { sinkhorn_team_image<TeamC>(A, work[NV + kVariantC * B + blk], wave, lane); return; }
   blk -= cnt;
   cnt = work[kVariantB];
@@ -444,7 +453,8 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   // bound by instruction issue (1.3 -> 0.7 us).  Waves without an image end at
   // once; a wave that has ended no longer counts at the workgroup's barriers.
   const int nP = work[kVariantPair];
-  const int others = work[kVariantC] + work[kVariantB] + work[kVariantDual48] +
+  const int others = work[kVariantWideA] + work[kVariantWideB] + work[kVariantWideC] + work[kVariantC] +
+                     work[kVariantB] + work[kVariantDual48] +
                      (nA + kWavesPerBlock - 1) / kWavesPerBlock + work[kVariantDual];
   const int per_block = others + (nP + 1) / 2 <= cus ? 2 : kWavesPerBlock / PairShape::kWaves;
   if (blk < (nP + per_block - 1) / per_block) {

@@ -53,6 +53,11 @@ using TeamTall = TeamShape<8, 3, 19, 8>;  // M <= 1216, R <= 64
 // upper column slots empty (the iteration is bound by instruction issue).
 using TeamTall48 = TeamShape<8, 3, 19, 6>;  // R <= 48
 using TeamTall32 = TeamShape<8, 3, 19, 4>;  // R <= 32
+// Heavily pruned images of up to 512 tokens (65 to 224 pruned), likewise held as
+// fp32; between them the three cover every such image with M + R <= 512.
+using TeamWideA = TeamShape<8, 4, 14, 8>;   // M <= 448, R <= 128
+using TeamWideB = TeamShape<8, 5, 24, 6>;   // M <= 384, R <= 192
+using TeamWideC = TeamShape<8, 5, 20, 7>;   // M <= 320, R <= 224
 // The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
 // lane, kCols augmented columns.
 struct WaveShape {
@@ -75,12 +80,13 @@ constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 // or R + 1 <= 48.
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
-              kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kGeneralVariant = 9;
-constexpr int kWorkLists = 9;
+              kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kVariantWideA = 9,
+              kVariantWideB = 10, kVariantWideC = 11, kGeneralVariant = 12;
+constexpr int kWorkLists = 12;
 // What a call launches besides the 512-row register shapes, as the kernels
 // receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
 // tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the
-// kernel matrix's range fits fp32.
+// kernel matrix's range fits fp32 (the shapes that hold it as fp32 may be used).
 constexpr int kModeLarge = 1, kModeF32 = 2;
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
 // pruned tokens.
@@ -101,6 +107,11 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if (TeamC::fits(m, r)) return kVariantC;
+  if (mode & kModeF32) {
+    if (TeamWideA::fits(m, r)) return kVariantWideA;
+    if (TeamWideB::fits(m, r)) return kVariantWideB;
+    if (TeamWideC::fits(m, r)) return kVariantWideC;
+  }
   return kGeneralVariant;
 }
 

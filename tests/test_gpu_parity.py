@@ -197,6 +197,49 @@ def test_tall_register_shapes_at_their_edges():
     assert rep.max_score_abs <= hz.SCORE_ATOL
 
 
+@pytest.mark.parametrize("override", [dict(), dict(eps=0.02), dict(iters=0), dict(iters=1)])
+def test_wide_register_shapes_at_their_edges(override):
+    """Images of at most 512 tokens with 65 to 225 pruned ones, on both sides of the
+    limits of the three shapes that hold such a matrix as fp32 in one workgroup's
+    registers (448 x 128, 384 x 192, 320 x 224); with eps = 0.02 exp's range does not
+    fit fp32 and the general kernel takes them all."""
+    shapes = [(447, 65), (384, 128), (385, 127), (383, 129), (320, 192), (321, 191), (288, 224), (287, 225),
+              (100, 200), (240, 160), (64, 65)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 27, **dict(dict(iters=40), **override))
+    assert max(m + r for m, r in shapes) <= 512
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, f"wide shapes {override}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
+def test_heavily_pruned_400_token_pages_fused():
+    """Dynamic retention at its clamp on 400-token pages whose tokens resemble each other:
+    160 pruned tokens per page, through the fused call."""
+    rng = np.random.default_rng(28)
+    d, imgs = 1024, []
+    for c in [400, 400, 380, 256, 512]:
+        common = rng.standard_normal(d)
+        common /= np.linalg.norm(common)
+        x = common[None, :] + rng.standard_normal((c, d)) / np.sqrt(d)
+        dup = rng.integers(0, c, size=c // 5)
+        x[rng.permutation(c)[:c // 5]] = x[dup] + rng.standard_normal((c // 5, d)) * (0.05 / np.sqrt(d))
+        x *= rng.lognormal(0, 0.3, size=(c, 1))
+        imgs.append(x.astype(np.float32))
+    dens = np.array([0.05, 0.3, 0.1, 0.2, 0.15], dtype=np.float32)
+    batch = synth.pack(0, "bf16", imgs, dens, dict(synth.DEFAULT_PARAMS, dynamic=1, iters=30))
+    f = hz.run_prune(batch)
+    pruned = np.diff(batch.offsets) - f["keep"]
+    assert (pruned > 64).all(), pruned
+    rep = hz.compare_batch(batch, f, staged=False)
+    _log(rep, f"wide fused pruned={list(pruned)}")
+    s = hz.run_staged(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+
+
 @pytest.mark.parametrize("override", [dict(ratio=0.96), dict(ratio=0.99), dict(ratio=0.96, iters=0),
                                       dict(ratio=0.96, eps=0.02)])
 def test_tall_images_fused(override):
