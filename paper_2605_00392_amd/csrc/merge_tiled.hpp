@@ -18,6 +18,7 @@
 #pragma once
 #include "common.hpp"
 #include "scores_mfma.hpp"
+#include "sinkhorn_team.hpp"
 
 namespace rtp {
 
@@ -28,20 +29,39 @@ constexpr int kMergeTilePitch = 80;    // LDS bytes per staged row (32 bf16 + pa
 constexpr int kMergeTiledThreads = 256;
 constexpr int kMergeOutPitch = kMergeTileCols + 4;   // floats per row of the output staging tile
 
-__global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled(
-    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
-    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
-    const int32_t* __restrict__ out_offsets, const float* __restrict__ plan,
-    const long long* __restrict__ plan_offsets, float alpha, int max_tokens, int tiles_d,
-    bf16_t* __restrict__ out, const int32_t* __restrict__ status) {
-  if (status && status[0]) return;
-  const int b = blockIdx.y;
+// What both launch forms of the kernel pass on.
+struct MergeTiledArgs {
+  const bf16_t* tokens;
+  const int32_t* offsets;
+  int D;
+  const int32_t* sel_idx;
+  const int32_t* keep;
+  const int32_t* out_offsets;
+  const float* plan;
+  const long long* plan_offsets;
+  float alpha;
+  int max_tokens, tiles_d;
+  bf16_t* out;
+};
+
+// Tile `tile` (kept-row tile major, feature tile minor) of image b.
+__device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int tile) {
+  const bf16_t* __restrict__ tokens = A.tokens;
+  const int32_t* __restrict__ offsets = A.offsets;
+  const int D = A.D;
+  const int32_t* __restrict__ sel_idx = A.sel_idx;
+  const int32_t* __restrict__ out_offsets = A.out_offsets;
+  const float* __restrict__ plan = A.plan;
+  const long long* __restrict__ plan_offsets = A.plan_offsets;
+  const float alpha = A.alpha;
+  const int max_tokens = A.max_tokens, tiles_d = A.tiles_d;
+  bf16_t* __restrict__ out = A.out;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
   if (lo < 0 || n <= 0 || n > max_tokens) return;
-  const int m = min(max(keep[b], 0), n), r = n - m;
+  const int m = min(max(A.keep[b], 0), n), r = n - m;
   if (r <= kTiledMinPruned) return;                  // k_merge_lds
-  const int ti = blockIdx.x / tiles_d, td = blockIdx.x - ti * tiles_d;
+  const int ti = tile / tiles_d, td = tile - ti * tiles_d;
   const int i0 = ti * kMergeTileRows, d0 = td * kMergeTileCols;
   if (i0 >= m) return;
   const int32_t* sel = sel_idx + lo;
@@ -180,6 +200,29 @@ __global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled(
       }
       *reinterpret_cast<uint4*>(out + (obase + i) * D + d0 + dd) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     }
+  }
+}
+
+// One workgroup per (tile, image): the staged call, and fused calls whose images
+// are known to be large.
+__global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled(MergeTiledArgs A,
+                                                                   const int32_t* __restrict__ status) {
+  if (status && status[0]) return;
+  merge_tile(A, blockIdx.y, blockIdx.x);
+}
+
+// A fixed number of workgroups that walk the tiles of the images on the tiled
+// work list (see k_scores_tiled_list).
+__global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled_list(MergeTiledArgs A, int tiles,
+                                                                        const int32_t* __restrict__ work, int B,
+                                                                        const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int count = work[kListTiled];
+  const long long items = static_cast<long long>(count) * tiles;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    __syncthreads();   // the previous tile's last LDS reads
+    const int k = static_cast<int>(item / tiles);
+    merge_tile(A, work[kWorkLists + kListTiled * B + k], static_cast<int>(item - static_cast<long long>(k) * tiles));
   }
 }
 

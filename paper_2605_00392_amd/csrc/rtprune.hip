@@ -288,6 +288,12 @@ int launch_scan(const rtprune_batch* in, const int32_t* keep, int32_t* out_off, 
   return launched();
 }
 
+// Workgroups of the list forms of the tiled kernels: eight per CU, or all tiles if fewer.
+unsigned tiled_list_blocks(int tiles, int B) {
+  const long long all = static_cast<long long>(tiles) * B;
+  return static_cast<unsigned>(std::min<long long>(all, 8LL * compute_units()));
+}
+
 // Largest pruned set any image of the call can have.  `hint` >= 0: the caller's
 // bound (fixed retention); kPrunedFromClamp: the kept counts come from this
 // call's dynamic ratio, whose clamp bounds them; kPrunedUnknown: the kept counts
@@ -304,7 +310,7 @@ int pruned_bound(const rtprune_batch* in, const DevParams& p, int hint) {
 template <typename T>
 int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
-                    double* scores_out, int max_pruned_hint, hipStream_t s) {
+                    double* scores_out, int max_pruned_hint, const int32_t* work, hipStream_t s) {
   const T* tok = static_cast<const T*>(in->tokens);
   const double* sq = at<double>(ws, L.norm64);
   double* kmat = at<double>(ws, L.kmat);
@@ -338,9 +344,17 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
       if (rmax > kTiledMinPruned) {
         const int tiles_m = (in->max_tokens + kTileRows - 1) / kTileRows;
         const int tiles_n = (rmax + kTileCols - 1) / kTileCols;
-        hipLaunchKernelGGL(k_scores_tiled, dim3(tiles_m * tiles_n, in->B), dim3(kTiledThreads), 0, s, tok,
-                           in->offsets, in->D, sel, keep, plan_off, sq, p, kmat, L.plan_cap, scores_out, tiles_n,
-                           st);
+        const int tiles = tiles_m * tiles_n;
+        const ScoresTiledArgs TA{tok, in->offsets, in->D, sel, keep, plan_off, sq, p, kmat, L.plan_cap, scores_out,
+                                 tiles_n};
+        // pruned sets known to be large (fixed retention): a workgroup per tile and
+        // image; sizes decided on the device, or barely above the threshold: a fixed
+        // number of workgroups over the work list
+        if (max_pruned_hint >= 2 * kTiledMinPruned)
+          hipLaunchKernelGGL(k_scores_tiled, dim3(tiles, in->B), dim3(kTiledThreads), 0, s, TA, st);
+        else
+          hipLaunchKernelGGL(k_scores_tiled_list, dim3(tiled_list_blocks(tiles, in->B)), dim3(kTiledThreads), 0, s,
+                             TA, tiles, work, in->B, st);
       }
       return launched();
     }
@@ -362,9 +376,6 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
   set_sinkhorn_mode(p, L);
-  RTP_TRY(in->dtype == RTP_BF16
-              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s)
-              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, s));
   const double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   int32_t* work = at<int32_t>(ws, L.work);
@@ -372,6 +383,9 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     ProfScope prof(KID_CLASSIFY, s);
     hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.mode, st);
   }
+  RTP_TRY(in->dtype == RTP_BF16
+              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, s)
+              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, s));
   SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
@@ -432,7 +446,7 @@ template <typename T>
 int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                    const int32_t* keep, const int32_t* out_off, const float* plan,
                    const long long* plan_off, void* out, int max_pruned_hint, const int32_t* status,
-                   hipStream_t s) {
+                   const int32_t* work, hipStream_t s) {
   const int tiles = (in->max_tokens + kMergeRowsPerBlock - 1) / kMergeRowsPerBlock;
   const dim3 grid(tiles, in->B), block(256);
   const T* tok = static_cast<const T*>(in->tokens);
@@ -465,9 +479,15 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
     if (tiled) {
       const int tiles_i = (in->max_tokens + kMergeTileRows - 1) / kMergeTileRows;
       const int tiles_d = in->D / kMergeTileCols;
-      hipLaunchKernelGGL(k_merge_tiled, dim3(tiles_i * tiles_d, in->B), dim3(kMergeTiledThreads), 0, s, tok,
-                         in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens, tiles_d,
-                         static_cast<bf16_t*>(out), status);
+      const MergeTiledArgs TA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens,
+                              tiles_d, static_cast<bf16_t*>(out)};
+      // as for the scores: the list form when the sizes were decided on the device
+      // and the call has a work list (the fused calls)
+      if (max_pruned_hint >= 2 * kTiledMinPruned || !work || !status)
+        hipLaunchKernelGGL(k_merge_tiled, dim3(tiles_i * tiles_d, in->B), dim3(kMergeTiledThreads), 0, s, TA, status);
+      else
+        hipLaunchKernelGGL(k_merge_tiled_list, dim3(tiled_list_blocks(tiles_i * tiles_d, in->B)),
+                           dim3(kMergeTiledThreads), 0, s, TA, tiles_i * tiles_d, work, in->B, status);
     }
   }
   return launched();
@@ -475,11 +495,11 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
 
 int launch_merge(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
                  const int32_t* out_off, const float* plan, const long long* plan_off, void* out,
-                 int max_pruned_hint, const int32_t* status, hipStream_t s) {
+                 int max_pruned_hint, const int32_t* status, const int32_t* work, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   return in->dtype == RTP_BF16
-             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, s)
-             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, s);
+             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s)
+             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s);
 }
 
 }  // namespace
@@ -730,7 +750,7 @@ extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(check_params(params, &p));
   if (!sel_idx || !keep_counts || !out_offsets || !plan || !plan_offsets || !out) return RTP_EINVAL;
   return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan,
-                      reinterpret_cast<const long long*>(plan_offsets), out, kPrunedUnknown, nullptr,
+                      reinterpret_cast<const long long*>(plan_offsets), out, kPrunedUnknown, nullptr, nullptr,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -761,7 +781,8 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
-  return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status, s);
+  return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status,
+                      at<int32_t>(workspace, L.work), s);
 }
 
 extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* density,
@@ -813,7 +834,8 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
   // the merge writes image b's kept rows at visual_start[b], between its text spans
-  RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status, s));
+  RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status,
+                       at<int32_t>(workspace, L.work), s));
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SPLICE, s);
   const dim3 grid(64, in->B);

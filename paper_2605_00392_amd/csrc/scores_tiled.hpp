@@ -34,19 +34,40 @@ constexpr int kTiledChain = 1;         // steps (of two 32-term partial products
 
 __host__ __device__ inline bool score_is_tiled(int r) { return r > kTiledMinPruned; }
 
-__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(
-    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
-    const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
-    const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
-    double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out, int tiles_n,
-    const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  const int b = blockIdx.y;
+// What both launch forms of the kernel pass on.
+struct ScoresTiledArgs {
+  const bf16_t* tokens;
+  const int32_t* offsets;
+  int D;
+  const int32_t* sel_idx;
+  const int32_t* keep;
+  const long long* plan_offsets;
+  const double* norm64;
+  DevParams p;
+  double* kmat;
+  long long plan_cap;
+  double* scores_out;
+  int tiles_n;
+};
+
+// Tile `tile` (kept-row tile major) of image b.
+__device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int tile) {
+  const bf16_t* __restrict__ tokens = A.tokens;
+  const int32_t* __restrict__ offsets = A.offsets;
+  const int D = A.D;
+  const int32_t* __restrict__ sel_idx = A.sel_idx;
+  const long long* __restrict__ plan_offsets = A.plan_offsets;
+  const double* __restrict__ norm64 = A.norm64;
+  const DevParams& p = A.p;
+  double* __restrict__ kmat = A.kmat;
+  double* __restrict__ scores_out = A.scores_out;
+  const long long plan_cap = A.plan_cap;
+  const int tiles_n = A.tiles_n;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
-  const int m = min(max(keep[b], 0), n), r = n - m;
+  const int m = min(max(A.keep[b], 0), n), r = n - m;
   if (!score_is_tiled(r)) return;
-  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x - tm * tiles_n;
+  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
   const int i0 = tm * kTileRows, j0 = tn * kTileCols;
   if (i0 >= m || j0 >= r) return;
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
@@ -190,6 +211,30 @@ __global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(
           if (scores_out) scores_out[po + at] = sc;
         }
       }
+  }
+}
+
+// One workgroup per (tile, image): for calls whose images are known to be large
+// (the hardware hands out workgroups as CUs come free, which balances best).
+__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(ScoresTiledArgs A, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  scores_tile(A, blockIdx.y, blockIdx.x);
+}
+
+// A fixed number of workgroups that walk the tiles of the images on the tiled
+// work list: for calls that may well have no such image (kept counts decided on
+// the device), where a grid sized for the worst case would cost more to launch
+// empty than the rest of the call's small kernels together.
+__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled_list(ScoresTiledArgs A, int tiles,
+                                                                    const int32_t* __restrict__ work, int B,
+                                                                    const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int count = work[kListTiled];
+  const long long items = static_cast<long long>(count) * tiles;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    __syncthreads();   // the previous tile's last LDS reads
+    const int k = static_cast<int>(item / tiles);
+    scores_tile(A, work[kWorkLists + kListTiled * B + k], static_cast<int>(item - static_cast<long long>(k) * tiles));
   }
 }
 

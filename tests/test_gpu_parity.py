@@ -293,9 +293,12 @@ def test_multi_workgroup_sinkhorn_other_widths(dtype, d):
     _log(rep, f"sweep {dtype} D={d}")
 
 
-@pytest.mark.parametrize("counts,ratio", [([260], 0.25), ([200, 7 + 193], 0.0174), ([321, 450], 0.4)])
+@pytest.mark.parametrize("counts,ratio", [([260], 0.25), ([200, 7 + 193], 0.0174), ([321, 450], 0.4),
+                                          ([130], 0.5), ([72, 71], 0.09), ([400], 0.8375)])
 def test_matrix_core_tiles_at_their_edges(counts, ratio):
-    """Pruned sets just above the tiled kernels' threshold, tiles cut by both edges."""
+    """Pruned sets just above the tiled kernels' threshold (65 pruned tokens; the second
+    image of the fifth case has 64 and stays below it) and around 192, tiles cut by both
+    edges."""
     batch = _clustered(counts, 1024, "bf16", 23, ratio=ratio, iters=10)
     s = hz.run_staged(batch)
     rep = hz.compare_batch(batch, s, staged=True)
