@@ -74,6 +74,12 @@ WORKLOADS: Dict[int, Workload] = {
                 _params(iters=100, ratio=1238.0 / 2137.0), 2137),
     8: Workload(8, "c8_b16_4512tok_bf16_keep2783", 16, "bf16",
                 _params(iters=100, ratio=2783.0 / 4512.0), 4512),
+    # The benchmark's pages at the average retention the paper reports for its
+    # dynamic ratio on DeepSeek-OCR-Large (Table 2: 337 of 400 tokens kept): with
+    # the default f_normalize the synthetic pages of workload 5 keep 98 %, so this
+    # is the shape of the paper's own operating point (63 pruned tokens per page).
+    9: Workload(9, "c9_b1024_400tok_bf16_keep337", 1024, "bf16",
+                _params(iters=100, ratio=337.0 / 400.0), 400),
 }
 
 
@@ -155,7 +161,7 @@ def gen_image(cfg: int, image: int, d: int = D_MODEL):
         _scale_outliers(rng, x)
         rho = rng.uniform(0.1, 0.9)
         return x.astype(np.float32), np.float32(rho)
-    if cfg in (5, 6, 7, 8):
+    if cfg in (5, 6, 7, 8, 9):
         n = w.fixed_tokens
         n_copy = (3 * n) // 10
         n_base = n - n_copy

@@ -126,7 +126,7 @@ def test_c5_full_batch_sampled_against_oracle():
 
 
 # ------------------------------------------- other OCR models' token counts (Table 6)
-@pytest.mark.parametrize("cfg,images,kept", [(6, 3, 560), (7, 2, 1238), (8, 1, 2783)])
+@pytest.mark.parametrize("cfg,images,kept", [(6, 3, 560), (7, 2, 1238), (8, 1, 2783), (9, 6, 337)])
 def test_large_pages(cfg, images, kept):
     batch = synth.gen_batch(cfg, images=range(images))
     f = hz.run_prune(batch)
