@@ -292,16 +292,41 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
       t[CPT] = acc;
     }
     x_dust = static_cast<double>(r) * rcp64(kz * sum_y);
+    constexpr bool kScatter = W > 1 && LOG_TC == 3 && CPT <= 8;
+    if constexpr (kScatter) {
+      // Eight column slots x eight row slots per wave, up to eight column sums per
+      // lane (taken as eight): the sums over the row slots (lane bits 3-5) are a
+      // reduce-scatter - each exchange hands half of the values to the partner,
+      // 4 + 2 + 1 additions instead of 3 per value - which leaves the wave's total of
+      // column cslot + 8 (4 b5 + 2 b4 + b3) in this lane, where it goes to LDS directly.
+      auto tv = [&](int c) { return c < CPT ? t[c < CPT ? c : 0] : 0.0; };
+      double h[4], q[2];
 #pragma unroll
-    for (int c = 0; c <= CPT; ++c) t[c] = cross_sum<LOG_TC>(t[c]);
+      for (int c = 0; c < 4; ++c) h[c] = halve32(tv(c), tv(c + 4));
+#pragma unroll
+      for (int c = 0; c < 2; ++c) q[c] = halve16(h[c], h[c + 2]);
+      const bool b3 = (lane & 8) != 0;
+      const double keep = b3 ? q[1] : q[0], send = b3 ? q[0] : q[1];
+      const double mine = keep + dpp_move<0x128>(send);              // lane ^ 8
+      const int c_own = 4 * (lane >> 5) + 2 * ((lane >> 4) & 1) + (b3 ? 1 : 0);
+      if (c_own < CPT) xw[tw][cslot][c_own] = mine;
+      t[CPT] = cross_sum<LOG_TC>(t[CPT]);
+      if (lane < TC) xw[tw][lane][CPT] = t[CPT];
+      __syncthreads();
+    } else {
+#pragma unroll
+      for (int c = 0; c <= CPT; ++c) t[c] = cross_sum<LOG_TC>(t[c]);
+    }
     if (W > 1) {
       // wave totals -> LDS; one thread per (column slot, value) adds the W
       // partials; everybody reads back its CPT + 1 totals
-      if (lane < TC) {
+      if constexpr (!kScatter) {
+        if (lane < TC) {
 #pragma unroll
-        for (int c = 0; c <= CPT; ++c) xw[tw][lane][c] = t[c];
+          for (int c = 0; c <= CPT; ++c) xw[tw][lane][c] = t[c];
+        }
+        __syncthreads();
       }
-      __syncthreads();
       if (tt < TC * (CPT + 1)) {
         const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
         double acc = 0.0;
