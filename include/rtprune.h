@@ -176,11 +176,18 @@ int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
  * T[kept_i] + alpha * sum_j plan[i][j] * T[pruned_j] for image b (fp32
  * accumulation, one rounding to the token dtype); an image with R_b = 0 is
  * copied through.
- *   out   [sum M_b, D] same dtype as the tokens */
+ *   out        [sum M_b, D] same dtype as the tokens
+ *   workspace  as for the other calls, or NULL (then workspace_bytes is
+ *              ignored).  With a workspace the call sorts the images by their
+ *              pruned count first and runs the same kernels as the fused calls,
+ *              so its output equals theirs bit for bit; without one, images
+ *              with 17 to 64 pruned tokens take the slower vector kernel, whose
+ *              fp32 sums are ordered differently. */
 int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
                   const int32_t* keep_counts, const int32_t* out_offsets,
                   const float* plan, const int64_t* plan_offsets,
-                  const rtprune_params* params, void* out, void* stream);
+                  const rtprune_params* params, void* out, void* workspace,
+                  size_t workspace_bytes, void* stream);
 
 /* The whole operator (Algorithm 1) on a ragged batch, one enqueue, no host
  * synchronisation: [ratio ->] stage 1 -> stage 2 -> merge.
@@ -278,6 +285,15 @@ int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_offsets,
  * into the host buffer `buf` of `cap` bytes (RTP_EINVAL if it does not fit). */
 int rtprune_profile_enable(int on);
 int rtprune_profile_summary(char* buf, size_t cap);
+
+/* Tuning and test aid (process-global, not thread-safe).  Images with 17 to 64
+ * pruned tokens have a merge kernel of their own (matrix cores fed straight
+ * from memory), which the calls with a workspace run only when the batch holds
+ * at least `min_images` of them; a few cost less inside the vector kernel's
+ * launch.  The default (restored by a negative value) is four 128-row tiles per
+ * compute unit: 256 images of 400 tokens on MI355X.  Returns the value in force
+ * before the call (-1: the default). */
+int rtprune_mid_merge_min_images(int min_images);
 
 /* Measurement aid: a plain device-to-device copy kernel (`k_copy`) of `bytes`
  * bytes (a multiple of 16; both pointers 16-byte aligned, non-overlapping).

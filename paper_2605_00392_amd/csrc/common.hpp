@@ -22,6 +22,25 @@ typedef unsigned short bf16_t;     // raw bfloat16 bit pattern
 // 1.3 to 2 times faster than the vector kernel and the tiled scores are level or
 // better.)
 constexpr int kTiledMinPruned = 64;
+// Between kMergeMidMin and kTiledMinPruned pruned tokens the merge runs on the
+// matrix cores without staging (k_merge_mfma; bf16 tokens, width a multiple of 64).
+constexpr int kMergeMidMin = 16;
+__host__ __device__ inline bool merge_is_mid(int r) { return r > kMergeMidMin && r <= kTiledMinPruned; }
+// Which images the vector merge kernels leave to the others.  The middling ones
+// only when the call has many (`mid_count`, counted on the device, at least
+// `mid_min`): a few of them cost less inside the vector kernel's one large launch
+// than as two short launches of their own.
+constexpr int kSkipTiled = 1, kSkipMid = 2;
+struct MergeSkip {
+  int mask;
+  const int32_t* mid_count;   // device; read only when mask has kSkipMid
+  int mid_min;
+};
+__device__ __forceinline__ bool merge_mid_runs(const int32_t* mid_count, int mid_min) { return *mid_count >= mid_min; }
+__device__ __forceinline__ bool merge_elsewhere(const MergeSkip& k, int r) {
+  if ((k.mask & kSkipTiled) && r > kTiledMinPruned) return true;
+  return (k.mask & kSkipMid) && merge_is_mid(r) && merge_mid_runs(k.mid_count, k.mid_min);
+}
 
 struct DevParams {
   double z, alpha, eps;

@@ -348,6 +348,7 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
       for (int u = 0; u < NV; ++u) c[u] += (u == v);
     }
     if (n > 0 && n - m > kTiledMinPruned) c[kListTiled] += 1;
+    if (n > 0 && merge_is_mid(n - m)) c[kListMid] += 1;
   }
 #pragma unroll
   for (int v = 0; v < NV; ++v) cnt[v][tid] = c[v];
@@ -374,6 +375,7 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
         if (u == v) work[NV + u * B + at[u]++] = b;
     }
     if (n > 0 && n - m > kTiledMinPruned) work[NV + kListTiled * B + at[kListTiled]++] = b;
+    if (n > 0 && merge_is_mid(n - m)) work[NV + kListMid * B + at[kListMid]++] = b;
   }
   if (tid == 255) {
 #pragma unroll

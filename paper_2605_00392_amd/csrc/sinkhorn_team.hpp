@@ -84,7 +84,7 @@ constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3
               kVariantWideB = 10, kVariantWideC = 11, kGeneralVariant = 12;
 // The work lists k_classify builds: one per register-resident shape above, and
 // one of the images whose scores and merge go to the tiled matrix-core kernels.
-constexpr int kListTiled = 12, kWorkLists = 13;
+constexpr int kListTiled = 12, kListMid = 13, kWorkLists = 14;
 // What a call launches besides the 512-row register shapes, as the kernels
 // receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
 // tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void k_merge(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
     const int32_t* __restrict__ out_offsets, const float* __restrict__ plan,
-    const long long* __restrict__ plan_offsets, float alpha, int max_tokens, int tiled, T* __restrict__ out,
+    const long long* __restrict__ plan_offsets, float alpha, int max_tokens, MergeSkip skip, T* __restrict__ out,
     const int32_t* __restrict__ status) {
   if (status && status[0]) return;
   const int b = blockIdx.y;
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void k_merge(
   if (lo < 0 || n <= 0 || n > max_tokens) return;
   const int m = min(max(keep[b], 0), n), r = n - m;
   const int i0 = blockIdx.x * kMergeRowsPerBlock;
-  if (i0 >= m || (tiled && r > kTiledMinPruned)) return;   // large pruned sets: k_merge_tiled
+  if (i0 >= m || merge_elsewhere(skip, r)) return;   // larger pruned sets: the matrix-core kernels
   const int rows = min(kMergeRowsPerBlock, m - i0);
   const int ngroups = D >> 2;
   const int32_t* sel = sel_idx + lo;

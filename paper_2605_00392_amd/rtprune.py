@@ -26,7 +26,7 @@ EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune", "rtprune_prune_splice",
     "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_copy_bytes",
-    "rtprune_text_density_workspace_bytes", "rtprune_text_density",
+    "rtprune_text_density_workspace_bytes", "rtprune_text_density", "rtprune_mid_merge_min_images",
 )
 
 
@@ -86,12 +86,14 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_ot_pair.restype = ctypes.c_int
     lib.rtprune_ot_pair.argtypes = [pb, vp, vp, vp, pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.rtprune_merge.restype = ctypes.c_int
-    lib.rtprune_merge.argtypes = [pb, vp, vp, vp, vp, vp, pp, vp, vp]
+    lib.rtprune_merge.argtypes = [pb, vp, vp, vp, vp, vp, pp, vp, vp, ctypes.c_size_t, vp]
     lib.rtprune_prune.restype = ctypes.c_int
     lib.rtprune_prune.argtypes = [pb, vp, pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.rtprune_prune_splice.restype = ctypes.c_int
     lib.rtprune_prune_splice.argtypes = [pb, vp, pp, ctypes.POINTER(rtprune_text_spans), i32, vp, ctypes.c_int64,
                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.rtprune_mid_merge_min_images.restype = ctypes.c_int
+    lib.rtprune_mid_merge_min_images.argtypes = [ctypes.c_int]
     lib.rtprune_profile_enable.restype = ctypes.c_int
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_summary.restype = ctypes.c_int
@@ -217,11 +219,12 @@ def rtprune_ot_pair(batch: DeviceBatch, sel_idx, keep_counts, plan_offsets, para
 
 
 def rtprune_merge(batch: DeviceBatch, sel_idx, keep_counts, out_offsets, plan, plan_offsets,
-                  params: rtprune_params, out, stream=None) -> int:
+                  params: rtprune_params, out, workspace=None, stream=None) -> int:
     d = batch.desc()
     return load_library().rtprune_merge(
         ctypes.byref(d), _addr(sel_idx), _addr(keep_counts), _addr(out_offsets), _addr(plan),
-        _addr(plan_offsets), ctypes.byref(params), _addr(out), _stream(stream))
+        _addr(plan_offsets), ctypes.byref(params), _addr(out), _addr(workspace),
+        workspace.numel() if workspace is not None else 0, _stream(stream))
 
 
 def rtprune_prune(batch: DeviceBatch, density, params: rtprune_params, out, out_offsets,
@@ -249,6 +252,10 @@ def rtprune_prune_splice(batch: DeviceBatch, density, params: rtprune_params, te
         _addr(seq), int(seq_capacity_rows), _addr(seq_offsets), _addr(position_ids), _addr(keep_counts),
         _addr(sel_idx), _addr(pair), _addr(ratio), _addr(workspace),
         workspace.numel() if workspace is not None else 0, _stream(stream))
+
+
+def rtprune_mid_merge_min_images(min_images: int) -> int:
+    return load_library().rtprune_mid_merge_min_images(int(min_images))
 
 
 def rtprune_profile_enable(on: int) -> int:

@@ -97,7 +97,7 @@ def run_staged(batch: synth.Batch, params: Optional[Dict] = None, keep_counts_in
     rt.check(rt.rtprune_ot_pair(db, sel, keep, plan_off, p, scores, plan, pair, ws))
     torch.cuda.synchronize()
     out = torch.zeros((max(n_out, 1), db.D), dtype=db.tokens.dtype, device=device)
-    rt.check(rt.rtprune_merge(db, sel, keep, out_off, plan, plan_off, p, out))
+    rt.check(rt.rtprune_merge(db, sel, keep, out_off, plan, plan_off, p, out, ws))
     torch.cuda.synchronize()
     res.update(status=device_status(ws), norms=_np(norms)[:total], sel=_np(sel)[:total], keep=_np(keep)[:B],
                out_offsets=_np(out_off), plan_offsets=_np(plan_off), scores=_np(scores)[:n_plan],

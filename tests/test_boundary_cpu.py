@@ -138,7 +138,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert rt.rtprune_dynamic_ratio(b, None, ok, None, None, 0x6000, ws, stream=0) == rt.RTP_EINVAL
     assert rt.rtprune_norms_topk(b, None, ok, None, None, 0x6000, 0x7000, 0x8000, ws, stream=0) == rt.RTP_EINVAL
     assert rt.rtprune_ot_pair(b, None, 0x6000, 0x8000, ok, None, None, None, ws, stream=0) == rt.RTP_EINVAL
-    assert rt.rtprune_merge(b, 0x6000, 0x6100, 0x6200, None, 0x8000, ok, 0x9000, stream=0) == rt.RTP_EINVAL
+    assert rt.rtprune_merge(b, 0x6000, 0x6100, 0x6200, None, 0x8000, ok, 0x9000, ws, stream=0) == rt.RTP_EINVAL
     # splice: position mode, capacity (64 tokens + 10 prefix rows need 74), text pointers
     txt = rt.make_text_spans(0xA000, 0xB000, 10)
     sp = lambda text, mode, cap, seq=0x4000: rt.rtprune_prune_splice(b, None, ok, text, mode, seq, cap, 0x5000, None,

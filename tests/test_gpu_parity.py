@@ -125,6 +125,25 @@ def test_c5_full_batch_sampled_against_oracle():
     np.testing.assert_array_equal(f["pair"], g["pair"])
 
 
+def test_c9_full_batch_sampled_against_oracle():
+    """The benchmark's pages at the paper's average retention (Table 2), whole batch: 63 pruned
+    tokens per page, enough pages for the matrix-core merge kernel of the middling pruned sets
+    to run by default."""
+    batch = synth.gen_batch(9)
+    assert batch.batch == 1024 and batch.total_tokens == 409600
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    assert (f["keep"] == 337).all()
+    rng = np.random.default_rng(9)
+    picks = sorted(rng.choice(1024, size=12, replace=False).tolist())
+    _log(hz.compare_batch(batch, f, images=picks), "c9 fused (12 sampled images)")
+    for b in range(0, 1024, 41):
+        sel = f["sel"][b * 400:(b + 1) * 400]
+        assert sorted(sel.tolist()) == list(range(400))
+    g = hz.run_prune(batch)
+    np.testing.assert_array_equal(f["out"], g["out"])
+
+
 # ------------------------------------------- other OCR models' token counts (Table 6)
 @pytest.mark.parametrize("cfg,images,kept", [(6, 3, 560), (7, 2, 1238), (8, 1, 2783), (9, 6, 337)])
 def test_large_pages(cfg, images, kept):
@@ -307,6 +326,51 @@ def test_matrix_core_tiles_at_their_edges(counts, ratio):
     f = hz.run_prune(batch)
     rows = int(s["out_offsets"][-1])
     np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+
+
+@pytest.mark.parametrize("counts,ratio,d", [
+    ([100, 116, 96], 0.83, 1024),      # 17, 19 and 16 pruned tokens: the last stays with the vector kernel
+    ([160, 161], 0.8, 1280),           # 32 pruned tokens (one operand block), 128 and 129 kept rows
+    ([193, 40], 0.665, 1024),          # 64 pruned tokens, rows cut by a tile; a 13-token pruned set beside it
+    ([400, 400], 0.8425, 1280),        # the paper's average retention on a 400-token page
+    ([97, 50], 0.34, 256),             # fewer kept rows than a wave takes, 64 and 33 pruned
+    ([120, 300], 0.6, 192),            # width a multiple of 64 only; the second image is beyond the range
+    ([120], 0.6, 96),                  # width no multiple of 64: the vector kernel
+])
+def test_unstaged_matrix_core_merge_at_its_edges(counts, ratio, d):
+    """Pruned sets of 17 to 64 tokens (the merge kernel that feeds the matrix cores straight
+    from memory), at both ends of the range, with kept rows cut by its 32- and 128-row blocks."""
+    batch = _clustered(counts, d, "bf16", 29, ratio=ratio, iters=10)
+    before = rt.rtprune_mid_merge_min_images(1)     # by default only batches with hundreds of them run it
+    try:
+        s = hz.run_staged(batch)
+        f = hz.run_prune(batch)
+    finally:
+        rt.rtprune_mid_merge_min_images(before)
+    rep = hz.compare_batch(batch, s, staged=True)
+    _log(rep, f"mid merge {counts} {ratio} D={d}")
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    v = hz.run_prune(batch)                         # and the same images through the vector kernel
+    rep = hz.compare_batch(batch, v, staged=False)
+    _log(rep, f"mid merge, vector kernel {counts} {ratio} D={d}")
+
+
+def test_merge_without_workspace():
+    """The merge entry point without a workspace (vector kernel for every small pruned set)."""
+    import torch
+    batch = _clustered([160, 97, 300, 40], 1024, "bf16", 31, ratio=0.7, iters=10)
+    s = hz.run_staged(batch)
+    db = rt.upload(batch, "cuda:0")
+    dev = lambda a, t: torch.from_numpy(np.ascontiguousarray(a)).to(t).cuda()
+    out = torch.zeros((int(s["out_offsets"][-1]), db.D), dtype=db.tokens.dtype, device="cuda:0")
+    rt.check(rt.rtprune_merge(db, dev(s["sel"], torch.int32), dev(s["keep"], torch.int32),
+                              dev(s["out_offsets"], torch.int32), dev(s["plan"], torch.float32),
+                              dev(s["plan_offsets"], torch.int64), rt.make_params(batch.params), out, None))
+    torch.cuda.synchronize()
+    got = dict(s, out=hz._np(out))
+    rep = hz.compare_batch(batch, got, staged=True)
+    _log(rep, "merge without workspace")
 
 
 # ------------------------------------------------------------------ parameter sweeps
