@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP64_VECTOR_TFLOPS = 78.6      # 256 CU x 2.4 GHz x 128 flop/clk
 FP32_VECTOR_TFLOPS = 157.3     # fp32 vector peak
 BF16_MFMA_TFLOPS = 2500.0      # dense bf16 matrix-core peak
+COMPUTE_UNITS = 256
 
 
 def _gen_one(args):
@@ -75,15 +76,32 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
         return "hbm", tok_bytes + 12.0 * n.sum(), "GB/s", HBM_PEAK_GBS
     if kernel == "k_merge":
         # kept and pruned rows read once, merged kept rows written once, plan read;
-        # one fp32 multiply-add per (kept, pruned, d).  With many pruned tokens per image
-        # the arithmetic outweighs the traffic (ridge of the fp32 vector units: 20 flop/B)
+        # one fp32 multiply-add per (kept, pruned, d)
         nbytes = tok_bytes + float(m.sum()) * d * elt + 4.0 * float((m * r).sum())
         flops = 2.0 * float((m * r).sum()) * d
-        if flops / nbytes > FP32_VECTOR_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-            if elt == 2 and d % 128 == 0 and r.max(initial=0) > 64:
-                # pruned sets of more than 64 go to the matrix cores (useful flops: the
-                # plan's two bf16 terms double the executed ones)
+        # Which unit does the multiply-adds: pruned sets of more than 64 go to the matrix
+        # cores (bf16, width a multiple of 128), and so do those of 17 to 64 (width a
+        # multiple of 64) when the batch holds enough of them to fill the chip (four
+        # 128-row tiles per compute unit); the rest runs on the fp32 vector units.
+        on_mfma = np.zeros(len(n), bool)
+        if elt == 2 and d % 128 == 0:
+            on_mfma |= r > 64
+        mid = (r > 16) & (r <= 64)
+        tiles = max(1, -(-int(n.max(initial=1)) // 128))
+        if elt == 2 and d % 64 == 0 and mid.sum() >= max(1, -(-4 * COMPUTE_UNITS // tiles)):
+            on_mfma |= mid
+        mfma_share = float((m * r)[on_mfma].sum()) / max(1.0, float((m * r).sum()))
+        if mfma_share > 0.5:
+            # (useful flops: the plan's two bf16 terms double the executed ones)
+            if flops / nbytes > BF16_MFMA_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
                 return "mfma", flops, "TFLOP/s", BF16_MFMA_TFLOPS
+            if r.max(initial=0) > 64:
+                # the LDS-tiled kernel re-reads its operands per tile: priced as a contraction
+                return "mfma", flops, "TFLOP/s", BF16_MFMA_TFLOPS
+            return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
+        # vector units: with many pruned tokens per image the arithmetic outweighs the
+        # traffic (ridge of the fp32 vector units: 20 flop/B)
+        if flops / nbytes > FP32_VECTOR_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
             return "alu", flops, "TFLOP/s", FP32_VECTOR_TFLOPS
         return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
     if kernel == "k_scores":
