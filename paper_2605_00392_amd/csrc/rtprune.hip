@@ -332,14 +332,16 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
       const dim3 grid((in->max_tokens + rows_per_block - 1) / rows_per_block, in->B), block(64 * kMfmaWaves);
       int nt = 1;
       if (max_pruned_hint >= 0) nt = score_tiles_per_pass(max_pruned_hint);
+      // (NT > 1 deals an image's workgroups to one XCD and wants B rounded up to eight)
+      const dim3 grid8(grid.x, (in->B + 7) / 8 * 8);
       if (nt == 1)
-        hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+        hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
                            sq, p, kmat, L.plan_cap, scores_out, st);
       else if (nt == 2)
-        hipLaunchKernelGGL((k_scores_mfma<2>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+        hipLaunchKernelGGL((k_scores_mfma<2>), grid8, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
                            sq, p, kmat, L.plan_cap, scores_out, st);
       else
-        hipLaunchKernelGGL((k_scores_mfma<4>), grid, block, 0, s, tok, in->offsets, in->D, sel, keep, plan_off,
+        hipLaunchKernelGGL((k_scores_mfma<4>), grid8, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
                            sq, p, kmat, L.plan_cap, scores_out, st);
       RTP_TRY(launched());
       // images with many pruned tokens: the LDS-tiled kernel.  Largest pruned set

@@ -48,7 +48,7 @@ inline int score_tiles_per_pass(int max_pruned) {
 
 template <int NT>
 __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
-    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int D,
+    const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int B, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
     const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
     double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
@@ -59,12 +59,27 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
   // to last and the merge after it does so again, so each pass starts on the
   // images its predecessor touched last, which are the ones the memory-side cache
   // still holds (measured on 1 GB batches: 2 % off this kernel, 1 % off the merge).
-  const int b = gridDim.y - 1 - blockIdx.y;
+  //
+  // With more than one column tile per pass (NT > 1: the call may have pruned sets
+  // of 17 tokens and more) every wave of an image re-reads a sizeable pruned set,
+  // so the image's workgroups are given linear ids of one residue modulo eight:
+  // workgroups are dealt to the eight XCDs in turn, and the set is then fetched
+  // into one L2 instead of eight (1024 pages with 63 pruned tokens each: 2.4 GB
+  // fetched from memory without this, against 1.05 GB of tokens).  The grid's y
+  // extent is B rounded up to a multiple of eight for it.
+  int by = blockIdx.y, bx = blockIdx.x;
+  if (NT > 1) {
+    const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y, slot = linear >> 3;
+    by = static_cast<int>(slot / gridDim.x) * 8 + static_cast<int>(linear & 7);
+    bx = static_cast<int>(slot % gridDim.x);
+    if (by >= B) return;
+  }
+  const int b = B - 1 - by;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
   const int m = min(max(keep[b], 0), n), r = n - m;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i0 = (blockIdx.x * kMfmaWaves + wave) * kMfmaRowsPerWave;
+  const int i0 = (bx * kMfmaWaves + wave) * kMfmaRowsPerWave;
   if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // larger pruned sets: k_scores_tiled
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
