@@ -287,8 +287,8 @@ int rtprune_profile_enable(int on);
 int rtprune_profile_summary(char* buf, size_t cap);
 
 /* Tuning and test aid (process-global, not thread-safe).  Images with 17 to 64
- * pruned tokens have a merge kernel of their own (matrix cores fed straight
- * from memory), which the calls with a workspace run only when the batch holds
+ * pruned tokens have a merge kernel of their own (the kept rows streamed past
+ * the matrix cores), which the calls with a workspace run only when the batch holds
  * at least `min_images` of them; a few cost less inside the vector kernel's
  * launch.  The default (restored by a negative value) is four 128-row tiles per
  * compute unit: 256 images of 400 tokens on MI355X.  Returns the value in force

@@ -38,7 +38,6 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 // Byte offsets of the workspace regions for a batch shape.
 struct Layout {
   size_t status, norm64, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
-  size_t tpt;           // transposed pruned rows for k_merge_mfma (0: none)
   size_t sw_x, sw_y, sw_colpart, sw_xpart, sw_ysum, sw_ydust, sw_bestv, sw_besti;   // sweep Sinkhorn state
   int chunks_per_image, chunks_per_part, parts_per_image;
   int sweep;            // the batch may hold images beyond the register-resident Sinkhorn shapes
@@ -73,8 +72,6 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   L.work = take(sizeof(int32_t) * kWorkLists * (1 + static_cast<size_t>(B)));
   L.kmat = take(sizeof(double) * L.plan_cap);
   L.plan = take(sizeof(float) * L.plan_cap);
-  // 64 pruned rows of every image, transposed (the merge of images with 17 to 64 pruned tokens)
-  L.tpt = (D % kMergeMidFeatures == 0 && max_tokens > kMergeMidMin) ? take(sizeof(bf16_t) * merge_mid_copy_elems(D) * B) : 0;
   // more than 512 tokens: an image can have more kept tokens than any register shape holds
   L.sweep = max_tokens > 512 ? 1 : 0;
   L.strip_cap = L.plan_cap / kSweepRows + total + 1;
@@ -454,7 +451,7 @@ template <typename T>
 int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                    const int32_t* keep, const int32_t* out_off, const float* plan,
                    const long long* plan_off, void* out, int max_pruned_hint, const int32_t* status,
-                   const int32_t* work, bf16_t* tpt, hipStream_t s) {
+                   const int32_t* work, hipStream_t s) {
   const int tiles = (in->max_tokens + kMergeRowsPerBlock - 1) / kMergeRowsPerBlock;
   const dim3 grid(tiles, in->B), block(256);
   const T* tok = static_cast<const T*>(in->tokens);
@@ -463,9 +460,9 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   // multiple of 128) when the call can produce any
   const int rmax = pruned_bound(in, p, max_pruned_hint);
   const bool tiled = std::is_same<T, bf16_t>::value && in->D % 128 == 0 && rmax > kTiledMinPruned;
-  // and those with a middling number to the unstaged one, when the call has the
-  // work lists and the room for the transposed rows (the fused calls)
-  const bool mid = std::is_same<T, bf16_t>::value && in->D % kMergeMidFeatures == 0 && rmax > kMergeMidMin && work && status && tpt;
+  // and those with a middling number to the one that streams the kept rows, when the
+  // call has the work lists (a workspace)
+  const bool mid = std::is_same<T, bf16_t>::value && in->D % kMergeMidFeatures == 0 && rmax > kMergeMidMin && work && status;
   // (when the device counts enough of them to fill the chip: four row tiles per compute unit)
   const int tiles_mid = (in->max_tokens + kMergeMidBlockRows - 1) / kMergeMidBlockRows;
   const int mid_min = g_mid_min_images >= 0 ? g_mid_min_images
@@ -493,15 +490,14 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   RTP_TRY(launched());
   if constexpr (std::is_same<T, bf16_t>::value) {
     if (mid) {
-      const int tiles_f = in->D / kMergeMidFeatures;
-      hipLaunchKernelGGL(k_transpose_pruned, dim3(tiled_list_blocks(tiles_f, in->B)), dim3(256), 0, s, tok, in->offsets,
-                         in->D, sel, keep, tpt, work, in->B, mid_min, status);
-      RTP_TRY(launched());
       const int tiles_i = tiles_mid;
-      const MergeMidArgs MA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens, tpt,
+      const MergeMidArgs MA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens,
                             static_cast<bf16_t*>(out)};
-      hipLaunchKernelGGL(k_merge_mfma, dim3((tiled_list_blocks(tiles_i, in->B) + 7) / 8 * 8), dim3(kMergeMidThreads), 0, s, MA,
-                         tiles_i, work, in->B, mid_min, status);
+      const dim3 gm((tiled_list_blocks(tiles_i, in->B) + 7) / 8 * 8);
+      if (in->D % (2 * kMergeMidFeatures) == 0)
+        hipLaunchKernelGGL(k_merge_mfma<2>, gm, dim3(kMergeMidThreads), 0, s, MA, tiles_i, work, in->B, mid_min, status);
+      else
+        hipLaunchKernelGGL(k_merge_mfma<1>, gm, dim3(kMergeMidThreads), 0, s, MA, tiles_i, work, in->B, mid_min, status);
       RTP_TRY(launched());
     }
     if (tiled) {
@@ -523,11 +519,11 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
 
 int launch_merge(const rtprune_batch* in, const DevParams& p, const int32_t* sel, const int32_t* keep,
                  const int32_t* out_off, const float* plan, const long long* plan_off, void* out,
-                 int max_pruned_hint, const int32_t* status, const int32_t* work, bf16_t* tpt, hipStream_t s) {
+                 int max_pruned_hint, const int32_t* status, const int32_t* work, hipStream_t s) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   return in->dtype == RTP_BF16
-             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, tpt, s)
-             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, nullptr, s);
+             ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s)
+             : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s);
 }
 
 }  // namespace
@@ -787,7 +783,7 @@ extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
   const long long* plan_off = reinterpret_cast<const long long*>(plan_offsets);
   if (!workspace)   // the vector kernel, and the tiled one over a worst-case grid
     return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan, plan_off, out, kPrunedUnknown, nullptr,
-                        nullptr, nullptr, s);
+                        nullptr, s);
   // with a workspace the images are sorted by pruned count first, as in the fused calls
   Layout L;
   RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
@@ -799,8 +795,7 @@ extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
     hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep_counts, in->B, work, 0, status);
     RTP_TRY(launched());
   }
-  return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan, plan_off, out, kPrunedUnknown, status, work,
-                      L.tpt ? at<bf16_t>(workspace, L.tpt) : nullptr, s);
+  return launch_merge(in, p, sel_idx, keep_counts, out_offsets, plan, plan_off, out, kPrunedUnknown, status, work, s);
 }
 
 extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
@@ -831,7 +826,7 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
   return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status,
-                      at<int32_t>(workspace, L.work), L.tpt ? at<bf16_t>(workspace, L.tpt) : nullptr, s);
+                      at<int32_t>(workspace, L.work), s);
 }
 
 extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* density,
@@ -884,7 +879,7 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
   // the merge writes image b's kept rows at visual_start[b], between its text spans
   RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status,
-                       at<int32_t>(workspace, L.work), L.tpt ? at<bf16_t>(workspace, L.tpt) : nullptr, s));
+                       at<int32_t>(workspace, L.work), s));
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SPLICE, s);
   const dim3 grid(64, in->B);
