@@ -84,6 +84,14 @@ def test_workspace_bytes(lib):
     assert rt.rtprune_workspace_bytes(1, 10000, 10000, 1280, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
 
 
+def test_mid_merge_minimum_is_a_process_wide_setting(lib):
+    """The tuning aid returns the value in force before the call; negative restores the default."""
+    assert rt.rtprune_mid_merge_min_images(3) == -1
+    assert rt.rtprune_mid_merge_min_images(0) == 3
+    assert rt.rtprune_mid_merge_min_images(-5) == 0
+    assert rt.rtprune_mid_merge_min_images(-1) == -1
+
+
 def _fake_batch(**kw):
     # addresses are never dereferenced: every call below must fail validation first
     v = dict(tokens=0x1000, offsets=0x2000, total_tokens=64, max_tokens=64, B=1, D=1280, dtype=rt.RTP_BF16)
