@@ -322,24 +322,10 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
     // 6e-8 sqrt(32 / D) of the cosine, which the pairing's near-tie band covers from
     // D = 1024 up; narrower tokens take the fp64 vector kernel.
     if (in->D % 128 == 0 && in->D >= kMfmaMinWidth) {
-      // matrix-core path.  With a fixed retention the pruned-set size is known up
-      // to rounding; with the dynamic ratio it is usually a few percent of the
-      // image, so the leanest shape is used and larger sets take several passes.
-      const int rows_per_block = kMfmaRowsPerWave * kMfmaWaves;
-      const dim3 grid((in->max_tokens + rows_per_block - 1) / rows_per_block, in->B), block(64 * kMfmaWaves);
-      int nt = 1;
-      if (max_pruned_hint >= 0) nt = score_tiles_per_pass(max_pruned_hint);
-      // (NT > 1 deals an image's workgroups to one XCD and wants B rounded up to eight)
-      const dim3 grid8(grid.x, (in->B + 7) / 8 * 8);
-      if (nt == 1)
-        hipLaunchKernelGGL((k_scores_mfma<1>), grid, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
-                           sq, p, kmat, L.plan_cap, scores_out, st);
-      else if (nt == 2)
-        hipLaunchKernelGGL((k_scores_mfma<2>), grid8, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
-                           sq, p, kmat, L.plan_cap, scores_out, st);
-      else
-        hipLaunchKernelGGL((k_scores_mfma<4>), grid8, block, 0, s, tok, in->offsets, in->B, in->D, sel, keep, plan_off,
-                           sq, p, kmat, L.plan_cap, scores_out, st);
+      // matrix-core path (an image's workgroups on one XCD: B rounded up to eight)
+      const dim3 gs((in->max_tokens + kScoreRows - 1) / kScoreRows, (in->B + 7) / 8 * 8);
+      hipLaunchKernelGGL(k_scores_mfma, gs, dim3(kScoreThreads), 0, s, tok, in->offsets, in->B, in->D, sel, keep,
+                         plan_off, sq, p, kmat, L.plan_cap, scores_out, st);
       RTP_TRY(launched());
       // images with many pruned tokens: the LDS-tiled kernel.  Largest pruned set
       // the call can produce: the caller's bound, else what the retention clamp allows

@@ -11,12 +11,20 @@
 // at most 2e-8 (5e-9 rms), i.e. plan entries move by under 5e-7 relative at
 // eps = 0.05, inside the 1e-6 band in which an index flip counts as a near-tie.
 //
-// One wave owns MT tiles of 16 kept rows and walks the pruned rows in groups of
-// NT tiles of 16.  Operand fragments are read straight from global memory, 64
-// elements of the contraction per step: lane l reads elements 16 (l / 16) .. + 15
-// of row (l % 16), so four lanes cover one 128-byte line.  Which 32 of the 64
-// elements a matrix instruction contracts is immaterial as long as both
-// operands use the same assignment, which they do by construction.
+// The matrix instruction wants lane l to hold eight elements of row (l % 16),
+// and 16 neighbouring lanes that read 16 different rows cost the texture-address
+// unit one cache line per cycle (measured on L2-resident rows: 65 cycles per
+// 16-byte-per-lane load against 18 when eight neighbouring lanes read one
+// 128-byte line).  So rows are read in the second order and reach the operand
+// order through LDS (rows 144 bytes apart: writes and reads are free of bank
+// conflicts), and the four waves of a workgroup share the pruned rows: a
+// workgroup takes 128 kept rows (32 per wave) against all, at most 64, pruned
+// rows, 64 elements of the contraction per step, the next step's rows in flight
+// while the current one is multiplied.  Column tiles of 16 pruned rows that an
+// image does not have are skipped.  (A kernel that read its operands straight
+// into the operand order, one wave per workgroup, came before this one: equal on
+// 1024 pages with 7 pruned tokens each, where the pass is bound by HBM reads at
+// 4.4 TB/s; 12 % slower on ragged pages with a few dozen, 20 % slower at 63.)
 #pragma once
 #include "common.hpp"
 #include "sinkhorn_team.hpp"
@@ -25,162 +33,146 @@ namespace rtp {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-#ifndef RTP_MFMA_ROWS_PER_WAVE
-#define RTP_MFMA_ROWS_PER_WAVE 32
-#endif
-#ifndef RTP_MFMA_WAVES
-#define RTP_MFMA_WAVES 1
-#endif
-constexpr int kMfmaRowsPerWave = RTP_MFMA_ROWS_PER_WAVE;   // MT tiles of 16 kept rows
-constexpr int kMfmaWaves = RTP_MFMA_WAVES;
 constexpr int kMfmaMinWidth = 1024;   // token widths below this take the fp64 vector score kernel
 
-// Column tiles of 16 pruned rows a wave keeps accumulators for at once (NT of
-// the kernel below), chosen on the host from the largest pruned set the call
-// can produce: a larger NT reads the kept rows fewer times when R is large but
-// costs registers, hence occupancy, when R is small.  Any NT is correct for any
-// image: the kernel walks the pruned rows in groups of 16 NT.
-inline int score_tiles_per_pass(int max_pruned) {
-  const int need = (max_pruned + 15) >> 4;
-  return need <= 1 ? 1 : (need == 2 ? 2 : 4);
-}
+constexpr int kScoreThreads = 256;
+constexpr int kScoreRows = 128;                      // kept rows per workgroup
+constexpr int kScorePitch = 72;                      // bf16 per LDS row: 64 elements and 16 bytes
+constexpr int kScoreBufElems = (64 + kScoreRows) * kScorePitch;
 
-template <int NT>
-__global__ __launch_bounds__(64 * kMfmaWaves) void k_scores_mfma(
+__global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
     const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int B, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
     const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
     double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
     const int32_t* __restrict__ status) {
-  constexpr int MT = kMfmaRowsPerWave / 16;
   if (status[0]) return;
+  __shared__ __align__(16) bf16_t stage[kScoreBufElems];
   // Images are taken last to first: the norm pass before this one walks them first
   // to last and the merge after it does so again, so each pass starts on the
   // images its predecessor touched last, which are the ones the memory-side cache
   // still holds (measured on 1 GB batches: 2 % off this kernel, 1 % off the merge).
-  //
-  // With more than one column tile per pass (NT > 1: the call may have pruned sets
-  // of 17 tokens and more) every wave of an image re-reads a sizeable pruned set,
-  // so the image's workgroups are given linear ids of one residue modulo eight:
-  // workgroups are dealt to the eight XCDs in turn, and the set is then fetched
-  // into one L2 instead of eight (1024 pages with 63 pruned tokens each: 2.4 GB
-  // fetched from memory without this, against 1.05 GB of tokens).  The grid's y
-  // extent is B rounded up to a multiple of eight for it.
-  int by = blockIdx.y, bx = blockIdx.x;
-  if (NT > 1) {
-    const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y, slot = linear >> 3;
-    by = static_cast<int>(slot / gridDim.x) * 8 + static_cast<int>(linear & 7);
-    bx = static_cast<int>(slot % gridDim.x);
-    if (by >= B) return;
-  }
+  // An image's workgroups get linear ids of one residue modulo eight: workgroups
+  // are dealt to the eight XCDs in turn, so the image's pruned rows, which all its
+  // workgroups read, are fetched into one L2 instead of eight (1024 pages with 63
+  // pruned tokens each: 2.4 GB fetched from memory without this, against 1.05 GB of
+  // tokens).  The grid's y extent is B rounded up to a multiple of eight for it.
+  const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y, slot = linear >> 3;
+  const int by = static_cast<int>(slot / gridDim.x) * 8 + static_cast<int>(linear & 7);
+  const int bx = static_cast<int>(slot % gridDim.x);
+  if (by >= B) return;
   const int b = B - 1 - by;
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
   const int m = min(max(keep[b], 0), n), r = n - m;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i0 = (bx * kMfmaWaves + wave) * kMfmaRowsPerWave;
-  if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // larger pruned sets: k_scores_tiled
+  const int i0 = bx * kScoreRows;
+  if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // (the same for the whole workgroup)
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
   const bool k_f32 = kernel_is_f32(p, m, r);
   const int32_t* sel = sel_idx + lo;
-  const int frow = lane & 15, fk = (lane >> 4) * 16;   // 16 elements = 32 bytes per lane and step
   const double inv_eps = 1.0 / p.eps;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int iw = i0 + 32 * wave;                       // the wave's first kept row
+  const bool active = iw < m;                          // else the wave only helps with the pruned rows
+  const int ntiles = (r + 15) >> 4;                    // column tiles of 16 pruned rows that exist
+  constexpr int kPitch = kScorePitch;
 
-  const bf16_t* arow[MT];
+  // reading: eight lanes per row.  Pruned rows t / 8 and t / 8 + 32 by the whole
+  // workgroup; kept rows l / 8 + 8 q (q = 0 .. 3) of the wave's 32 by each wave.
+  const char* base = reinterpret_cast<const char*>(tokens + static_cast<size_t>(lo) * D);
+  const int chunk = tid & 7;
+  uint32_t poff[2], koff[4];                           // byte offsets within the image (at most 8192 rows of 8 KB)
 #pragma unroll
-  for (int t = 0; t < MT; ++t) {
-    const int i = min(i0 + 16 * t + frow, m - 1);
-    arow[t] = tokens + static_cast<size_t>(lo + clamp_index(sel[i], n)) * D + fk;
-  }
+  for (int q = 0; q < 2; ++q)
+    poff[q] = static_cast<uint32_t>(clamp_index(sel[m + min((tid >> 3) + 32 * q, r - 1)], n) * D + 8 * chunk) * 2u;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    koff[q] = static_cast<uint32_t>(clamp_index(sel[min(iw + (lane >> 3) + 8 * q, m - 1)], n) * D + 8 * chunk) * 2u;
+  // LDS rows 0 .. 63: pruned; 64 + 32 wave ..: the wave's kept rows
+  const int wr_p = (tid >> 3) * kPitch + 8 * chunk;                        // + 32 q rows
+  const int wr_k = (64 + 32 * wave + (lane >> 3)) * kPitch + 8 * chunk;    // + 8 q rows
+  // (instruction h of a step contracts elements 16 g + 8 h .. + 7, g = 0 .. 3; which 32
+  // of the 64 is immaterial as long as both operands use the same assignment)
+  const int rd = (lane & 15) * kPitch + 16 * (lane >> 4);                  // + tile's first row, + 8 h elements
 
-  for (int j0 = 0; j0 < r; j0 += 16 * NT) {
-    const bf16_t* brow[NT];
+  double acc[2][4][4];
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      const int j = min(j0 + 16 * u + frow, r - 1);
-      brow[u] = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j], n)) * D + fk;
-    }
-    double acc[MT][NT][4];
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int u = 0; u < NT; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
+      for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
 
-    // 64 elements per step: a lane reads 32 contiguous bytes of its row (four
-    // lanes cover one 128-byte line) and feeds them to two matrix instructions.
-    // The next step's fragments are requested before the current step's
-    // arithmetic.
-    uint4 fa[MT][2], fb[NT][2];
-    auto load_step = [&](int k0, uint4 (&a)[MT][2], uint4 (&bb)[NT][2]) {
+  u32x4_t gp[2], gk[4];
+  auto load_step = [&](int k0, u32x4_t (&gp)[2], u32x4_t (&gk)[4]) {
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        a[t][0] = *reinterpret_cast<const uint4*>(arow[t] + k0);
-        a[t][1] = *reinterpret_cast<const uint4*>(arow[t] + k0 + 8);
-      }
+    for (int q = 0; q < 2; ++q) gp[q] = *reinterpret_cast<const u32x4_t*>(base + poff[q] + 2 * k0);
 #pragma unroll
-      for (int u = 0; u < NT; ++u) {
-        bb[u][0] = *reinterpret_cast<const uint4*>(brow[u] + k0);
-        bb[u][1] = *reinterpret_cast<const uint4*>(brow[u] + k0 + 8);
-      }
-    };
-    auto compute_step = [&](const uint4 (&a)[MT][2], const uint4 (&bb)[NT][2]) {
+    for (int q = 0; q < 4; ++q) gk[q] = *reinterpret_cast<const u32x4_t*>(base + koff[q] + 2 * k0);
+  };
+  auto stage_step = [&](bf16_t* buf, const u32x4_t (&gp)[2], const u32x4_t (&gk)[4]) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+    for (int q = 0; q < 2; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_p + 32 * q * kPitch) = gp[q];
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_k + 8 * q * kPitch) = gk[q];
+  };
+  const int last = D - 64;
+  load_step(0, gp, gk);
+  stage_step(stage, gp, gk);
+  for (int k0 = 0; k0 < D; k0 += 64) {
+    load_step(min(k0 + 64, last), gp, gk);             // unconditional: the step index is clamped instead
+    __syncthreads();                                   // this step's rows are in LDS
+    const bf16_t* cur = stage + rd;
+    if (active) {
 #pragma unroll
-          for (int u = 0; u < NT; ++u) {
-            const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
-            const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8_t, a[t][h]), __builtin_bit_cast(bf16x8_t, bb[u][h]), zero, 0, 0, 0);
+      for (int h = 0; h < 2; ++h) {
+        bf16x8_t a[2], bb[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
-          }
-    };
-    // two fragment buffers used alternately, so that the loads of one are in
-    // flight while the other is consumed (no register copies between steps)
-    uint4 ga[MT][2], gb[NT][2];
-    // Loads are unconditional (the step index is clamped instead) so that the
-    // number of loads in flight is fixed and the waits can be counted ones.
-    // D is a multiple of 128 here, so steps come in pairs and nothing in the
-    // loop body is conditional.
-    const int last = D - 64;
-    load_step(0, fa, fb);
-    for (int k0 = 0; k0 < D; k0 += 128) {
-      load_step(k0 + 64, ga, gb);
-      __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic
-      compute_step(fa, fb);
-      __builtin_amdgcn_sched_barrier(0);
-      load_step(min(k0 + 128, last), fa, fb);
-      __builtin_amdgcn_sched_barrier(0);
-      compute_step(ga, gb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile
+        for (int t = 0; t < 2; ++t)
+          a[t] = *reinterpret_cast<const bf16x8_t*>(cur + (64 + 32 * wave + 16 * t) * kPitch + 8 * h);
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      const int j = j0 + 16 * u + (lane & 15);
-      if (j >= r) continue;
-      const double nj = norm64[lo + clamp_index(sel[m + j], n)];
+        for (int u = 0; u < 4; ++u) bb[u] = *reinterpret_cast<const bf16x8_t*>(cur + 16 * u * kPitch + 8 * h);
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
+        for (int u = 0; u < 4; ++u) {
+          if (u < ntiles) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int i = i0 + 16 * t + 4 * (lane >> 4) + v;
-          if (i < m) {
-            const double ni = norm64[lo + clamp_index(sel[i], n)];
-            const double s = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
-            const long long at = static_cast<long long>(i) * r + j;
-            store_kernel(kmat, po, i, j, r, exp((s - p.shift) * inv_eps), k_f32);
-            if (scores_out) scores_out[po + at] = s;
+            for (int t = 0; t < 2; ++t) {
+              const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
+              const floatx4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t], bb[u], zero, 0, 0, 0);
+#pragma unroll
+              for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(c[v]);
+            }
           }
         }
+      }
     }
+    __syncthreads();                                   // and have been read by every wave
+    stage_step(stage, gp, gk);
+  }
+  if (!active) return;
+
+  // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int j = 16 * u + (lane & 15);
+    if (j >= r) continue;
+    const double nj = norm64[lo + clamp_index(sel[m + j], n)];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = iw + 16 * t + 4 * (lane >> 4) + v;
+        if (i < m) {
+          const double ni = norm64[lo + clamp_index(sel[i], n)];
+          const double sc = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
+          const long long at = static_cast<long long>(i) * r + j;
+          store_kernel(kmat, po, i, j, r, exp((sc - p.shift) * inv_eps), k_f32);
+          if (scores_out) scores_out[po + at] = sc;
+        }
+      }
   }
 }
 
