@@ -105,10 +105,17 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
             return "alu", flops, "TFLOP/s", FP32_VECTOR_TFLOPS
         return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
     if kernel == "k_scores":
+        flops = 2.0 * float((m * r).sum()) * d          # one multiply-add per (kept, pruned, d)
         if elt == 2 and d % 128 == 0:
-            # bf16 matrix cores: one multiply-add per (kept, pruned, d)
-            return "mfma", 2.0 * float((m * r).sum()) * d, "TFLOP/s", BF16_MFMA_TFLOPS
-        return "alu", 2.0 * float((m * r).sum()) * d, "TFLOP/s", FP64_VECTOR_TFLOPS
+            # bf16 matrix cores.  Every token row read once, the kernel matrix written once
+            # (8 bytes per entry): below the ridge of the matrix cores (312 flop/B) the pass
+            # is a stream over the tokens.  Pruned sets of more than 64 take the LDS-tiled
+            # kernel, priced as a contraction.
+            nbytes = tok_bytes + 8.0 * float((m * r).sum())
+            if r.max(initial=0) <= 64 and flops / nbytes < BF16_MFMA_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+                return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
+            return "mfma", flops, "TFLOP/s", BF16_MFMA_TFLOPS
+        return "alu", flops, "TFLOP/s", FP64_VECTOR_TFLOPS
     if kernel == "k_sinkhorn" and big.any():
         # sweep kernels: the kernel matrix read once per iteration (it does not fit on chip)
         return "hbm", kbytes * iters * float((m * r)[big].sum()), "GB/s", HBM_PEAK_GBS
