@@ -119,7 +119,7 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     if kernel == "k_sinkhorn" and big.any():
         # sweep kernels: the kernel matrix read once per iteration (it does not fit on chip)
         return "hbm", kbytes * iters * float((m * r)[big].sum()), "GB/s", HBM_PEAK_GBS
-    if kernel in ("k_sinkhorn", "k_sinkhorn_regs", "k_sinkhorn_tall"):
+    if kernel in ("k_sinkhorn", "k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn_tall"):
         # register-resident or single-workgroup kernels: two sweeps of multiply-adds over
         # the augmented matrix per iteration (counted over the whole batch)
         return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
@@ -213,7 +213,7 @@ def bench_large_pages(rt, torch, synth, steps: int, cfg: int = 8, batch=None):
     n_h = np.diff(batch.offsets).astype(np.int64)
     keep_h = keep.cpu().numpy().astype(np.int64)
     roof = {}
-    for k_ in ("k_sinkhorn_regs", "k_sinkhorn", "k_scores", "k_merge"):
+    for k_ in ("k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn", "k_scores", "k_merge"):
         if kernels.get(k_, 0.0) < 0.02 * ms:      # a kernel that has nothing to do on this workload
             continue
         bound, amount, unit, peak = kernel_work(k_, n_h, keep_h, D, 2, int(batch.params["iters"]),

@@ -169,9 +169,9 @@ int compute_units() {
 // When enabled, each kernel launch is bracketed by two HIP events recorded on
 // the launch stream; rtprune_profile_summary() turns them into per-kernel totals.
 
-enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN_TALL, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_SPLICE, KID_COUNT };
+enum KernelId { KID_PREPARE, KID_NORMS, KID_SELECT, KID_SCAN, KID_SCORES, KID_CLASSIFY, KID_SINKHORN_REGS, KID_SINKHORN_C32, KID_SINKHORN_TALL, KID_SINKHORN, KID_MERGE, KID_DENSITY_PREPARE, KID_DENSITY_SOBEL, KID_DENSITY_FINISH, KID_SPLICE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select", "k_scan",
-                                             "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn_tall", "k_sinkhorn",
+                                             "k_scores", "k_classify", "k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn_tall", "k_sinkhorn",
                                              "k_merge", "k_density_prepare", "k_density_sobel",
                                              "k_density_finish", "k_splice"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
@@ -379,6 +379,11 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
     hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, compute_units(), st);
+  }
+  if (p.mode & kModeF32) {
+    ProfScope prof(KID_SINKHORN_C32, s);
+    hipLaunchKernelGGL(k_sinkhorn_c32, dim3(std::min(in->B, 2 * compute_units())), dim3(kDualThreads), 0, s, A, work,
+                       in->B, st);
   }
   if (p.mode & kModeLarge) {
     ProfScope prof(KID_SINKHORN_TALL, s);

@@ -493,4 +493,18 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_tall(SinkhornArgs A,
   if (blk < cnt) sinkhorn_waves_image<TallShape>(A, work[NV + kVariantTall * B + blk], 0, wave, lane);
 }
 
+// Team C's images held as fp32, one at a time per workgroup, two workgroups per
+// compute unit (at most 128 registers per lane); the grid is at most two
+// workgroups per compute unit, which take the list in turns.  Launched when the
+// kernel matrix's range fits fp32.
+__global__ __launch_bounds__(kDualThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_sinkhorn_c32(
+    SinkhornArgs A, const int32_t* __restrict__ work, int B, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int cnt = work[kVariantC32];
+  for (int blk = blockIdx.x; blk < cnt; blk += gridDim.x) {
+    if (blk != static_cast<int>(blockIdx.x)) __syncthreads();   // the previous image's LDS is still being read
+    sinkhorn_team_image<TeamC32, float>(A, work[kWorkLists + kVariantC32 * B + blk], threadIdx.x >> 6, threadIdx.x & 63);
+  }
+}
+
 }  // namespace rtp

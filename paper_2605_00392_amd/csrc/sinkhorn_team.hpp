@@ -45,6 +45,10 @@ struct TeamShape {
 // to the general kernel (variant kGeneralVariant).
 using TeamB = TeamShape<8, 2, 4, 10>;    // M <= 512,  R <= 40
 using TeamC = TeamShape<8, 3, 8, 8>;     // M <= 512,  R <= 64
+// Team C's columns with six rows per lane and the kernel matrix held as fp32
+// (when its range allows): half the registers, so that two workgroups share a
+// compute unit and one's waits are filled by the other (k_sinkhorn_c32).
+using TeamC32 = TeamShape<8, 3, 6, 8>;   // M <= 384,  R <= 64
 // Tall images (tiled pages with a few pruned tokens): the kernel matrix is held
 // as fp32 values, which the same range condition as for the sweep kernels allows,
 // and widened at each use; all sums and both scaling vectors stay fp64.
@@ -81,10 +85,10 @@ constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
               kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kVariantWideA = 9,
-              kVariantWideB = 10, kVariantWideC = 11, kGeneralVariant = 12;
+              kVariantWideB = 10, kVariantWideC = 11, kVariantC32 = 12, kGeneralVariant = 13;
 // The work lists k_classify builds: one per register-resident shape above, and
 // one of the images whose scores and merge go to the tiled matrix-core kernels.
-constexpr int kListTiled = 12, kListMid = 13, kWorkLists = 14;
+constexpr int kListTiled = 13, kListMid = 14, kWorkLists = 15;
 // What a call launches besides the 512-row register shapes, as the kernels
 // receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
 // tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the
@@ -108,6 +112,7 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   if ((mode & kModeLarge) && r <= kSweepMaxPruned) return kVariantSweep;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
+  if ((mode & kModeF32) && TeamC32::fits(m, r)) return kVariantC32;
   if (TeamC::fits(m, r)) return kVariantC;
   if (mode & kModeF32) {
     if (TeamWideA::fits(m, r)) return kVariantWideA;

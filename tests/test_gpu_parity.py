@@ -233,6 +233,20 @@ def test_wide_register_shapes_at_their_edges(override):
     assert rep.max_score_abs <= hz.SCORE_ATOL
 
 
+@pytest.mark.parametrize("override", [dict(), dict(eps=0.02), dict(iters=0), dict(iters=1), dict(eps=1.0, iters=100)])
+def test_64_column_register_shapes_at_their_edges(override):
+    """41 to 64 pruned tokens: the 384 x 64 shape that holds the matrix as fp32 (two workgroups
+    per compute unit) on both sides of its limits, and the 512 x 64 fp64 shape beyond them; with
+    eps = 0.02 exp's range does not fit fp32 and the fp64 shape takes them all."""
+    shapes = [(384, 64), (385, 64), (384, 41), (383, 63), (337, 63), (447, 64), (50, 49), (1, 64), (448, 41)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 33, **dict(dict(iters=40), **override))
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, f"64-column shapes {override}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
 def test_heavily_pruned_400_token_pages_fused():
     """Dynamic retention at its clamp on 400-token pages whose tokens resemble each other:
     160 pruned tokens per page, through the fused call."""
