@@ -199,12 +199,15 @@ def bench_large_pages(rt, torch, synth, steps: int, cfg: int = 8, batch=None):
 
     step()
     torch.cuda.synchronize()
-    rt.rtprune_profile_enable(1)
     t1 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
+    rt.rtprune_profile_enable(1)             # per-kernel durations from steps of their own
+    for _ in range(max(2, min(5, steps))):
+        step()
+    torch.cuda.synchronize()
     rc, prof = rt.rtprune_profile_summary()
     rt.rtprune_profile_enable(0)
     rt.check(rc)
@@ -284,6 +287,21 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # Every kernel's duration, from a few steps before the timed region (an event pair
+    # per launch costs a few microseconds of stream time each, ten and more per step);
+    # the timed region then records the slowest kernel alone.
+    rt.rtprune_profile_only(None)
+    rt.rtprune_profile_enable(1)
+    pre_steps = max(2, min(5, args.steps))
+    for _ in range(pre_steps):
+        step()
+    torch.cuda.synchronize()
+    rc, pre = rt.rtprune_profile_summary()
+    rt.rtprune_profile_enable(0)
+    rt.check(rc)
+    kernels_pre = {r_["kernel"]: r_["total_ms"] / max(1, r_["launches"]) for r_ in pre}
+    dominant_pre = max(kernels_pre, key=kernels_pre.get) if kernels_pre else None
+    rt.check(rt.rtprune_profile_only(dominant_pre))
     rt.rtprune_profile_enable(1)
     # one event pair per step on the launch stream (torch's current stream): median and
     # minimum of the steps beside the wall-clock mean
@@ -298,6 +316,7 @@ def main() -> int:
     t2 = time.perf_counter()
     rc, prof = rt.rtprune_profile_summary()
     rt.rtprune_profile_enable(0)
+    rt.rtprune_profile_only(None)
     rt.check(rc)
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     status = int(ws[:4].view(torch.int32).item())
@@ -317,10 +336,10 @@ def main() -> int:
     n_h = np.diff(batch.offsets).astype(np.int64)
     elt = 2 if batch.dtype == "bf16" else 4
 
-    kernels = {}
-    for rec in prof:
+    kernels = dict(kernels_pre)
+    for rec in prof:                         # the slowest kernel: as measured inside the timed region
         kernels[rec["kernel"]] = rec["total_ms"] / max(1, rec["launches"])
-    dominant = max(kernels, key=kernels.get) if kernels else None
+    dominant = dominant_pre
     roofline = None
     if dominant:
         bound, amount, unit, peak = kernel_work(dominant, n_h, keep_h, D, elt, int(batch.params["iters"]),
@@ -399,6 +418,7 @@ def main() -> int:
                    "iters": int(batch.params["iters"]), "eps": batch.params["eps"],
                    "dynamic": int(batch.params["dynamic"]), "gen_s": round(gen_s, 1)},
         "kernels_ms": {k_: round(v, 5) for k_, v in kernels.items()},
+        "kernels_ms_from": f"{pre_steps} profiled steps before the timed region; {dominant} from the timed region",
         "step_hbm_floor_frac": round(step_hbm_frac, 5),
         "roofline": roofline,
         "cpu_baseline": cpu,

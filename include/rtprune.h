@@ -285,6 +285,11 @@ int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_offsets,
  * into the host buffer `buf` of `cap` bytes (RTP_EINVAL if it does not fit). */
 int rtprune_profile_enable(int on);
 int rtprune_profile_summary(char* buf, size_t cap);
+/* Restricts the recording to the launches reported under one name (as in the
+ * summary, e.g. "k_merge"); NULL or "" records all again.  An event pair takes a
+ * few microseconds of stream time, so a timed region that wants one kernel's
+ * duration records that kernel alone.  RTP_EINVAL for an unknown name. */
+int rtprune_profile_only(const char* kernel);
 
 /* Tuning and test aid (process-global, not thread-safe).  Images with 17 to 64
  * pruned tokens have a merge kernel of their own (the kept rows streamed past

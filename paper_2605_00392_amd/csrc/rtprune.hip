@@ -178,6 +178,7 @@ struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
   std::mutex mu;
   bool on = false;
+  int only = -1;               // >= 0: record this kernel id alone (rtprune_profile_only)
   std::vector<ProfRec> recs;
 } g_prof;
 
@@ -187,7 +188,7 @@ struct ProfScope {
   hipEvent_t start = nullptr, stop = nullptr;
   bool live = false;
   ProfScope(int kid_, hipStream_t s_) : kid(kid_), s(s_) {
-    if (!g_prof.on) return;
+    if (!g_prof.on || (g_prof.only >= 0 && g_prof.only != kid)) return;
     if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) return;
     live = hipEventRecord(start, s) == hipSuccess;
   }
@@ -380,7 +381,9 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     ProfScope prof(KID_SINKHORN_REGS, s);
     hipLaunchKernelGGL(k_sinkhorn_regs, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, compute_units(), st);
   }
-  if (p.mode & kModeF32) {
+  // (its images have 48 to 64 pruned tokens: smaller sets go to the shapes above, and in
+  // batches with large images the sweep kernels take them)
+  if ((p.mode & kModeF32) && !(p.mode & kModeLarge) && pruned_bound(in, p, max_pruned_hint) >= 48) {
     ProfScope prof(KID_SINKHORN_C32, s);
     hipLaunchKernelGGL(k_sinkhorn_c32, dim3(std::min(in->B, 2 * compute_units())), dim3(kDualThreads), 0, s, A, work,
                        in->B, st);
@@ -390,10 +393,18 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     hipLaunchKernelGGL(k_sinkhorn_tall, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
   }
   RTP_TRY(launched());
-  ProfScope prof(KID_SINKHORN, s);
-  hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
-                     L.plan_cap, plan, pair, 1, p.mode, st);
-  RTP_TRY(launched());
+  // The general kernel takes what no shape above does.  With the fp32-held shapes
+  // in use and at most 512 tokens per image those cover every image with up to 224
+  // pruned tokens (64 / 128 / 192 / 224 pruned against 512 / 448 / 384 / 320 kept),
+  // so a call that cannot produce a larger pruned set has nothing left for it.
+  const bool all_in_registers = (p.mode & kModeF32) && !(p.mode & kModeLarge) &&
+                                pruned_bound(in, p, max_pruned_hint) <= TeamWideC::kMaxR;
+  ProfScope prof(KID_SINKHORN, s);   // (with the sweep launches below)
+  if (!all_in_registers) {
+    hipLaunchKernelGGL(k_sinkhorn, dim3(in->B), dim3(1024), 0, s, in->offsets, keep, plan_off, p, kmat,
+                       L.plan_cap, plan, pair, 1, p.mode, st);
+    RTP_TRY(launched());
+  }
   if (p.mode & kModeLarge) {
     // large images: two launches per iteration over all of them, then plan and pairing
     SweepArgs SA{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
@@ -566,6 +577,18 @@ extern "C" int rtprune_profile_enable(int on) {
   }
   g_prof.recs.clear();
   g_prof.on = on != 0;
+  return RTP_OK;
+}
+
+extern "C" int rtprune_profile_only(const char* kernel) {
+  int kid = -1;
+  if (kernel && kernel[0]) {
+    for (int k = 0; k < KID_COUNT; ++k)
+      if (std::strcmp(kernel, kKernelNames[k]) == 0) kid = k;
+    if (kid < 0) return RTP_EINVAL;
+  }
+  std::lock_guard<std::mutex> g(g_prof.mu);
+  g_prof.only = kid;
   return RTP_OK;
 }
 

@@ -25,7 +25,7 @@ RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE = 1, 2, 4
 EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune", "rtprune_prune_splice",
-    "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_copy_bytes",
+    "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_profile_only", "rtprune_copy_bytes",
     "rtprune_text_density_workspace_bytes", "rtprune_text_density", "rtprune_mid_merge_min_images",
 )
 
@@ -96,6 +96,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_mid_merge_min_images.argtypes = [ctypes.c_int]
     lib.rtprune_profile_enable.restype = ctypes.c_int
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
+    lib.rtprune_profile_only.restype = ctypes.c_int
+    lib.rtprune_profile_only.argtypes = [ctypes.c_char_p]
     lib.rtprune_profile_summary.restype = ctypes.c_int
     lib.rtprune_profile_summary.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     lib.rtprune_text_density_workspace_bytes.restype = ctypes.c_int
@@ -260,6 +262,10 @@ def rtprune_mid_merge_min_images(min_images: int) -> int:
 
 def rtprune_profile_enable(on: int) -> int:
     return load_library().rtprune_profile_enable(int(on))
+
+
+def rtprune_profile_only(kernel: Optional[str]) -> int:
+    return load_library().rtprune_profile_only(kernel.encode() if kernel else None)
 
 
 def rtprune_profile_summary():
