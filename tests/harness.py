@@ -15,7 +15,7 @@ from oracle import rtprune_oracle as orc
 from paper_2605_00392_amd import rtprune as rt
 from paper_2605_00392_amd import synth
 
-# Parity bars (also stated in the design doc)
+# Parity bars
 NEAR_TIE = 1e-6            # relative gap below which an index disagreement is a counted near-tie
 MERGE_RTOL, MERGE_ATOL = 2e-3, 1e-3     # bf16 merged features, elementwise
 MERGE_ROW_REL = 3e-3       # per-token ||g - o|| / ||o||; bf16 rounding alone gives about 2^-8 / sqrt(3) = 2.3e-3
