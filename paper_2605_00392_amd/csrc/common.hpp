@@ -23,7 +23,7 @@ typedef unsigned short bf16_t;     // raw bfloat16 bit pattern
 // better.)
 constexpr int kTiledMinPruned = 64;
 // Between kMergeMidMin and kTiledMinPruned pruned tokens the merge runs on the
-// matrix cores with only the pruned rows staged (k_merge_mfma; bf16 tokens, width a multiple of 64).
+// matrix cores with only the pruned rows staged (merge_mfma.hpp; bf16 tokens, width a multiple of 64).
 constexpr int kMergeMidMin = 16;
 __host__ __device__ inline bool merge_is_mid(int r) { return r > kMergeMidMin && r <= kTiledMinPruned; }
 // Which images the vector merge kernels leave to the others.  The middling ones

@@ -30,6 +30,7 @@
 #include "common.hpp"
 #include "scores_mfma.hpp"
 #include "sinkhorn_team.hpp"
+#include "merge_tiled.hpp"
 
 namespace rtp {
 
@@ -226,23 +227,42 @@ __device__ __forceinline__ void merge_mid_tile(const MergeMidArgs& A, int b, int
   }
 }
 
-// A fixed number of workgroups (a multiple of eight) over the row tiles of the
-// images on the list.  Workgroups are dealt to the eight XCDs in turn, so item q
+// The list forms of both matrix-core merge kernels in one launch (the sizes of the
+// pruned sets were decided on the device): a fixed number of workgroups, a multiple
+// of eight, first walk the tiles of the images on the tiled list (more than 64
+// pruned tokens; merge_tiled.hpp), then the row tiles of the images on this file's
+// list.  For the latter, workgroups being dealt to the eight XCDs in turn, item q
 // runs on XCD q % 8: the tiles of one image are given items of one residue, and
-// its pruned rows are fetched into one L2 only.
+// its pruned rows are fetched into one L2 only.  `tiles_t` / `tiles_m` = 0: that
+// role is not wanted.  Both roles use the same LDS buffer.
 template <int SPI>
-__global__ __launch_bounds__(kMergeMidThreads) void k_merge_mfma(
-    MergeMidArgs A, int tiles, const int32_t* __restrict__ work, int B, int mid_min,
+__global__ __launch_bounds__(kMergeMidThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_merge_lists(
+    MergeTiledArgs TA, int tiles_t, MergeMidArgs A, int tiles_m, const int32_t* __restrict__ work, int B, int mid_min,
     const int32_t* __restrict__ status) {
-  if (status[0] || !merge_mid_runs(work + kListMid, mid_min)) return;
-  __shared__ __align__(16) bf16_t bbuf[2 * SPI * kMergeMidBufElems];
-  const int count = work[kListMid];
-  const long long items = static_cast<long long>((count + 7) / 8) * 8 * tiles;
-  for (long long q = blockIdx.x; q < items; q += gridDim.x) {
-    const long long s = q >> 3;
-    const int k = static_cast<int>(s / tiles) * 8 + static_cast<int>(q & 7);
-    if (k >= count) continue;
-    merge_mid_tile<SPI>(A, work[kWorkLists + kListMid * B + k], kMergeMidBlockRows * static_cast<int>(s % tiles), bbuf);
+  if (status[0]) return;
+  static_assert(kMergeTiledThreads == kMergeMidThreads, "one workgroup shape for both roles");
+  constexpr int kLdsBytes = kMergeTiledLdsBytes > 2 * SPI * kMergeMidBufElems * 2 ? kMergeTiledLdsBytes
+                                                                                  : 2 * SPI * kMergeMidBufElems * 2;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kLdsBytes];
+  if (tiles_t > 0) {
+    const int count = work[kListTiled];
+    const long long items = static_cast<long long>(count) * tiles_t;
+    for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+      __syncthreads();   // the previous tile's last LDS reads
+      const int k = static_cast<int>(item / tiles_t);
+      merge_tile(TA, work[kWorkLists + kListTiled * B + k], static_cast<int>(item - static_cast<long long>(k) * tiles_t), lds);
+    }
+  }
+  if (tiles_m > 0 && merge_mid_runs(work + kListMid, mid_min)) {
+    const int count = work[kListMid];
+    const long long items = static_cast<long long>((count + 7) / 8) * 8 * tiles_m;
+    for (long long q = blockIdx.x; q < items; q += gridDim.x) {
+      const long long s = q >> 3;
+      const int k = static_cast<int>(s / tiles_m) * 8 + static_cast<int>(q & 7);
+      if (k >= count) continue;
+      merge_mid_tile<SPI>(A, work[kWorkLists + kListMid * B + k], kMergeMidBlockRows * static_cast<int>(s % tiles_m),
+                          reinterpret_cast<bf16_t*>(lds));
+    }
   }
 }
 

@@ -27,6 +27,7 @@ constexpr int kMergeTileCols = 128;    // features per workgroup tile
 constexpr int kMergeTileStep = 32;     // pruned rows per step
 constexpr int kMergeTilePitch = 80;    // LDS bytes per staged row (32 bf16 + padding)
 constexpr int kMergeTiledThreads = 256;
+constexpr int kMergeTiledLdsBytes = 2 * 3 * 128 * 80;   // merge_tile's LDS buffer (its staging tiles; the output tile fits too)
 constexpr int kMergeOutPitch = kMergeTileCols + 4;   // floats per row of the output staging tile
 
 // What both launch forms of the kernel pass on.
@@ -45,7 +46,7 @@ struct MergeTiledArgs {
 };
 
 // Tile `tile` (kept-row tile major, feature tile minor) of image b.
-__device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int tile) {
+__device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int tile, unsigned char* lds) {
   const bf16_t* __restrict__ tokens = A.tokens;
   const int32_t* __restrict__ offsets = A.offsets;
   const int D = A.D;
@@ -73,7 +74,7 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
   constexpr int kOperand = kMergeTileRows * kMergeTilePitch;          // one staged operand
   constexpr int kStageBytes = 2 * 3 * kOperand;                       // [buffer][P hi, P lo, T^T]
   constexpr int kOutBytes = 64 * kMergeOutPitch * 4;                  // half of the output tile, fp32
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageBytes > kOutBytes ? kStageBytes : kOutBytes];
+  static_assert(kMergeTiledLdsBytes >= kStageBytes && kMergeTiledLdsBytes >= kOutBytes, "the caller's LDS buffer");
 
   // staging of P: thread t takes entries 4 (t % 8) .. + 3 of the step for rows t / 8 + 32 q
   const int pj = 4 * (tid & 7), prow = tid >> 3;
@@ -208,22 +209,8 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
 __global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled(MergeTiledArgs A,
                                                                    const int32_t* __restrict__ status) {
   if (status && status[0]) return;
-  merge_tile(A, blockIdx.y, blockIdx.x);
-}
-
-// A fixed number of workgroups that walk the tiles of the images on the tiled
-// work list (see k_scores_tiled_list).
-__global__ __launch_bounds__(kMergeTiledThreads) void k_merge_tiled_list(MergeTiledArgs A, int tiles,
-                                                                        const int32_t* __restrict__ work, int B,
-                                                                        const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  const int count = work[kListTiled];
-  const long long items = static_cast<long long>(count) * tiles;
-  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
-    __syncthreads();   // the previous tile's last LDS reads
-    const int k = static_cast<int>(item / tiles);
-    merge_tile(A, work[kWorkLists + kListTiled * B + k], static_cast<int>(item - static_cast<long long>(k) * tiles));
-  }
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kMergeTiledLdsBytes];
+  merge_tile(A, blockIdx.y, blockIdx.x, lds);
 }
 
 }  // namespace rtp

@@ -491,29 +491,28 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   }
   RTP_TRY(launched());
   if constexpr (std::is_same<T, bf16_t>::value) {
-    if (mid) {
-      const int tiles_i = tiles_mid;
+    const int tiles_ti = (in->max_tokens + kMergeTileRows - 1) / kMergeTileRows;
+    const int tiles_td = in->D / kMergeTileCols;
+    const MergeTiledArgs TA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens,
+                            tiles_td, static_cast<bf16_t*>(out)};
+    // pruned sets known to be large (fixed retention), or no work list: a workgroup per
+    // tile and image for the tiled kernel; else its list form shares a launch with the
+    // middling sets' kernel
+    const bool tiled_grid = tiled && (max_pruned_hint >= 2 * kTiledMinPruned || !work || !status);
+    if (tiled_grid)
+      hipLaunchKernelGGL(k_merge_tiled, dim3(tiles_ti * tiles_td, in->B), dim3(kMergeTiledThreads), 0, s, TA, status);
+    const bool tiled_list = tiled && !tiled_grid;
+    if (tiled_list || mid) {
       const MergeMidArgs MA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens,
                             static_cast<bf16_t*>(out)};
-      const dim3 gm((tiled_list_blocks(tiles_i, in->B) + 7) / 8 * 8);
+      const int tiles_t = tiled_list ? tiles_ti * tiles_td : 0, tiles_m = mid ? tiles_mid : 0;
+      const dim3 gl((tiled_list_blocks(std::max(tiles_t, tiles_m), in->B) + 7) / 8 * 8);
       if (in->D % (2 * kMergeMidFeatures) == 0)
-        hipLaunchKernelGGL(k_merge_mfma<2>, gm, dim3(kMergeMidThreads), 0, s, MA, tiles_i, work, in->B, mid_min, status);
+        hipLaunchKernelGGL(k_merge_lists<2>, gl, dim3(kMergeMidThreads), 0, s, TA, tiles_t, MA, tiles_m, work, in->B,
+                           mid_min, status);
       else
-        hipLaunchKernelGGL(k_merge_mfma<1>, gm, dim3(kMergeMidThreads), 0, s, MA, tiles_i, work, in->B, mid_min, status);
-      RTP_TRY(launched());
-    }
-    if (tiled) {
-      const int tiles_i = (in->max_tokens + kMergeTileRows - 1) / kMergeTileRows;
-      const int tiles_d = in->D / kMergeTileCols;
-      const MergeTiledArgs TA{tok, in->offsets, in->D, sel, keep, out_off, plan, plan_off, alpha, in->max_tokens,
-                              tiles_d, static_cast<bf16_t*>(out)};
-      // as for the scores: the list form when the sizes were decided on the device
-      // and the call has a work list (the fused calls)
-      if (max_pruned_hint >= 2 * kTiledMinPruned || !work || !status)
-        hipLaunchKernelGGL(k_merge_tiled, dim3(tiles_i * tiles_d, in->B), dim3(kMergeTiledThreads), 0, s, TA, status);
-      else
-        hipLaunchKernelGGL(k_merge_tiled_list, dim3(tiled_list_blocks(tiles_i * tiles_d, in->B)),
-                           dim3(kMergeTiledThreads), 0, s, TA, tiles_i * tiles_d, work, in->B, status);
+        hipLaunchKernelGGL(k_merge_lists<1>, gl, dim3(kMergeMidThreads), 0, s, TA, tiles_t, MA, tiles_m, work, in->B,
+                           mid_min, status);
     }
   }
   return launched();
