@@ -92,6 +92,15 @@ def test_mid_merge_minimum_is_a_process_wide_setting(lib):
     assert rt.rtprune_mid_merge_min_images(-1) == -1
 
 
+def test_profile_filter_names(lib):
+    """The measurement aid takes the names the summary reports, and nothing else."""
+    assert rt.rtprune_profile_only("k_merge") == rt.RTP_OK
+    assert rt.rtprune_profile_only("k_sinkhorn_c32") == rt.RTP_OK
+    assert rt.rtprune_profile_only("no_such_kernel") == rt.RTP_EINVAL
+    assert rt.rtprune_profile_only(None) == rt.RTP_OK
+    assert rt.rtprune_profile_only("") == rt.RTP_OK
+
+
 def _fake_batch(**kw):
     # addresses are never dereferenced: every call below must fail validation first
     v = dict(tokens=0x1000, offsets=0x2000, total_tokens=64, max_tokens=64, B=1, D=1280, dtype=rt.RTP_BF16)

@@ -618,3 +618,35 @@ def test_non_default_stream():
     with torch.cuda.stream(st):
         got = hz.run_prune(batch)
     np.testing.assert_array_equal(ref["out"], got["out"])
+
+
+def test_profile_records_per_kernel_and_can_be_restricted_to_one():
+    """The measurement aids: one record per launch group while enabled, one kernel's alone on
+    request, nothing once disabled; the results of the call do not change."""
+    import torch
+    batch = synth.gen_batch(2, images=range(4))
+    plain = hz.run_prune(batch)
+    rt.rtprune_profile_enable(1)
+    try:
+        f = hz.run_prune(batch)
+        torch.cuda.synchronize()
+        rc, rows = rt.rtprune_profile_summary()
+        assert rc == rt.RTP_OK
+        names = {r["kernel"] for r in rows}
+        assert {"k_prepare", "k_norms", "k_select", "k_scores", "k_sinkhorn_regs", "k_merge"} <= names
+        assert all(r["launches"] >= 1 and r["total_ms"] > 0 for r in rows)
+        rt.rtprune_profile_enable(1)                    # discards the records
+        assert rt.rtprune_profile_only("k_merge") == rt.RTP_OK
+        g = hz.run_prune(batch)
+        torch.cuda.synchronize()
+        rc, rows = rt.rtprune_profile_summary()
+        assert rc == rt.RTP_OK and [r["kernel"] for r in rows] == ["k_merge"] and rows[0]["launches"] == 1
+    finally:
+        rt.rtprune_profile_only(None)
+        rt.rtprune_profile_enable(0)
+    hz.run_prune(batch)
+    rc, rows = rt.rtprune_profile_summary()
+    assert rc == rt.RTP_OK and rows == []
+    for other in (f, g):
+        np.testing.assert_array_equal(other["out"], plain["out"])
+        np.testing.assert_array_equal(other["pair"], plain["pair"])
