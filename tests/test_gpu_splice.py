@@ -88,6 +88,16 @@ def test_splice_matches_oracle_and_packed_output(cfg, images, mode):
     assert rep.images == B
 
 
+def test_splice_through_the_merge_kernel_for_middling_pruned_sets():
+    """63 pruned tokens per page, the matrix-core merge kernel for 17 to 64 switched on for a
+    small batch: it writes into the sequence at each image's visual start like the others."""
+    before = rt.rtprune_mid_merge_min_images(1)
+    try:
+        test_splice_matches_oracle_and_packed_output(9, 3, orc.POSITIONS_ORIGINAL)
+    finally:
+        rt.rtprune_mid_merge_min_images(before)
+
+
 def test_splice_without_text_is_the_packed_output():
     batch = synth.gen_batch(2, images=range(3))
     g = _run(batch, None, None, None, None, orc.POSITIONS_CONSECUTIVE)
