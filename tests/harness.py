@@ -6,6 +6,7 @@ here and nowhere else.
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional
 
@@ -230,3 +231,76 @@ def compare_batch(batch: synth.Batch, gpu: Dict, params: Optional[Dict] = None,
         compare_image(b, batch, gpu, p, rep, staged=staged,
                       keep_count=None if keep_counts is None else int(keep_counts[b]))
     return rep
+
+
+# ---------------------------------------------------------------------------
+# whole large batches: the oracle fanned out over host processes
+# ---------------------------------------------------------------------------
+def host_workers() -> int:
+    """Worker processes for the oracle: the host's cores, at most 16."""
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def _merge_reports(into: Report, rep: Report) -> None:
+    into.images += rep.images
+    into.ratio_boundary += rep.ratio_boundary
+    into.selection_near_ties += rep.selection_near_ties
+    into.pairing_near_ties += rep.pairing_near_ties
+    into.pairs_checked += rep.pairs_checked
+    for k in ("max_ratio_err", "max_merge_row_rel", "max_plan_rel", "max_score_abs"):
+        setattr(into, k, max(getattr(into, k), getattr(rep, k)))
+    into.notes.extend(rep.notes)
+
+
+def _slice_images(batch: synth.Batch, gpu: Dict, b0: int, b1: int):
+    """Images b0..b1-1 of a batch and of a fused result, re-based to start at zero."""
+    lo, hi = int(batch.offsets[b0]), int(batch.offsets[b1])
+    sub = synth.Batch(batch.cfg, batch.dtype, batch.tokens[lo:hi], (batch.offsets[b0:b1 + 1] - lo).astype(np.int32),
+                      batch.density[b0:b1], batch.params, list(range(b0, b1)))
+    o0, o1 = int(gpu["out_offsets"][b0]), int(gpu["out_offsets"][b1])
+    g = dict(out=gpu["out"][o0:o1], out_offsets=(gpu["out_offsets"][b0:b1 + 1] - o0),
+             keep=gpu["keep"][b0:b1], sel=gpu["sel"][lo:hi], pair=gpu["pair"][lo:hi], ratio=gpu["ratio"][b0:b1])
+    return sub, g
+
+
+def _compare_chunk(task):
+    """Runs in a worker process (numpy and the oracle only; nothing here touches a GPU)."""
+    sub, g, params, first = task
+    try:
+        from threadpoolctl import threadpool_limits
+        limit = threadpool_limits(1)
+    except ImportError:                                  # pragma: no cover
+        limit = None
+    try:
+        rep = compare_batch(sub, g, params)
+    except AssertionError as e:
+        raise AssertionError(f"images {first}..{first + sub.batch - 1} (index inside the chunk first): {e}") from None
+    finally:
+        if limit is not None:
+            limit.restore_original_limits()
+    rep.notes = [f"chunk at image {first}: {n}" for n in rep.notes]
+    return rep
+
+
+def compare_batch_parallel(batch: synth.Batch, gpu: Dict, params: Optional[Dict] = None,
+                           chunk: int = 16, workers: Optional[int] = None) -> Report:
+    """compare_batch over every image of a fused result, the oracle spread over host
+    processes.  The workers are started fresh (spawn), so they inherit nothing of this
+    process's GPU state, and they import no GPU code."""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    workers = host_workers() if workers is None else workers
+    tasks = []
+    for b0 in range(0, batch.batch, chunk):
+        b1 = min(batch.batch, b0 + chunk)
+        sub, g = _slice_images(batch, gpu, b0, b1)
+        tasks.append((sub, g, params, b0))
+    total = Report()
+    if workers <= 1 or len(tasks) <= 1:
+        for t in tasks:
+            _merge_reports(total, _compare_chunk(t))
+        return total
+    with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as pool:
+        for rep in pool.map(_compare_chunk, tasks):
+            _merge_reports(total, rep)
+    return total

@@ -1,6 +1,8 @@
 """GPU parity of rtprune_prune_splice: the fused call writing straight into the
-prefill input, against the oracle's splice and against the packed output of
-rtprune_prune (same kernels, so bit for bit)."""
+prefill input.  Placement (sequence offsets, position ids, text rows) against the
+oracle's splice; the merged visual rows inside the sequences against the oracle's
+merge directly; and the whole against the packed output of rtprune_prune (same
+kernels, so bit for bit)."""
 import numpy as np
 import pytest
 
@@ -42,13 +44,16 @@ def _run(batch, prefix, poff, suffix, soff, mode, params=None):
     pos = torch.full((cap,), -7, dtype=torch.int32, device=dev)
     keep = torch.full((max(B, 1),), -7, dtype=torch.int32, device=dev)
     sel = torch.full((max(total, 1),), -7, dtype=torch.int32, device=dev)
+    pair = torch.full((max(total, 1),), -7, dtype=torch.int32, device=dev)
+    ratio = torch.full((max(B, 1),), -7.0, dtype=torch.float32, device=dev)
     dens = torch.from_numpy(batch.density).to(dev)
     text = rt.make_text_spans(pre, po, prow, suf, so, srow)
-    rt.check(rt.rtprune_prune_splice(db, dens, p, text, mode, seq, cap, seq_off, pos, keep, sel, None, None, ws))
+    rt.check(rt.rtprune_prune_splice(db, dens, p, text, mode, seq, cap, seq_off, pos, keep, sel, pair, ratio, ws))
     torch.cuda.synchronize()
     assert int(ws[:4].view(torch.int32).item()) == 0
     return dict(seq=hz._np(seq), seq_off=seq_off.cpu().numpy(), pos=pos.cpu().numpy(),
-                keep=keep.cpu().numpy(), sel=sel.cpu().numpy(), cap=cap)
+                keep=keep.cpu().numpy(), sel=sel.cpu().numpy(), pair=pair.cpu().numpy(),
+                ratio=ratio.cpu().numpy(), cap=cap)
 
 
 @pytest.mark.parametrize("mode", [orc.POSITIONS_CONSECUTIVE, orc.POSITIONS_ORIGINAL])
@@ -83,8 +88,18 @@ def test_splice_matches_oracle_and_packed_output(cfg, images, mode):
     assert (g["pos"][at:] == -7).all()
     tail = g["seq"][at:]
     assert (tail == tail.flat[0]).all() if tail.size else True
-    # and the spliced visual rows are the rows the oracle's merge gives (usual bars)
-    rep = hz.compare_batch(batch, f, staged=False)
+    # and the visual rows inside the sequences, taken from `seq` itself (with the kept
+    # counts, index lists, pairing and retention the splice call returned), are the rows
+    # the oracle's merge gives, to the bars of every other parity test
+    pre_n = np.diff(poff)
+    vis, vis_off = [], np.zeros(B + 1, dtype=np.int32)
+    for b in range(B):
+        a = int(g["seq_off"][b]) + int(pre_n[b])
+        vis.append(g["seq"][a:a + int(g["keep"][b])])
+        vis_off[b + 1] = vis_off[b] + int(g["keep"][b])
+    from_seq = dict(out=np.concatenate(vis, axis=0), out_offsets=vis_off, keep=g["keep"][:B], sel=g["sel"],
+                    pair=g["pair"], ratio=g["ratio"][:B])
+    rep = hz.compare_batch(batch, from_seq, staged=False)
     assert rep.images == B
 
 
