@@ -32,29 +32,10 @@ BF16_MFMA_TFLOPS = 2500.0      # dense bf16 matrix-core peak
 COMPUTE_UNITS = 256
 
 
-def _gen_one(args):
-    from paper_2605_00392_amd import synth
-    cfg, i = args
-    x, rho = synth.gen_image(cfg, i)
-    return synth.f32_to_bf16_bits(x) if synth.WORKLOADS[cfg].dtype == "bf16" else x, float(rho)
-
-
 def generate(cfg: int, workers: int):
-    """Draw the workload on the host (a process pool only speeds the drawing up)."""
+    """Draw the workload on the host (worker processes only speed the drawing up)."""
     from paper_2605_00392_amd import synth
-    w = synth.WORKLOADS[cfg]
-    workers = max(1, min(workers, 16, (os.cpu_count() or 1)))
-    if w.batch < 64 or workers == 1:
-        return synth.gen_batch(cfg)
-    import multiprocessing as mp
-    with mp.get_context("fork").Pool(workers) as pool:
-        parts = pool.map(_gen_one, [(cfg, i) for i in range(w.batch)], chunksize=8)
-    counts = [p[0].shape[0] for p in parts]
-    offsets = np.zeros(len(counts) + 1, dtype=np.int32)
-    offsets[1:] = np.cumsum(counts)
-    tokens = np.concatenate([p[0] for p in parts], axis=0)
-    dens = np.asarray([p[1] for p in parts], dtype=np.float32)
-    return synth.Batch(cfg, w.dtype, tokens, offsets, dens, dict(w.params), list(range(w.batch)))
+    return synth.gen_batch_parallel(cfg, max(1, min(workers, 16, (os.cpu_count() or 1))))
 
 
 def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, iters: int,

@@ -34,9 +34,11 @@
  *   of the call skip its work, touch no output, and set a nonzero int32 at
  *   byte 0 of the workspace (see RTP_DEV_*).  No call crashes on bad data.
  * - Limits: 1 <= D <= 4096 and D % 4 == 0 (D % 8 == 0 for bf16);
- *   max_tokens <= 8192;
+ *   max_tokens <= 8192; B <= 65535 (an image is a row of the launch grids);
  *   (max(1,z) - min(-1,z)) / eps <= 600 (else RTP_EUNSUPPORTED).
- * - Calls are thread-safe as long as concurrent calls use distinct workspaces.
+ * - The operator's calls keep no state between calls and are thread-safe as long
+ *   as concurrent calls use distinct workspaces (the measurement aids at the end
+ *   of this header are process-wide switches; see there).
  */
 #ifndef RTPRUNE_H
 #define RTPRUNE_H
@@ -94,6 +96,13 @@ typedef struct rtprune_params {
   float phi_lo;    /* f_normalize(phi) = clamp((phi - phi_lo) / (phi_hi - phi_lo), 0, 1) */
   float phi_hi;    /* phi_hi > phi_lo */
   int32_t metric;  /* rtp_metric: the importance score stage 1 ranks tokens by */
+  int32_t mid_merge_min_images; /* kernel choice only, no effect on what is computed beyond the
+                      order of fp32 additions in the merge: images with 17 to 64 pruned tokens have
+                      a merge kernel of their own (kept rows streamed past the matrix cores), which
+                      the calls with a workspace run only when the batch holds at least this many
+                      such images (a few cost less inside the vector kernel's launch).  0: decide by
+                      the size of the chip (four 128-row tiles per compute unit: 256 images of 400
+                      tokens on MI355X); n > 0: from n such images on.  >= 0 */
 } rtprune_params;
 
 /* One packed ragged batch of visual tokens. */
@@ -110,11 +119,24 @@ typedef struct rtprune_batch {
 /* Name of a status code (host string, static storage). */
 const char* rtprune_status_string(int status);
 
-/* Bytes of device workspace any call below needs for a batch of this shape.
- * `bytes` is a host pointer.  The workspace must be 256-byte aligned.  Its
- * content is scratch: nothing is carried from one call to the next. */
+/* Bytes of device workspace for a batch of this shape.  `bytes` is a host
+ * pointer.  The workspace must be 256-byte aligned.  Its content is scratch:
+ * nothing is carried from one call to the next, and it need not be cleared.
+ *   params = NULL  the worst case over all parameters: enough for every call
+ *                  below, whatever kept counts the staged calls are given
+ *                  (the kernel matrix and the plan take
+ *                  12 * total_tokens * max_tokens / 4 bytes of it);
+ *   params given   what rtprune_prune, rtprune_prune_splice,
+ *                  rtprune_dynamic_ratio and rtprune_norms_topk need with
+ *                  these parameters: the fixed retention, or the clamp of the
+ *                  dynamic one, bounds every pruned set by
+ *                  (1 - retention) * max_tokens + 1 tokens, and the kernel
+ *                  matrix and the plan are sized from that bound.
+ *                  rtprune_ot_pair and rtprune_merge take their kept counts
+ *                  from the caller and always ask for the worst case. */
 int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t max_tokens,
-                            int32_t D, int32_t dtype, size_t* bytes);
+                            int32_t D, int32_t dtype, const rtprune_params* params,
+                            size_t* bytes);
 
 /* Dynamic pruning ratio (Sec. 3.3.3).  For each image: phi = mean pairwise
  * cosine over all its tokens (Eq. 7; 0 when N < 2; a zero-norm token has cosine
@@ -276,9 +298,13 @@ int rtprune_text_density(const uint8_t* pixels, const int64_t* pixel_offsets,
                          const int32_t* patch_offsets, void* workspace,
                          size_t workspace_bytes, void* stream);
 
-/* Measurement aid (not part of the operator; process-global, not thread-safe).
+/* Measurement aid (not part of the operator).  The switches are process-wide:
+ * they may be flipped from any thread, and they apply to every call that starts
+ * after the flip, on whichever thread; a program that prunes from several
+ * threads while recording gets all of their launches in one summary.
  * While enabled, every kernel the calls above launch is bracketed by two HIP
- * events recorded on the launch stream.  rtprune_profile_enable(1) discards
+ * events recorded on the launch stream (events are created per launch: with the
+ * aid on, calls allocate).  rtprune_profile_enable(1) discards
  * earlier records and starts recording, (0) stops.  rtprune_profile_summary
  * waits for the recorded events and writes a JSON array
  *   [{"kernel": name, "launches": n, "total_ms": t}, ...]
@@ -290,15 +316,6 @@ int rtprune_profile_summary(char* buf, size_t cap);
  * few microseconds of stream time, so a timed region that wants one kernel's
  * duration records that kernel alone.  RTP_EINVAL for an unknown name. */
 int rtprune_profile_only(const char* kernel);
-
-/* Tuning and test aid (process-global, not thread-safe).  Images with 17 to 64
- * pruned tokens have a merge kernel of their own (the kept rows streamed past
- * the matrix cores), which the calls with a workspace run only when the batch holds
- * at least `min_images` of them; a few cost less inside the vector kernel's
- * launch.  The default (restored by a negative value) is four 128-row tiles per
- * compute unit: 256 images of 400 tokens on MI355X.  Returns the value in force
- * before the call (-1: the default). */
-int rtprune_mid_merge_min_images(int min_images);
 
 /* Measurement aid: a plain device-to-device copy kernel (`k_copy`) of `bytes`
  * bytes (a multiple of 16; both pointers 16-byte aligned, non-overlapping).

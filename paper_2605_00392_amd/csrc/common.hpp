@@ -10,6 +10,7 @@ namespace rtp {
 constexpr int kWave = 64;
 constexpr int kMaxTokens = 8192;   // per image
 constexpr int kMaxD = 4096;
+constexpr int kMaxImages = 65535;  // per call: an image is a row (y) of the launch grids
 constexpr double kTinyNorm = 1e-12;
 
 typedef unsigned short bf16_t;     // raw bfloat16 bit pattern
@@ -47,6 +48,7 @@ struct DevParams {
   double shift;      // max(1, z): exp((s - shift) / eps) <= 1 for every score s
   float ratio, ratio_min, ratio_max, phi_lo, phi_hi;
   int iters, dynamic, metric;
+  int mid_min;  // rtprune_params::mid_merge_min_images (0: decided by the size of the chip)
   int mode;    // which Sinkhorn kernels the call launches (kMode... bits)
   int k32;     // those images' kernel matrix is stored in fp32 (its range allows it)
 };

@@ -18,10 +18,7 @@
 
 namespace rtp {
 
-#ifndef RTP_MERGE_BLOCK_ROWS
-#define RTP_MERGE_BLOCK_ROWS 16
-#endif
-constexpr int kMergeBlockRows = RTP_MERGE_BLOCK_ROWS;
+constexpr int kMergeBlockRows = 16;   // kept rows per workgroup
 constexpr int kMergeWaveRows = 4;    // kept rows a wave merges at a time
 constexpr int kMergeLdsBytes = 30 * 1024;
 constexpr int kMergeMaxChunk = 64;   // pruned rows per LDS chunk, at most one per lane

@@ -7,6 +7,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <type_traits>
@@ -15,7 +16,7 @@
 #include "rtprune.h"
 #include "common.hpp"
 #include "stage1.hpp"
-#include "stage2_ref.hpp"
+#include "stage2_general.hpp"
 #include "sinkhorn_team.hpp"
 #include "sinkhorn_dual.hpp"
 #include "sinkhorn_sweep.hpp"
@@ -45,7 +46,8 @@ struct Layout {
   long long strip_cap;  // entries available in the per-strip arrays
 };
 
-Layout make_layout(int B, long long total, int max_tokens, int D) {
+// `rmax`: an upper bound on any image's pruned set (max_tokens when nothing is known).
+Layout make_layout(int B, long long total, int max_tokens, int D, int rmax) {
   Layout L;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
@@ -57,8 +59,9 @@ Layout make_layout(int B, long long total, int max_tokens, int D) {
   const long long all_chunks = static_cast<long long>(B) * L.chunks_per_image;
   L.chunks_per_part = static_cast<int>(std::min<long long>(L.chunks_per_image, std::max<long long>(1, all_chunks / kNormMinWorkgroups)));
   L.parts_per_image = (L.chunks_per_image + L.chunks_per_part - 1) / L.chunks_per_part;
-  // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4
-  L.plan_cap = total * static_cast<long long>(max_tokens) / 4 + 1;
+  // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4, and <= sum_b N_b rmax
+  L.plan_cap = std::min(total * static_cast<long long>(max_tokens) / 4,
+                        total * static_cast<long long>(std::max(0, std::min(rmax, max_tokens)))) + 1;
   L.status = take(256);
   L.norm64 = take(sizeof(double) * total);
   L.score = take(sizeof(float) * total);
@@ -102,7 +105,7 @@ int check_batch(const rtprune_batch* in) {
   if (in->total_tokens > 0 && !in->tokens) return RTP_EINVAL;
   if (reinterpret_cast<uintptr_t>(in->tokens) % 16 != 0) return RTP_EINVAL;
   if (in->D % 4 != 0 || (in->dtype == RTP_BF16 && in->D % 8 != 0)) return RTP_EUNSUPPORTED;
-  if (in->D > kMaxD || in->max_tokens > kMaxTokens) return RTP_EUNSUPPORTED;
+  if (in->D > kMaxD || in->max_tokens > kMaxTokens || in->B > kMaxImages) return RTP_EUNSUPPORTED;
   if (in->total_tokens > 0x7fffffffLL) return RTP_EUNSUPPORTED;
   if (in->total_tokens > static_cast<long long>(in->B) * in->max_tokens) return RTP_EINVAL;
   return RTP_OK;
@@ -112,6 +115,7 @@ int check_params(const rtprune_params* p, DevParams* d) {
   if (!p) return RTP_EINVAL;
   if (!(p->eps > 0.f) || p->iters < 0) return RTP_EINVAL;
   if (p->metric != RTP_METRIC_L2NORM && p->metric != RTP_METRIC_VARIANCE) return RTP_EINVAL;
+  if (p->mid_merge_min_images < 0) return RTP_EINVAL;
   if (!std::isfinite(p->z) || !std::isfinite(p->alpha) || !std::isfinite(p->eps)) return RTP_EINVAL;
   if (p->dynamic) {
     if (!(p->ratio_min > 0.f) || !(p->ratio_max <= 1.f) || !(p->ratio_min <= p->ratio_max)) return RTP_EINVAL;
@@ -134,13 +138,23 @@ int check_params(const rtprune_params* p, DevParams* d) {
   d->iters = p->iters;
   d->dynamic = p->dynamic ? 1 : 0;
   d->metric = p->metric;
+  d->mid_min = p->mid_merge_min_images;
   d->mode = 0;                                   // set per batch by launch_ot
   d->k32 = (hi - lo) / eps <= 80.0 ? 1 : 0;      // exp(-80) is a normal fp32 number
   return RTP_OK;
 }
 
-int check_ws(const rtprune_batch* in, void* ws, size_t ws_bytes, Layout* L) {
-  *L = make_layout(in->B, in->total_tokens, in->max_tokens, in->D);
+// Largest pruned set an image of at most `max_tokens` tokens can have under these
+// parameters: R = N - ceil(retention N - 1e-3) <= (1 - retention) N + 1, with the fixed
+// retention or the lower clamp of the dynamic one.
+int params_pruned_bound(const DevParams& p, int max_tokens) {
+  const double keep = p.dynamic ? static_cast<double>(p.ratio_min) : static_cast<double>(p.ratio);
+  return std::min(std::max(max_tokens - 1, 0), static_cast<int>((1.0 - keep) * max_tokens) + 1);
+}
+constexpr int kPrunedAny = 1 << 30;   // make_layout: no bound on the pruned sets
+
+int check_ws(const rtprune_batch* in, int rmax, void* ws, size_t ws_bytes, Layout* L) {
+  *L = make_layout(in->B, in->total_tokens, in->max_tokens, in->D, rmax);
   if (!ws || reinterpret_cast<uintptr_t>(ws) % kAlign != 0 || ws_bytes < L->total) return RTP_EWORKSPACE;
   return RTP_OK;
 }
@@ -149,13 +163,13 @@ inline int launched() { return hipGetLastError() == hipSuccess ? RTP_OK : RTP_EH
 
 // Compute units of the current device (256 on MI355X; that value if the query fails).
 int compute_units() {
-  static int cached = 0;   // one kind of device per process; a repeated query gives the same value
-  if (cached > 0) return cached;
+  static std::atomic<int> cached{0};   // one kind of device per process; a repeated query gives the same value
+  if (cached.load(std::memory_order_relaxed) > 0) return cached.load(std::memory_order_relaxed);
   int dev = 0, n = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
     n = 256;
-  cached = n;
+  cached.store(n, std::memory_order_relaxed);
   return n;
 }
 
@@ -176,9 +190,9 @@ const char* const kKernelNames[KID_COUNT] = {"k_prepare", "k_norms", "k_select",
                                              "k_density_finish", "k_splice"};
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct ProfState {
-  std::mutex mu;
-  bool on = false;
-  int only = -1;               // >= 0: record this kernel id alone (rtprune_profile_only)
+  std::mutex mu;               // guards `recs`
+  std::atomic<bool> on{false};
+  std::atomic<int> only{-1};   // >= 0: record this kernel id alone (rtprune_profile_only)
   std::vector<ProfRec> recs;
 } g_prof;
 
@@ -188,7 +202,8 @@ struct ProfScope {
   hipEvent_t start = nullptr, stop = nullptr;
   bool live = false;
   ProfScope(int kid_, hipStream_t s_) : kid(kid_), s(s_) {
-    if (!g_prof.on || (g_prof.only >= 0 && g_prof.only != kid)) return;
+    const int only = g_prof.only.load(std::memory_order_relaxed);
+    if (!g_prof.on.load(std::memory_order_relaxed) || (only >= 0 && only != kid)) return;
     if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) return;
     live = hipEventRecord(start, s) == hipSuccess;
   }
@@ -372,6 +387,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   if (!classified) {
     ProfScope prof(KID_CLASSIFY, s);
     hipLaunchKernelGGL(k_classify, dim3(1), dim3(256), 0, s, in->offsets, keep, in->B, work, p.mode, st);
+    RTP_TRY(launched());
   }
   RTP_TRY(in->dtype == RTP_BF16
               ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, s)
@@ -447,8 +463,6 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
   return launched();
 }
 
-int g_mid_min_images = -1;   // rtprune_mid_merge_min_images; negative: by the size of the chip
-
 template <typename T>
 int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                    const int32_t* keep, const int32_t* out_off, const float* plan,
@@ -467,8 +481,7 @@ int launch_merge_t(const rtprune_batch* in, const DevParams& p, const int32_t* s
   const bool mid = std::is_same<T, bf16_t>::value && in->D % kMergeMidFeatures == 0 && rmax > kMergeMidMin && work && status;
   // (when the device counts enough of them to fill the chip: four row tiles per compute unit)
   const int tiles_mid = (in->max_tokens + kMergeMidBlockRows - 1) / kMergeMidBlockRows;
-  const int mid_min = g_mid_min_images >= 0 ? g_mid_min_images
-                                            : std::max(1, (4 * compute_units() + tiles_mid - 1) / tiles_mid);
+  const int mid_min = p.mid_min > 0 ? p.mid_min : std::max(1, (4 * compute_units() + tiles_mid - 1) / tiles_mid);
   const MergeSkip skip{(tiled ? kSkipTiled : 0) | (mid ? kSkipMid : 0), mid ? work + kListMid : nullptr, mid_min};
   ProfScope prof(KID_MERGE, s);
   if (in->D <= 1280) {
@@ -562,12 +575,6 @@ extern "C" int rtprune_copy_bytes(void* dst, const void* src, size_t bytes, void
   return launched();
 }
 
-extern "C" int rtprune_mid_merge_min_images(int min_images) {
-  const int before = g_mid_min_images;
-  g_mid_min_images = min_images < 0 ? -1 : min_images;
-  return before;
-}
-
 extern "C" int rtprune_profile_enable(int on) {
   std::lock_guard<std::mutex> g(g_prof.mu);
   for (ProfRec& r : g_prof.recs) {
@@ -620,8 +627,14 @@ extern "C" int rtprune_profile_summary(char* buf, size_t cap) {
 }
 
 extern "C" int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t max_tokens, int32_t D,
-                                       int32_t dtype, size_t* bytes) {
+                                       int32_t dtype, const rtprune_params* params, size_t* bytes) {
   if (!bytes) return RTP_EINVAL;
+  int rmax = kPrunedAny;
+  if (params) {
+    DevParams p;
+    RTP_TRY(check_params(params, &p));
+    rmax = params_pruned_bound(p, max_tokens);
+  }
   rtprune_batch in;
   std::memset(&in, 0, sizeof(in));
   int32_t dummy = 0;
@@ -634,7 +647,8 @@ extern "C" int rtprune_workspace_bytes(int32_t B, int64_t total_tokens, int32_t 
   in.dtype = dtype;
   RTP_TRY(check_batch(&in));
   if (total_tokens < 0 || total_tokens > 0x7fffffffLL) return RTP_EINVAL;
-  *bytes = make_layout(B, total_tokens, max_tokens, D).total;
+  if (total_tokens > static_cast<long long>(B) * max_tokens) return RTP_EINVAL;
+  *bytes = make_layout(B, total_tokens, max_tokens, D, rmax).total;
   return RTP_OK;
 }
 
@@ -734,7 +748,7 @@ extern "C" int rtprune_dynamic_ratio(const rtprune_batch* in, const float* densi
   }
   if (!density || !keep_counts) return RTP_EINVAL;
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, 0 /* no kernel matrix or plan */, workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
   RTP_TRY(launch_norms(in, 1, p.metric, L, workspace, nullptr, s));
@@ -755,7 +769,7 @@ extern "C" int rtprune_norms_topk(const rtprune_batch* in, const int32_t* keep_c
   RTP_TRY(check_params(&q, &p));
   if (!sel_idx || !keep_counts || !out_offsets || !plan_offsets) return RTP_EINVAL;
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, 0 /* no kernel matrix or plan */, workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* status = at<int32_t>(workspace, L.status);
   RTP_TRY(launch_prepare(in, status, s));
@@ -774,7 +788,7 @@ extern "C" int rtprune_ot_pair(const rtprune_batch* in, const int32_t* sel_idx,
   RTP_TRY(check_params(params, &p));
   if (!sel_idx || !keep_counts || !plan_offsets) return RTP_EINVAL;
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, kPrunedAny, workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   RTP_TRY(launch_prepare(in, at<int32_t>(workspace, L.status), s));
   // exact squared norms of every row (fp32 norms from stage 1 would cost 1e-7 on S)
@@ -799,7 +813,7 @@ extern "C" int rtprune_merge(const rtprune_batch* in, const int32_t* sel_idx,
                         nullptr, s);
   // with a workspace the images are sorted by pruned count first, as in the fused calls
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, kPrunedAny, workspace, workspace_bytes, &L));
   int32_t* status = at<int32_t>(workspace, L.status);
   int32_t* work = at<int32_t>(workspace, L.work);
   RTP_TRY(launch_prepare(in, status, s));
@@ -821,7 +835,7 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   if (!out || !out_offsets) return RTP_EINVAL;
   if (p.dynamic && !density) return RTP_EINVAL;
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, params_pruned_bound(p, in->max_tokens), workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* status = at<int32_t>(workspace, L.status);
   int32_t* keep = keep_counts ? keep_counts : at<int32_t>(workspace, L.keep);
@@ -867,7 +881,7 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   if (need > 0x7fffffffLL) return RTP_EUNSUPPORTED;
   if (static_cast<long long>(in->D) * (in->dtype == RTP_BF16 ? 2 : 4) % 16 != 0) return RTP_EUNSUPPORTED;
   Layout L;
-  RTP_TRY(check_ws(in, workspace, workspace_bytes, &L));
+  RTP_TRY(check_ws(in, params_pruned_bound(p, in->max_tokens), workspace, workspace_bytes, &L));
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* status = at<int32_t>(workspace, L.status);
   int32_t* keep = keep_counts ? keep_counts : at<int32_t>(workspace, L.keep);

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // (the same for the whole workgroup)
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
-  const bool k_f32 = kernel_is_f32(p, m, r);
+  const int k_layout = kernel_layout(p, m, r);
   const int32_t* sel = sel_idx + lo;
   const double inv_eps = 1.0 / p.eps;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
           const double ni = norm64[lo + clamp_index(sel[i], n)];
           const double sc = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
           const long long at = static_cast<long long>(i) * r + j;
-          store_kernel(kmat, po, i, j, r, exp((sc - p.shift) * inv_eps), k_f32);
+          store_kernel(kmat, po, i, j, m, r, exp((sc - p.shift) * inv_eps), k_layout);
           if (scores_out) scores_out[po + at] = sc;
         }
       }

@@ -92,7 +92,10 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
   if (lane < 32) ys[wave][lane] = y;
   __syncthreads();
 
-  for (int it = 0; it < p.iters; ++it) {
+  // (the loop ends as soon as the iterates repeat: see settled_stop)
+  __shared__ int moved[kDualThreads / 64];
+  int stop_at = p.iters;
+  for (int it = 0; it < stop_at; ++it) {
     // ---- u-update (row copy) ----
     {
       double s0 = 0.0, s1 = 0.0;
@@ -101,10 +104,19 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
         s0 = fma(Kr[c], ys[wave][c], s0);
         s1 = fma(Kr[c + 1], ys[wave][c + 1], s1);
       }
-      x = (tid <= m) ? a_row * rcp64(s0 + s1) : 0.0;
+      const double xn = (tid <= m) ? a_row * rcp64_tight(s0 + s1) : 0.0;
+      const int bits = __builtin_amdgcn_ballot_w64(__double_as_longlong(xn) != __double_as_longlong(x)) != 0 ? 1 : 0;
+      x = xn;
       xs[tid] = x;
+      if (lane == 0) moved[wave] = bits;   // (rewritten only after the next barrier but one)
     }
     __syncthreads();
+    {
+      int moved_bits = 0;
+#pragma unroll
+      for (int w = 0; w < kDualThreads / 64; ++w) moved_bits |= moved[w];
+      stop_at = settled_stop(stop_at, it, moved_bits != 0);   // the same in every thread
+    }
     // ---- v-update (column copy) ----
     {
       const double* xq = xs + 32 * q;
@@ -121,7 +133,7 @@ __device__ __forceinline__ void sinkhorn_dual_image(const SinkhornArgs& A, int b
       double t = 0.0;
 #pragma unroll
       for (int c = 0; c < kDualChunks; ++c) t += part[c][j];
-      y = (j <= r) ? b_col * rcp64(t) : 0.0;
+      y = (j <= r) ? b_col * rcp64_tight(t) : 0.0;
       if (lane < 32) ys[wave][lane] = y;   // read back by this wave only
     }
   }
@@ -235,7 +247,9 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
   ys[wave][lane] = y;
   __syncthreads();
 
-  for (int it = 0; it < p.iters; ++it) {
+  __shared__ int moved[NW];                // (the loop ends as soon as the iterates repeat: see settled_stop)
+  int stop_at = p.iters;
+  for (int it = 0; it < stop_at; ++it) {
     {
       double s0 = 0.0, s1 = 0.0;
 #pragma unroll
@@ -243,10 +257,19 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
         s0 = fma(Kr[c], ys[wave][c], s0);
         s1 = fma(Kr[c + 1], ys[wave][c + 1], s1);
       }
-      x = (tid <= m) ? a_row * rcp64(s0 + s1) : 0.0;
+      const double xn = (tid <= m) ? a_row * rcp64_tight(s0 + s1) : 0.0;
+      const int bits = __builtin_amdgcn_ballot_w64(__double_as_longlong(xn) != __double_as_longlong(x)) != 0 ? 1 : 0;
+      x = xn;
       xs[tid] = x;
+      if (lane == 0) moved[wave] = bits;
     }
     __syncthreads();
+    {
+      int moved_bits = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) moved_bits |= moved[w];
+      stop_at = settled_stop(stop_at, it, moved_bits != 0);
+    }
     {
       const double* xq = xs + CR * wave;
       double s0 = 0.0, s1 = 0.0;
@@ -262,7 +285,7 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
       double t = 0.0;
 #pragma unroll
       for (int c = 0; c < NW; ++c) t += part[c][lane];
-      y = (lane <= r) ? b_col * rcp64(t) : 0.0;
+      y = (lane <= r) ? b_col * rcp64_tight(t) : 0.0;
       ys[wave][lane] = y;                  // read back by this wave only
     }
   }
@@ -405,8 +428,8 @@ __global__ __launch_bounds__(256) void k_scan_classify(const int32_t* __restrict
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are
 // handed out longest-running role first: the wide teams, team C, team B, two-copy (48 columns),
-// one-wave (eight images per workgroup), two-copy (32 columns), two-wave (two or
-// four images per workgroup).  `cus`: compute units of the device.
+// two-copy (32 columns), two-wave (two or four images per workgroup), one-wave (eight
+// images per workgroup).  `cus`: compute units of the device.
 __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
                                                                const int32_t* __restrict__ work, int B, int cus,
                                                                const int32_t* __restrict__ status) {
@@ -439,14 +462,6 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
     return;
   }
   blk -= cnt;
-  const int nA = work[kVariantA];
-  cnt = (nA + kWavesPerBlock - 1) / kWavesPerBlock;
-  if (blk < cnt) {
-    const int idx = blk * kWavesPerBlock + wave;
-    if (idx < nA) sinkhorn_waves_image<WaveShape>(A, work[NV + kVariantA * B + idx], wave, 0, lane);
-    return;
-  }
-  blk -= cnt;
   cnt = work[kVariantDual];
   if (blk < cnt) { sinkhorn_dual_image(A, work[NV + kVariantDual * B + blk]); return; }
   blk -= cnt;
@@ -456,15 +471,25 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
   // first four waves, so that each wave has a SIMD to itself: the iteration is
   // bound by instruction issue (1.3 -> 0.7 us).  Waves without an image end at
   // once; a wave that has ended no longer counts at the workgroup's barriers.
+  const int nA = work[kVariantA];
   const int nP = work[kVariantPair];
   const int others = work[kVariantWideA] + work[kVariantWideB] + work[kVariantWideC] + work[kVariantC] +
                      work[kVariantB] + work[kVariantDual48] +
                      (nA + kWavesPerBlock - 1) / kWavesPerBlock + work[kVariantDual];
   const int per_block = others + (nP + 1) / 2 <= cus ? 2 : kWavesPerBlock / PairShape::kWaves;
-  if (blk < (nP + per_block - 1) / per_block) {
+  cnt = (nP + per_block - 1) / per_block;
+  if (blk < cnt) {
     const int slot = wave / PairShape::kWaves, idx = blk * per_block + slot;
     if (slot >= per_block || idx >= nP) return;
     sinkhorn_waves_image<PairShape>(A, work[NV + kVariantPair * B + idx], slot, wave % PairShape::kWaves, lane);
+    return;
+  }
+  blk -= cnt;
+  // one-wave images, eight per workgroup: the shortest-running role, handed out last
+  cnt = (nA + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (blk < cnt) {
+    const int idx = blk * kWavesPerBlock + wave;
+    if (idx < nA) sinkhorn_waves_image<WaveShape>(A, work[NV + kVariantA * B + idx], wave, 0, lane);
   }
 }
 

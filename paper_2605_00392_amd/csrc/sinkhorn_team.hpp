@@ -31,6 +31,29 @@ __device__ __forceinline__ double rcp64(double d) {
   return fma(fma(-d, r, 1.0), r, r);
 }
 
+// Where the iteration loop may end.  One iteration maps (x, y) to (x', y') by
+// x' = f(y), y' = g(x'), in a fixed order of operations, so it is a function of
+// the state's bits.  `moved` says whether the x just computed in iteration `it`
+// (0-based) differs anywhere from the previous x.  If it does not, and the previous
+// x itself came out of an update (it >= 1, so that the current y is g of it), the y
+// about to be computed repeats too, and so does every later iterate: this iteration
+// is the last that needs running, and the state after it equals, bit for bit, the
+// state after all the iterations asked for.  (Iterates that alternate between two
+// states were looked for as well and do not occur: pages that do not settle wander.)
+__device__ __forceinline__ int settled_stop(int stop_at, int it, bool moved) {
+  return (it >= 1 && !moved) ? min(stop_at, it + 1) : stop_at;
+}
+
+// 1 / d to the last bit or two: a second Newton step on top of rcp64's.  The shapes
+// that stop once their iterates repeat (settled_stop) use it: with the one-step value,
+// off by up to ten units in the last place, the iterates of one page in seven wander
+// among neighbouring values without ever repeating; with this one 97 % of 1024
+// benchmark pages settle, after 35 iterations on average.
+__device__ __forceinline__ double rcp64_tight(double d) {
+  const double r = rcp64(d);
+  return fma(fma(-d, r, 1.0), r, r);
+}
+
 template <int W_, int LOG_TC_, int RPT_, int CPT_>
 struct TeamShape {
   static constexpr int W = W_, LOG_TC = LOG_TC_, RPT = RPT_, CPT = CPT_;
@@ -122,12 +145,26 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   return kGeneralVariant;
 }
 
-// The kernel matrix of an image the sweep kernels take is stored in fp32 when
-// its range allows (p.k32): a relative rounding of 6e-8 on K = exp((S - shift)/eps)
-// is an absolute perturbation of eps * 6e-8 on the score S, below the scores' own
-// error, and it halves the bytes every iteration streams.
+// How an image's kernel matrix K = exp((S - shift)/eps) lies in its slot of the
+// workspace (plan_offsets[b], m r doubles); the score kernels write it and the
+// Sinkhorn kernel that serves the image reads it, both deciding by this function.
+//   kKernelRowsF64  row-major fp64, entry (i, j) at i r + j.
+//   kKernelRowsF32  the sweep kernels' images when the range allows (p.k32): fp32,
+//                   rows padded (k32_pitch).  A relative rounding of 6e-8 on K is an
+//                   absolute perturbation of eps * 6e-8 on the score S, below the
+//                   scores' own error, and it halves the bytes every iteration streams.
+//   kKernelColsF64  the one-, two- and eight-wave shapes, whose lanes own rows:
+//                   column-major fp64, entry (i, j) at j m + i, so that the 64 lanes of
+//                   a load read 64 consecutive entries (row-major, they read 64 cache
+//                   lines: the loads alone took 15 to 25 us of a workgroup's time).
+constexpr int kKernelRowsF64 = 0, kKernelRowsF32 = 1, kKernelColsF64 = 2;
+__device__ __forceinline__ int kernel_layout(const DevParams& p, int m, int r) {
+  const int v = sinkhorn_variant(m, r, p.mode);
+  if (v == kVariantSweep) return p.k32 ? kKernelRowsF32 : kKernelRowsF64;
+  return (v == kVariantA || v == kVariantPair || v == kVariantTall) ? kKernelColsF64 : kKernelRowsF64;
+}
 __device__ __forceinline__ bool kernel_is_f32(const DevParams& p, int m, int r) {
-  return p.k32 && sinkhorn_variant(m, r, p.mode) == kVariantSweep;
+  return kernel_layout(p, m, r) == kKernelRowsF32;
 }
 // fp32 layout of image b's kernel matrix: rows padded to a multiple of four
 // entries (when there are at least eight columns) and the first row on a 16-byte
@@ -137,9 +174,10 @@ __host__ __device__ inline int k32_pitch(int r) { return r >= 8 ? (r + 3) & ~3 :
 __device__ __forceinline__ float* k32_base(const double* kmat, long long po) {
   return reinterpret_cast<float*>(const_cast<double*>(kmat) + ((po + 1) & ~1LL));
 }
-__device__ __forceinline__ void store_kernel(double* __restrict__ kmat, long long po, int i, int j, int r,
-                                             double v, bool as_f32) {
-  if (as_f32) k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(v);
+__device__ __forceinline__ void store_kernel(double* __restrict__ kmat, long long po, int i, int j, int m, int r,
+                                             double v, int layout) {
+  if (layout == kKernelRowsF32) k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(v);
+  else if (layout == kKernelColsF64) kmat[po + static_cast<long long>(j) * m + i] = v;
   else kmat[po + static_cast<long long>(i) * r + j] = v;
 }
 

@@ -69,6 +69,58 @@ __device__ __forceinline__ double reduce_scatter(const double (&t)[C], int lane)
   return keep + (C == 8 ? dpp_move<0x140>(send) : dpp_move<0x128>(send));
 }
 
+// The same scatter with the maximum of 64-bit keys in place of the sum: the return
+// value is the largest of the wave's 64 candidates for column `wave_column<C>(lane)`.
+__device__ __forceinline__ long long key_max(long long a, long long b) { return a > b ? a : b; }
+__device__ __forceinline__ long long key_of(int hi, int lo) {
+  return (static_cast<long long>(hi) << 32) | static_cast<unsigned>(lo);
+}
+template <int CTRL>
+__device__ __forceinline__ long long dpp_move_key(long long v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(v >> 32), CTRL, 0xF, 0xF, false);
+  return key_of(hi, lo);
+}
+__device__ __forceinline__ long long max_halve32(long long a, long long b) {   // as halve32
+  const auto lo = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+  const auto hi = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(a >> 32), static_cast<unsigned>(b >> 32), false, false);
+  return key_max(key_of(static_cast<int>(hi[0]), static_cast<int>(lo[0])), key_of(static_cast<int>(hi[1]), static_cast<int>(lo[1])));
+}
+__device__ __forceinline__ long long max_halve16(long long a, long long b) {   // as halve16
+  const auto lo = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+  const auto hi = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a >> 32), static_cast<unsigned>(b >> 32), false, false);
+  return key_max(key_of(static_cast<int>(hi[0]), static_cast<int>(lo[0])), key_of(static_cast<int>(hi[1]), static_cast<int>(lo[1])));
+}
+template <int C>
+__device__ __forceinline__ long long max_scatter(const long long (&t)[C], int lane) {
+  static_assert(C == 8 || C == 16, "two shapes");
+  const bool b3 = (lane & 8) != 0;
+  long long h[C / 2];
+#pragma unroll
+  for (int c = 0; c < C / 2; ++c) h[c] = max_halve32(t[c], t[c + C / 2]);
+  long long q[C / 4];
+#pragma unroll
+  for (int c = 0; c < C / 4; ++c) q[c] = max_halve16(h[c], h[c + C / 4]);
+#pragma unroll
+  for (int c = 0; c < C / 4; ++c) {
+    q[c] = key_max(q[c], dpp_move_key<0xB1>(q[c]));                         // lane ^ 1
+    q[c] = key_max(q[c], dpp_move_key<0x4E>(q[c]));                         // lane ^ 2
+  }
+  long long v0, v1;
+  if (C == 8) {
+    v0 = key_max(q[0], dpp_move_key<0x141>(q[0]));
+    v1 = key_max(q[1], dpp_move_key<0x141>(q[1]));
+  } else {
+    const bool b2 = (lane & 4) != 0;
+    const long long k0 = b2 ? q[C == 8 ? 0 : 2] : q[0], s0 = b2 ? q[0] : q[C == 8 ? 0 : 2];
+    const long long k1 = b2 ? q[C == 8 ? 1 : 3] : q[1], s1 = b2 ? q[1] : q[C == 8 ? 1 : 3];
+    v0 = key_max(k0, dpp_move_key<0x141>(s0));
+    v1 = key_max(k1, dpp_move_key<0x141>(s1));
+  }
+  const long long keep = b3 ? v1 : v0, send = b3 ? v0 : v1;
+  return key_max(keep, C == 8 ? dpp_move_key<0x140>(send) : dpp_move_key<0x128>(send));
+}
+
 // One image on W waves.  `b` < 0 means no image: the waves only keep the
 // workgroup's barriers company.  `slot` numbers the image inside the workgroup,
 // `tw` the wave inside the image.
@@ -99,17 +151,25 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
   // Rows beyond the dustbin get a single 1 and a zero marginal, so their x is an
   // ordinary 0 and they add nothing to a column sum.
   double K[RPT][C], arow[RPT];
+  // Loads are unconditional (from a clamped position of a valid image, or the
+  // matrix's first entry otherwise) and all issued before the first of them is used,
+  // so that they are in flight together (left to itself the compiler waits for each
+  // one before the next: 20 us for a lane's 64 entries).  The matrix is stored column
+  // by column (kKernelColsF64): the lanes of a load read consecutive entries.
+#pragma unroll
+  for (int a = 0; a < RPT; ++a) {
+    const double* col0 = Kg + (active ? min(row0 + TR * a, m - 1) : 0);
+#pragma unroll
+    for (int c = 0; c < C; ++c) K[a][c] = col0[active ? static_cast<long long>(min(c, r - 1)) * m : 0];
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int a = 0; a < RPT; ++a) {
     const int i = row0 + TR * a;
-    // loads are unconditional (from a clamped position of a valid image, or the
-    // matrix's first entry otherwise) so that all of them are in flight together
-    const double* row = Kg + (active ? static_cast<long long>(min(i, m - 1)) * r : 0);
 #pragma unroll
     for (int c = 0; c < C; ++c) {
-      const double g = row[active ? min(c, r - 1) : 0];
       double v = 0.0;
-      if (active && i <= m && c <= r) v = (i < m && c < r) ? g : kz;
+      if (active && i <= m && c <= r) v = (i < m && c < r) ? K[a][c] : kz;
       if ((i > m || !active) && c == 0) v = 1.0;
       K[a][c] = v;
     }
@@ -128,15 +188,26 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
 #pragma unroll
   for (int c = 0; c < C; ++c) y[c] = (c <= r) ? 1.0 : 0.0;
 
-  for (int it = 0; it < p.iters; ++it) {
+  // The iteration is a fixed map of (x, y) in the device's arithmetic, so the end of
+  // the T iterations is known as soon as the iterates repeat (`settled_stop`): the
+  // rest is skipped without changing a bit of the result.  With several waves per image
+  // the waves agree through LDS, and the waves of a settled image keep meeting the
+  // workgroup's barrier, which the other images of the workgroup still use.
+  __shared__ int moved[2][kSinkhornBlockWaves];
+  int stop_at = p.iters;
+  for (int it = 0; it < stop_at; ++it) {
     // ---- u-update ----
+    bool differs = false;
 #pragma unroll
     for (int a = 0; a < RPT; ++a) {
       double acc = K[a][0] * y[0];
 #pragma unroll
       for (int c = 1; c < C; ++c) acc = fma(K[a][c], y[c], acc);
-      x[a] = arow[a] * rcp64(acc);
+      const double xn = arow[a] * rcp64_tight(acc);
+      differs |= __double_as_longlong(xn) != __double_as_longlong(x[a]);
+      x[a] = xn;
     }
+    int any_moved = __builtin_amdgcn_ballot_w64(differs) != 0 ? 1 : 0;
     // ---- v-update ----
     double t[C];
 #pragma unroll
@@ -149,15 +220,23 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
     double total = reduce_scatter<C>(t, lane);
     if (W > 1) {
       xchg[it & 1][W * slot + tw][lane] = total;
+      if (lane == 0) moved[it & 1][W * slot + tw] = any_moved;
       __syncthreads();
       total = 0.0;
+      any_moved = 0;
 #pragma unroll
-      for (int w = 0; w < W; ++w) total += xchg[it & 1][W * slot + w][lane];   // same order in every wave
+      for (int w = 0; w < W; ++w) {
+        total += xchg[it & 1][W * slot + w][lane];   // same order in every wave
+        any_moved |= moved[it & 1][W * slot + w];
+      }
     }
-    const double y_own = own_valid ? bcol * rcp64(total) : 0.0;
+    stop_at = settled_stop(stop_at, it, any_moved != 0);   // the same in every wave of the image
+    const double y_own = own_valid ? bcol * rcp64_tight(total) : 0.0;
 #pragma unroll
     for (int c = 0; c < C; ++c) y[c] = read_lane(y_own, column_lane<C>(c));
   }
+  if (W > 1)
+    for (int rest = stop_at; rest < p.iters; ++rest) __syncthreads();
   if (W == 1 && !active) return;
 
   // ---- plan and pairing (row m is the dustbin) ----
@@ -185,37 +264,27 @@ __device__ __forceinline__ void sinkhorn_waves_image(const SinkhornArgs& A, int 
     }
   }
   if (!pair_out) return;                               // the same for every wave of the workgroup
+  // A column's best over the wave's lanes: the largest key (value bits, then the lower
+  // row), found by the scatter that also adds up the column sums: 17 exchanges for 16
+  // columns where a butterfly per column takes 96.
+  long long key[C];
 #pragma unroll
-  for (int mask = 1; mask < kWave; mask <<= 1)
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-      const float ov = __shfl_xor(bv[c], mask, kWave);
-      const int oi = __shfl_xor(bi[c], mask, kWave);
-      if (ov > bv[c] || (ov == bv[c] && oi < bi[c])) { bv[c] = ov; bi[c] = oi; }
-    }
+  for (int c = 0; c < C; ++c) key[c] = key_of(__float_as_int(bv[c]), 0x7fffffff - bi[c]);   // plan entries are >= 0
+  const long long best = max_scatter<C>(key, lane);
   if (W == 1) {
-    if (lane == 0) {
-#pragma unroll
-      for (int c = 0; c < C; ++c)
-        if (c < r) pair_out[lo + m + c] = bi[c] >= m ? -1 : bi[c];
+    if (lane == column_lane<C>(own) && own < r) {
+      const int i = 0x7fffffff - static_cast<int>(best);
+      pair_out[lo + m + own] = i >= m ? -1 : i;
     }
   } else {
-    __shared__ float pv[kSinkhornBlockWaves][C];
-    __shared__ int pi[kSinkhornBlockWaves][C];
-    if (lane == 0) {
-#pragma unroll
-      for (int c = 0; c < C; ++c) { pv[W * slot + tw][c] = bv[c]; pi[W * slot + tw][c] = bi[c]; }
-    }
+    __shared__ long long pk[kSinkhornBlockWaves][C];
+    if (lane == column_lane<C>(own)) pk[W * slot + tw][own] = best;
     __syncthreads();
     if (active && tw == 0 && lane < r) {               // lane = column
-      float v = pv[W * slot][lane];
-      int i = pi[W * slot][lane];
+      long long k = pk[W * slot][lane];
 #pragma unroll
-      for (int w = 1; w < W; ++w) {
-        const float ov = pv[W * slot + w][lane];
-        const int oi = pi[W * slot + w][lane];
-        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-      }
+      for (int w = 1; w < W; ++w) k = key_max(k, pk[W * slot + w][lane]);
+      const int i = 0x7fffffff - static_cast<int>(k);
       pair_out[lo + m + lane] = i >= m ? -1 : i;
     }
   }

@@ -7,10 +7,7 @@
 
 namespace rtp {
 
-#ifndef RTP_NORM_ROWS_PER_CHUNK
-#define RTP_NORM_ROWS_PER_CHUNK 80
-#endif
-constexpr int kNormRowsPerChunk = RTP_NORM_ROWS_PER_CHUNK;  // token rows one workgroup of k_norms covers
+constexpr int kNormRowsPerChunk = 80;   // token rows one workgroup of k_norms covers
 constexpr int kNormThreads = 256;
 
 // Validate the ragged layout; every later kernel of the call skips its work

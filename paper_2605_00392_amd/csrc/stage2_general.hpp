@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void k_scores(
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ngroups = D >> 2;
   const long long po = plan_offsets[b];
-  const bool k_f32 = kernel_is_f32(p, m, r);
+  const int k_layout = kernel_layout(p, m, r);
   const int32_t* sel = sel_idx + lo;
   const double inv_eps = 1.0 / p.eps;
 
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void k_scores(
         const double nj = norm64[lo + tj];
         const double s = dot / fmax(ni * nj, kTinyNorm * kTinyNorm);
         const long long at = static_cast<long long>(i) * r + j;
-        store_kernel(kmat, po, i, j, r, exp((s - p.shift) * inv_eps), k_f32);
+        store_kernel(kmat, po, i, j, m, r, exp((s - p.shift) * inv_eps), k_layout);
         if (scores_out) scores_out[po + at] = s;
       }
     }

@@ -26,7 +26,7 @@ EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune", "rtprune_prune_splice",
     "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_profile_only", "rtprune_copy_bytes",
-    "rtprune_text_density_workspace_bytes", "rtprune_text_density", "rtprune_mid_merge_min_images",
+    "rtprune_text_density_workspace_bytes", "rtprune_text_density",
 )
 
 
@@ -40,7 +40,7 @@ class rtprune_params(ctypes.Structure):
         ("iters", ctypes.c_int32), ("dynamic", ctypes.c_int32),
         ("ratio", ctypes.c_float), ("ratio_min", ctypes.c_float), ("ratio_max", ctypes.c_float),
         ("phi_lo", ctypes.c_float), ("phi_hi", ctypes.c_float),
-        ("metric", ctypes.c_int32),
+        ("metric", ctypes.c_int32), ("mid_merge_min_images", ctypes.c_int32),
     ]
 
 
@@ -78,7 +78,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_status_string.restype = ctypes.c_char_p
     lib.rtprune_status_string.argtypes = [ctypes.c_int]
     lib.rtprune_workspace_bytes.restype = ctypes.c_int
-    lib.rtprune_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.rtprune_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, pp, ctypes.POINTER(ctypes.c_size_t)]
     lib.rtprune_dynamic_ratio.restype = ctypes.c_int
     lib.rtprune_dynamic_ratio.argtypes = [pb, vp, pp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.rtprune_norms_topk.restype = ctypes.c_int
@@ -92,8 +92,6 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_prune_splice.restype = ctypes.c_int
     lib.rtprune_prune_splice.argtypes = [pb, vp, pp, ctypes.POINTER(rtprune_text_spans), i32, vp, ctypes.c_int64,
                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
-    lib.rtprune_mid_merge_min_images.restype = ctypes.c_int
-    lib.rtprune_mid_merge_min_images.argtypes = [ctypes.c_int]
     lib.rtprune_profile_enable.restype = ctypes.c_int
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_only.restype = ctypes.c_int
@@ -115,13 +113,14 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
 def make_params(d: Optional[Dict[str, float]] = None, **kw) -> rtprune_params:
     """Fill the C parameter struct from a dict / keywords (paper defaults otherwise)."""
     v = dict(z=0.2, alpha=0.1, eps=0.05, iters=100, dynamic=0, ratio=0.84,
-             ratio_min=0.6, ratio_max=1.0, phi_lo=0.0, phi_hi=1.0, metric=RTP_METRIC_L2NORM)
+             ratio_min=0.6, ratio_max=1.0, phi_lo=0.0, phi_hi=1.0, metric=RTP_METRIC_L2NORM,
+             mid_merge_min_images=0)
     if d:
         v.update(d)
     v.update(kw)
     return rtprune_params(v["z"], v["alpha"], v["eps"], int(v["iters"]), int(v["dynamic"]),
                           v["ratio"], v["ratio_min"], v["ratio_max"], v["phi_lo"], v["phi_hi"],
-                          int(v["metric"]))
+                          int(v["metric"]), int(v["mid_merge_min_images"]))
 
 
 def _addr(x) -> Optional[int]:
@@ -186,10 +185,13 @@ def check(status: int) -> None:
 
 # --- the C entry points, name for name ---------------------------------------
 
-def rtprune_workspace_bytes(B: int, total_tokens: int, max_tokens: int, D: int, dtype: int):
-    """Returns ``(status, bytes)``."""
+def rtprune_workspace_bytes(B: int, total_tokens: int, max_tokens: int, D: int, dtype: int,
+                            params: Optional[rtprune_params] = None):
+    """Returns ``(status, bytes)``; ``params`` None asks for the worst case over all parameters."""
     n = ctypes.c_size_t(0)
-    rc = load_library().rtprune_workspace_bytes(B, total_tokens, max_tokens, D, dtype, ctypes.byref(n))
+    rc = load_library().rtprune_workspace_bytes(B, total_tokens, max_tokens, D, dtype,
+                                                ctypes.byref(params) if params is not None else None,
+                                                ctypes.byref(n))
     return rc, int(n.value)
 
 
@@ -256,10 +258,6 @@ def rtprune_prune_splice(batch: DeviceBatch, density, params: rtprune_params, te
         workspace.numel() if workspace is not None else 0, _stream(stream))
 
 
-def rtprune_mid_merge_min_images(min_images: int) -> int:
-    return load_library().rtprune_mid_merge_min_images(int(min_images))
-
-
 def rtprune_profile_enable(on: int) -> int:
     return load_library().rtprune_profile_enable(int(on))
 
@@ -297,9 +295,10 @@ def rtprune_text_density(pixels, pixel_offsets, heights, widths, B: int, max_hei
         _addr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream))
 
 
-def alloc_workspace(batch: DeviceBatch):
-    """A uint8 device tensor of the size ``rtprune_workspace_bytes`` asks for."""
+def alloc_workspace(batch: DeviceBatch, params: Optional[rtprune_params] = None):
+    """A uint8 device tensor of the size ``rtprune_workspace_bytes`` asks for (``params`` None:
+    enough for every call)."""
     import torch
-    rc, n = rtprune_workspace_bytes(batch.B, batch.total_tokens, batch.max_tokens, batch.D, batch.dtype)
+    rc, n = rtprune_workspace_bytes(batch.B, batch.total_tokens, batch.max_tokens, batch.D, batch.dtype, params)
     check(rc)
     return torch.empty(n, dtype=torch.uint8, device=batch.tokens.device)

@@ -246,6 +246,33 @@ def gen_batch(cfg: int, images: Optional[Sequence[int]] = None,
     return pack(cfg, w.dtype, xs, rho, w.params, ids)
 
 
+def _gen_packed_image(job):
+    cfg, i, d = job
+    x, rho = gen_image(cfg, i, d)
+    return (f32_to_bf16_bits(x) if WORKLOADS[cfg].dtype == "bf16" else x), float(rho)
+
+
+def gen_batch_parallel(cfg: int, workers: int = 0, d: int = D_MODEL) -> Batch:
+    """The same batch as :func:`gen_batch` (every image is drawn from its own seed), the
+    drawing spread over fresh worker processes; ``workers`` 0 = the host's cores, at most 16.
+    The workers are spawned, not forked, so this is safe in a process that has already
+    initialised a GPU."""
+    import multiprocessing as mp
+    import os
+    w = WORKLOADS[cfg]
+    workers = workers if workers > 0 else max(1, min(16, os.cpu_count() or 1))
+    if w.batch < 64 or workers == 1:
+        return gen_batch(cfg, d=d)
+    with mp.get_context("spawn").Pool(workers) as pool:
+        parts = pool.map(_gen_packed_image, [(cfg, i, d) for i in range(w.batch)], chunksize=8)
+    counts = [p[0].shape[0] for p in parts]
+    offsets = np.zeros(len(counts) + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    tokens = np.concatenate([p[0] for p in parts], axis=0)
+    dens = np.asarray([p[1] for p in parts], dtype=np.float32)
+    return Batch(cfg, w.dtype, tokens, offsets, dens, dict(w.params), list(range(w.batch)))
+
+
 def subset(batch: Batch, picks: Sequence[int]) -> Batch:
     """Re-pack the listed images (positions within ``batch``) as a new batch."""
     rows, rho, ids = [], [], []

@@ -60,7 +60,7 @@ def test_struct_layouts_match_the_header(tmp_path):
         assert int(got[st]) == ctypes.sizeof(cls), st
         for n in names:
             assert int(got[f"{st}.{n}"]) == getattr(cls, n).offset, (st, n)
-    assert ctypes.sizeof(rt.rtprune_params) == 44 and ctypes.sizeof(rt.rtprune_batch) == 40
+    assert ctypes.sizeof(rt.rtprune_params) == 48 and ctypes.sizeof(rt.rtprune_batch) == 40
 
 
 def test_status_strings(lib):
@@ -82,14 +82,28 @@ def test_workspace_bytes(lib):
     assert rt.rtprune_workspace_bytes(1, 64, 64, 1284, rt.RTP_BF16)[0] == rt.RTP_EUNSUPPORTED
     assert rt.rtprune_workspace_bytes(1, 64, 64, 8192, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
     assert rt.rtprune_workspace_bytes(1, 10000, 10000, 1280, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED
+    assert rt.rtprune_workspace_bytes(70000, 70000, 1, 64, rt.RTP_F32)[0] == rt.RTP_EUNSUPPORTED   # images per call
+    assert rt.rtprune_workspace_bytes(2, 1000, 400, 1280, rt.RTP_BF16)[0] == rt.RTP_EINVAL        # > B * max_tokens
 
 
-def test_mid_merge_minimum_is_a_process_wide_setting(lib):
-    """The tuning aid returns the value in force before the call; negative restores the default."""
-    assert rt.rtprune_mid_merge_min_images(3) == -1
-    assert rt.rtprune_mid_merge_min_images(0) == 3
-    assert rt.rtprune_mid_merge_min_images(-5) == 0
-    assert rt.rtprune_mid_merge_min_images(-1) == -1
+def test_workspace_bytes_follow_the_parameters(lib):
+    """With parameters the kernel matrix and the plan are sized from the bound the retention
+    puts on the pruned sets; without, for the worst case (half of every image pruned)."""
+    shape = (1024, 409600, 400, 1280, rt.RTP_BF16)
+    rc, worst = rt.rtprune_workspace_bytes(*shape)
+    assert rc == rt.RTP_OK
+    entries = lambda nbytes, base: (nbytes - base) / 12.0
+    rc, none = rt.rtprune_workspace_bytes(*shape, rt.make_params(dynamic=0, ratio=1.0))
+    assert rc == rt.RTP_OK and none < worst
+    # worst case: total * max_tokens / 4 entries of 12 bytes (fp64 kernel matrix, fp32 plan)
+    assert abs(entries(worst, none) - 409600 * (400 / 4 - 1)) < 1000
+    rc, fixed = rt.rtprune_workspace_bytes(*shape, rt.make_params(dynamic=0, ratio=0.84))
+    assert rc == rt.RTP_OK and abs(entries(fixed, none) - 409600 * (65 - 1)) < 1000     # (1 - 0.84) 400 + 1 = 65
+    rc, dyn = rt.rtprune_workspace_bytes(*shape, rt.make_params(dynamic=1, ratio_min=0.9))
+    assert rc == rt.RTP_OK and abs(entries(dyn, none) - 409600 * (41 - 1)) < 1000
+    rc, dyn6 = rt.rtprune_workspace_bytes(*shape, rt.make_params(dynamic=1, ratio_min=0.6))
+    assert rc == rt.RTP_OK and dyn6 == worst                                             # 161 pruned > 400 / 4
+    assert rt.rtprune_workspace_bytes(*shape, rt.make_params(eps=0.0))[0] == rt.RTP_EINVAL
 
 
 def test_profile_filter_names(lib):
@@ -143,6 +157,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert call(b, rt.make_params(ratio=1.5)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(z=float("nan"))) == rt.RTP_EINVAL
     assert call(b, rt.make_params(metric=2)) == rt.RTP_EINVAL
+    assert call(b, rt.make_params(mid_merge_min_images=-1)) == rt.RTP_EINVAL
+    assert call(_fake_batch(B=65536, total_tokens=65536, max_tokens=1), ok) == rt.RTP_EUNSUPPORTED
     assert call(b, rt.make_params(dynamic=1, ratio_min=0.0)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(dynamic=1, phi_lo=0.5, phi_hi=0.5)) == rt.RTP_EINVAL
     assert call(b, rt.make_params(eps=0.001)) == rt.RTP_EUNSUPPORTED       # exp range

@@ -93,7 +93,7 @@ def _log_counts(rep, name):
 
 
 def test_c4_ragged_multi_tile():
-    batch = synth.gen_batch(4)
+    batch = synth.gen_batch_parallel(4)
     assert batch.batch == 128 and batch.max_tokens <= 1156
     f = hz.run_prune(batch)
     assert f["rc"] == 0 and f["status"] == 0
@@ -113,7 +113,7 @@ def test_c4_ragged_multi_tile():
 
 
 def test_c5_full_batch_against_oracle():
-    batch = synth.gen_batch(5)
+    batch = synth.gen_batch_parallel(5)
     assert batch.batch == 1024 and batch.total_tokens == 409600
     f = hz.run_prune(batch)
     assert f["rc"] == 0 and f["status"] == 0
@@ -134,7 +134,7 @@ def test_c9_full_batch_against_oracle():
     """The benchmark's pages at the paper's average retention (Table 2), whole batch: 63 pruned
     tokens per page, enough pages for the matrix-core merge kernel of the middling pruned sets
     to run by default."""
-    batch = synth.gen_batch(9)
+    batch = synth.gen_batch_parallel(9)
     assert batch.batch == 1024 and batch.total_tokens == 409600
     f = hz.run_prune(batch)
     assert f["rc"] == 0 and f["status"] == 0
@@ -359,12 +359,9 @@ def test_unstaged_matrix_core_merge_at_its_edges(counts, ratio, d):
     """Pruned sets of 17 to 64 tokens (the merge kernel that feeds the matrix cores straight
     from memory), at both ends of the range, with kept rows cut by its 32- and 128-row blocks."""
     batch = _clustered(counts, d, "bf16", 29, ratio=ratio, iters=10)
-    before = rt.rtprune_mid_merge_min_images(1)     # by default only batches with hundreds of them run it
-    try:
-        s = hz.run_staged(batch)
-        f = hz.run_prune(batch)
-    finally:
-        rt.rtprune_mid_merge_min_images(before)
+    on = dict(batch.params, mid_merge_min_images=1)   # by default only batches with hundreds of them run it
+    s = hz.run_staged(batch, on)
+    f = hz.run_prune(batch, on)
     rep = hz.compare_batch(batch, s, staged=True)
     _log(rep, f"mid merge {counts} {ratio} D={d}")
     rows = int(s["out_offsets"][-1])

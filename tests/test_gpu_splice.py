@@ -58,8 +58,10 @@ def _run(batch, prefix, poff, suffix, soff, mode, params=None):
 
 @pytest.mark.parametrize("mode", [orc.POSITIONS_CONSECUTIVE, orc.POSITIONS_ORIGINAL])
 @pytest.mark.parametrize("cfg,images", [(3, 5), (4, 4), (1, 1)])
-def test_splice_matches_oracle_and_packed_output(cfg, images, mode):
+def test_splice_matches_oracle_and_packed_output(cfg, images, mode, extra=None):
     batch = synth.gen_batch(cfg, images=range(images))
+    if extra:
+        batch.params.update(extra)
     rng = np.random.default_rng(100 + cfg)
     B, d = batch.batch, batch.tokens.shape[1]
     pc = rng.integers(0, 9, size=B)
@@ -106,11 +108,7 @@ def test_splice_matches_oracle_and_packed_output(cfg, images, mode):
 def test_splice_through_the_merge_kernel_for_middling_pruned_sets():
     """63 pruned tokens per page, the matrix-core merge kernel for 17 to 64 switched on for a
     small batch: it writes into the sequence at each image's visual start like the others."""
-    before = rt.rtprune_mid_merge_min_images(1)
-    try:
-        test_splice_matches_oracle_and_packed_output(9, 3, orc.POSITIONS_ORIGINAL)
-    finally:
-        rt.rtprune_mid_merge_min_images(before)
+    test_splice_matches_oracle_and_packed_output(9, 3, orc.POSITIONS_ORIGINAL, dict(mid_merge_min_images=1))
 
 
 def test_splice_without_text_is_the_packed_output():

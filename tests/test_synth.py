@@ -52,3 +52,14 @@ def test_subset_repacks():
     s = synth.subset(b, [2, 0])
     assert s.batch == 2 and s.images == [2, 0]
     np.testing.assert_array_equal(s.tokens[: s.offsets[1]], b.tokens[b.offsets[2]: b.offsets[3]])
+
+
+def test_parallel_generation_gives_the_same_batch():
+    """Every image is drawn from its own seed, so spreading the drawing over worker
+    processes changes nothing (workload 4: 128 ragged pages)."""
+    a = synth.gen_batch(4)
+    b = synth.gen_batch_parallel(4, workers=3)
+    np.testing.assert_array_equal(a.offsets, b.offsets)
+    np.testing.assert_array_equal(a.tokens, b.tokens)
+    np.testing.assert_array_equal(a.density, b.density)
+    assert a.params == b.params and a.images == b.images
