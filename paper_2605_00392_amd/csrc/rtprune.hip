@@ -43,6 +43,7 @@ struct Layout {
   int chunks_per_image, chunks_per_part, parts_per_image;
   int sweep;            // the batch may hold images beyond the register-resident Sinkhorn shapes
   long long plan_cap;   // entries available in kmat / plan
+  long long plan_stride;   // entries per token of an image's slot when the slots are not packed (plan_slot)
   long long strip_cap;  // entries available in the per-strip arrays
 };
 
@@ -59,9 +60,10 @@ Layout make_layout(int B, long long total, int max_tokens, int D, int rmax) {
   const long long all_chunks = static_cast<long long>(B) * L.chunks_per_image;
   L.chunks_per_part = static_cast<int>(std::min<long long>(L.chunks_per_image, std::max<long long>(1, all_chunks / kNormMinWorkgroups)));
   L.parts_per_image = (L.chunks_per_image + L.chunks_per_part - 1) / L.chunks_per_part;
-  // sum_b M_b R_b <= sum_b N_b^2 / 4 <= total * max_tokens / 4, and <= sum_b N_b rmax
-  L.plan_cap = std::min(total * static_cast<long long>(max_tokens) / 4,
-                        total * static_cast<long long>(std::max(0, std::min(rmax, max_tokens)))) + 1;
+  // M_b R_b <= N_b^2 / 4 <= N_b ceil(max_tokens / 4), and <= N_b rmax: a slot of N_b * plan_stride entries
+  // holds any image's matrix, and total * plan_stride entries hold them all, packed or not
+  L.plan_stride = std::min<long long>((max_tokens + 3) / 4, std::max(0, std::min(rmax, max_tokens)));
+  L.plan_cap = total * L.plan_stride + 1;
   L.status = take(256);
   L.norm64 = take(sizeof(double) * total);
   L.score = take(sizeof(float) * total);
@@ -224,15 +226,18 @@ int launch_prepare(const rtprune_batch* in, int32_t* status, hipStream_t s) {
   return launched();
 }
 
+// `validate`: the kernel's first workgroup validates the ragged layout and writes the
+// status word (the fused calls); otherwise k_prepare has written it.
 template <typename T>
 int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layout& L, void* ws,
-                   float* norms_out, hipStream_t s) {
+                   float* norms_out, bool validate, hipStream_t s) {
   const dim3 grid(L.parts_per_image, in->B), block(kNormThreads);
   const T* tok = static_cast<const T*>(in->tokens);
   double* sq = at<double>(ws, L.norm64);
   float* sc = at<float>(ws, L.score);
   double* part = at<double>(ws, L.partial);
-  const int32_t* st = at<int32_t>(ws, L.status);
+  const NormCheck st{validate ? 1 : 0, in->B, static_cast<long long>(in->total_tokens), in->max_tokens,
+                     at<int32_t>(ws, L.status)};
   ProfScope prof(KID_NORMS, s);
   // groups of four elements per row; the lean variants need every k but the last
   // to be fully populated
@@ -258,11 +263,14 @@ int launch_norms_t(const rtprune_batch* in, int dynamic, int metric, const Layou
 }
 
 int launch_norms(const rtprune_batch* in, int dynamic, int metric, const Layout& L, void* ws,
-                 float* norms_out, hipStream_t s) {
+                 float* norms_out, hipStream_t s, bool validate = false) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
-  return in->dtype == RTP_BF16 ? launch_norms_t<bf16_t>(in, dynamic, metric, L, ws, norms_out, s)
-                               : launch_norms_t<float>(in, dynamic, metric, L, ws, norms_out, s);
+  return in->dtype == RTP_BF16 ? launch_norms_t<bf16_t>(in, dynamic, metric, L, ws, norms_out, validate, s)
+                               : launch_norms_t<float>(in, dynamic, metric, L, ws, norms_out, validate, s);
 }
+
+// The norm pass can stand in for k_prepare when it runs at all.
+bool norms_validate(const rtprune_batch* in) { return in->B > 0 && in->total_tokens > 0; }
 
 int launch_select(const rtprune_batch* in, const DevParams& p, const float* density,
                   const int32_t* keep_in, int do_select, const Layout& L, void* ws, float* phi,
@@ -270,17 +278,15 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
   if (in->B == 0) return RTP_OK;
   ProfScope prof(KID_SELECT, s);
   const size_t lds = 9 * static_cast<size_t>((in->max_tokens + 1) & ~1);   // 8-byte key + flag per token
+  const SelectArgs A{in->offsets, in->D, p, density, keep_in, at<float>(ws, L.score), at<double>(ws, L.partial),
+                     L.parts_per_image, L.chunks_per_part * kNormRowsPerChunk, do_select, in->max_tokens,
+                     phi, ratio, keep_out, sel};
+  const int32_t* st = at<int32_t>(ws, L.status);
   // long images: the rank counting is quadratic in the token count, so the workgroup grows with it
   if (in->max_tokens > 2048)
-    hipLaunchKernelGGL(k_select<1024>, dim3(in->B), dim3(1024), lds, s, in->offsets, in->D, p, density, keep_in,
-                       at<float>(ws, L.score), at<double>(ws, L.partial), L.parts_per_image,
-                       L.chunks_per_part * kNormRowsPerChunk, do_select,
-                       in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+    hipLaunchKernelGGL(k_select<1024>, dim3(in->B), dim3(1024), lds, s, A, st);
   else
-    hipLaunchKernelGGL(k_select<256>, dim3(in->B), dim3(256), lds, s, in->offsets, in->D, p, density, keep_in,
-                       at<float>(ws, L.score), at<double>(ws, L.partial), L.parts_per_image,
-                       L.chunks_per_part * kNormRowsPerChunk, do_select,
-                       in->max_tokens, phi, ratio, keep_out, sel, at<int32_t>(ws, L.status));
+    hipLaunchKernelGGL(k_select<256>, dim3(in->B), dim3(256), lds, s, A, st);
   return launched();
 }
 
@@ -327,7 +333,8 @@ int pruned_bound(const rtprune_batch* in, const DevParams& p, int hint) {
 template <typename T>
 int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* sel,
                     const int32_t* keep, const long long* plan_off, const Layout& L, void* ws,
-                    double* scores_out, int max_pruned_hint, const int32_t* work, hipStream_t s) {
+                    double* scores_out, int max_pruned_hint, const int32_t* work, const ScanJob& job,
+                    hipStream_t s) {
   const T* tok = static_cast<const T*>(in->tokens);
   const double* sq = at<double>(ws, L.norm64);
   double* kmat = at<double>(ws, L.kmat);
@@ -339,9 +346,10 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
     // D = 1024 up; narrower tokens take the fp64 vector kernel.
     if (in->D % 128 == 0 && in->D >= kMfmaMinWidth) {
       // matrix-core path (an image's workgroups on one XCD: B rounded up to eight)
-      const dim3 gs((in->max_tokens + kScoreRows - 1) / kScoreRows, (in->B + 7) / 8 * 8);
-      hipLaunchKernelGGL(k_scores_mfma, gs, dim3(kScoreThreads), 0, s, tok, in->offsets, in->B, in->D, sel, keep,
-                         plan_off, sq, p, kmat, L.plan_cap, scores_out, st);
+      const int tiles_s = (in->max_tokens + kScoreRows - 1) / kScoreRows;
+      const unsigned blocks = static_cast<unsigned>(tiles_s) * ((in->B + 7) / 8 * 8) + (job.on ? 1u : 0u);
+      hipLaunchKernelGGL(k_scores_mfma, dim3(blocks), dim3(kScoreThreads), 0, s, tok, in->offsets, in->B, in->D, sel,
+                         keep, plan_off, sq, p, kmat, L.plan_cap, scores_out, tiles_s, job, st);
       RTP_TRY(launched());
       // images with many pruned tokens: the LDS-tiled kernel.  Largest pruned set
       // the call can produce: the caller's bound, else what the retention clamp allows
@@ -375,9 +383,16 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
   return launched();
 }
 
+// Whether the score pass of a batch runs on the matrix-core kernel, whose launch can
+// carry the fused calls' scan job.
+bool scores_on_matrix_cores(const rtprune_batch* in) {
+  return in->dtype == RTP_BF16 && in->D % 128 == 0 && in->D >= kMfmaMinWidth && in->B > 0 && in->total_tokens > 0;
+}
+
 int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel, const int32_t* keep,
               const long long* plan_off, const Layout& L, void* ws, double* scores_out, float* plan,
-              int32_t* pair, int max_pruned_hint, bool classified, hipStream_t s) {
+              int32_t* pair, int max_pruned_hint, bool classified, hipStream_t s,
+              const ScanJob& job = ScanJob{0, nullptr, nullptr, nullptr, 0, 0}) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
   set_sinkhorn_mode(p, L);
@@ -390,8 +405,8 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     RTP_TRY(launched());
   }
   RTP_TRY(in->dtype == RTP_BF16
-              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, s)
-              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, s));
+              ? launch_scores_t<bf16_t>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, job, s)
+              : launch_scores_t<float>(in, p, sel, keep, plan_off, L, ws, scores_out, max_pruned_hint, work, job, s));
   SinkhornArgs A{in->offsets, keep, plan_off, p, kmat, L.plan_cap, plan, pair};
   {
     ProfScope prof(KID_SINKHORN_REGS, s);
@@ -538,6 +553,33 @@ int launch_merge(const rtprune_batch* in, const DevParams& p, const int32_t* sel
   return in->dtype == RTP_BF16
              ? launch_merge_t<bf16_t>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s)
              : launch_merge_t<float>(in, p, sel, keep, out_off, plan, plan_off, out, max_pruned_hint, status, work, s);
+}
+
+// Stage 1 of the fused calls: [layout check ->] norms (+ phi sums) -> ratio, kept count,
+// selection [-> prefix sums and work lists].  Two launches in the common case (the
+// norm pass checks the layout; the sums and lists are left to the score pass as `job`);
+// the separate kernels otherwise.  `text`: the splice call's text spans, checked
+// between the norm pass and the selection.
+int launch_stage1(const rtprune_batch* in, const DevParams& p, int mode, const float* density, float* ratio,
+                  int32_t* keep, int32_t* sel, int32_t* out_offsets, long long* plan_off, const Layout& L,
+                  void* ws, hipStream_t s, ScanJob* job, const TextSpans* text = nullptr) {
+  int32_t* status = at<int32_t>(ws, L.status);
+  int32_t* work = at<int32_t>(ws, L.work);
+  const bool validate = norms_validate(in);
+  if (!validate) RTP_TRY(launch_prepare(in, status, s));
+  RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, ws, nullptr, s, validate));
+  if (text && in->B > 0) {
+    hipLaunchKernelGGL(k_splice_check, dim3(1), dim3(256), 0, s, *text, in->B, status);
+    RTP_TRY(launched());
+  }
+  RTP_TRY(launch_select(in, p, density, nullptr, 1, L, ws, nullptr, ratio, keep, sel, s));
+  // the prefix sums and work lists: by an extra workgroup of the score pass when that runs
+  // on the matrix-core kernel (`job`), else by a launch of their own
+  if (scores_on_matrix_cores(in)) {
+    *job = ScanJob{1, out_offsets, plan_off, work, mode, L.plan_stride};
+    return RTP_OK;
+  }
+  return launch_scan(in, keep, out_offsets, plan_off, status, s, work, mode);
 }
 
 }  // namespace
@@ -842,16 +884,14 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   int32_t* sel = sel_idx ? sel_idx : at<int32_t>(workspace, L.sel);
   long long* plan_off = at<long long>(workspace, L.plan_off);
   float* plan = at<float>(workspace, L.plan);
-  RTP_TRY(launch_prepare(in, status, s));
-  RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
-  RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
   DevParams pm = p;
   set_sinkhorn_mode(pm, L);
-  RTP_TRY(launch_scan(in, keep, out_offsets, plan_off, status, s, at<int32_t>(workspace, L.work), pm.mode));
+  ScanJob job{0, nullptr, nullptr, nullptr, 0, 0};
+  RTP_TRY(launch_stage1(in, p, pm.mode, density, ratio, keep, sel, out_offsets, plan_off, L, workspace, s, &job));
   // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image
   const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
-  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s, job));
   return launch_merge(in, p, sel, keep, out_offsets, plan, plan_off, out, max_pruned, status,
                       at<int32_t>(workspace, L.work), s);
 }
@@ -891,19 +931,17 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   float* plan = at<float>(workspace, L.plan);
   const TextSpans t{text->prefix, text->prefix_offsets, text->prefix_rows,
                     text->suffix, text->suffix_offsets, text->suffix_rows};
-  RTP_TRY(launch_prepare(in, status, s));
-  if (in->B > 0) hipLaunchKernelGGL(k_splice_check, dim3(1), dim3(256), 0, s, t, in->B, status);
-  RTP_TRY(launched());
-  RTP_TRY(launch_norms(in, p.dynamic, p.metric, L, workspace, nullptr, s));
-  RTP_TRY(launch_select(in, p, density, nullptr, 1, L, workspace, nullptr, ratio, keep, sel, s));
+  // (the text offsets are checked after the norm pass has written the status word and
+  // before the first kernel that writes to the caller's arrays)
   DevParams pm = p;
   set_sinkhorn_mode(pm, L);
-  RTP_TRY(launch_scan(in, keep, nullptr, plan_off, status, s, at<int32_t>(workspace, L.work), pm.mode));
+  ScanJob job{0, nullptr, nullptr, nullptr, 0, 0};
+  RTP_TRY(launch_stage1(in, p, pm.mode, density, ratio, keep, sel, nullptr, plan_off, L, workspace, s, &job, &t));
   hipLaunchKernelGGL(k_splice_scan, dim3(1), dim3(256), 0, s, t, keep, in->B, seq_offsets, visual_start, status);
   RTP_TRY(launched());
   const int max_pruned = p.dynamic ? kPrunedFromClamp
                                    : static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1;
-  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s));
+  RTP_TRY(launch_ot(in, p, sel, keep, plan_off, L, workspace, nullptr, plan, pair, max_pruned, true, s, job));
   // the merge writes image b's kept rows at visual_start[b], between its text spans
   RTP_TRY(launch_merge(in, p, sel, keep, visual_start, plan, plan_off, seq, max_pruned, status,
                        at<int32_t>(workspace, L.work), s));

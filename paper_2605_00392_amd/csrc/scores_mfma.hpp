@@ -27,7 +27,9 @@
 // 4.4 TB/s; 12 % slower on ragged pages with a few dozen, 20 % slower at 63.)
 #pragma once
 #include "common.hpp"
+#include "stage1.hpp"
 #include "sinkhorn_team.hpp"
+#include "sinkhorn_dual.hpp"
 
 namespace rtp {
 
@@ -42,13 +44,36 @@ constexpr int kScoreRows = 128;                      // kept rows per workgroup
 constexpr int kScorePitch = 72;                      // bf16 per LDS row: 64 elements and 16 bytes
 constexpr int kScoreBufElems = (64 + kScoreRows) * kScorePitch;
 
+// What the fused calls ask of one extra workgroup of this launch: the batch-wide
+// prefix sum of the kept counts (where the merge writes each image), the Sinkhorn work
+// lists, and the per-image slots of the kernel matrix and the plan, as an array for the
+// kernels after this one.  Nothing in this launch depends on it: with a job, an image's
+// slot is the closed form plan_slot(offsets, b, stride), which this kernel evaluates for
+// itself.  It takes a launch of its own (k_scan_classify) out of every fused call.
+struct ScanJob {
+  int on;
+  int32_t* out_offsets;        // may be null
+  long long* plan_offsets;
+  int32_t* work;
+  int mode;
+  long long stride;
+};
+
+// Launched over tiles x rows8 workgroups (rows8 = B rounded up to a multiple of eight),
+// plus one when `job.on`.
 __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
     const bf16_t* __restrict__ tokens, const int32_t* __restrict__ offsets, int B, int D,
     const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ keep,
     const long long* __restrict__ plan_offsets, const double* __restrict__ norm64, DevParams p,
-    double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out,
+    double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out, int tiles, ScanJob job,
     const int32_t* __restrict__ status) {
   if (status[0]) return;
+  const unsigned linear = blockIdx.x;
+  if (job.on && linear == gridDim.x - 1) {
+    scan_images(offsets, keep, B, job.out_offsets, job.plan_offsets, job.stride);
+    classify_images(offsets, keep, B, job.work, job.mode);
+    return;
+  }
   __shared__ __align__(16) bf16_t stage[kScoreBufElems];
   // Images are taken last to first: the norm pass before this one walks them first
   // to last and the merge after it does so again, so each pass starts on the
@@ -58,10 +83,10 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   // are dealt to the eight XCDs in turn, so the image's pruned rows, which all its
   // workgroups read, are fetched into one L2 instead of eight (1024 pages with 63
   // pruned tokens each: 2.4 GB fetched from memory without this, against 1.05 GB of
-  // tokens).  The grid's y extent is B rounded up to a multiple of eight for it.
-  const unsigned linear = blockIdx.x + gridDim.x * blockIdx.y, slot = linear >> 3;
-  const int by = static_cast<int>(slot / gridDim.x) * 8 + static_cast<int>(linear & 7);
-  const int bx = static_cast<int>(slot % gridDim.x);
+  // tokens).  The launch covers B rounded up to a multiple of eight for it.
+  const unsigned slot = linear >> 3;
+  const int by = static_cast<int>(slot / tiles) * 8 + static_cast<int>(linear & 7);
+  const int bx = static_cast<int>(slot % tiles);
   if (by >= B) return;
   const int b = B - 1 - by;
   const int lo = offsets[b];
@@ -69,8 +94,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   const int m = min(max(keep[b], 0), n), r = n - m;
   const int i0 = bx * kScoreRows;
   if (r <= 0 || i0 >= m || r > kTiledMinPruned) return;   // (the same for the whole workgroup)
-  if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
-  const long long po = plan_offsets[b];
+  const long long po = job.on ? plan_slot(offsets, b, job.stride) : plan_offsets[b];
+  if (!plan_fits(po, m, r, plan_cap)) return;
   const int k_layout = kernel_layout(p, m, r);
   const int32_t* sel = sel_idx + lo;
   const double inv_eps = 1.0 / p.eps;

@@ -11,8 +11,8 @@ constexpr int kNormRowsPerChunk = 80;   // token rows one workgroup of k_norms c
 constexpr int kNormThreads = 256;
 
 // Validate the ragged layout; every later kernel of the call skips its work
-// when the status word is nonzero.
-__global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ offsets, int B,
+// when the status word is nonzero.  Called by all 256 threads of one workgroup.
+__device__ __forceinline__ void validate_offsets(const int32_t* __restrict__ offsets, int B,
                                                  long long total_tokens, int max_tokens,
                                                  int32_t* __restrict__ status) {
   __shared__ int bad;
@@ -30,8 +30,29 @@ __global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ off
   }
   if (flags) atomicOr(&bad, flags);
   __syncthreads();
-  if (threadIdx.x == 0) status[0] = bad;
+  if (threadIdx.x == 0) {
+    status[0] = bad;
+  }
 }
+
+__global__ __launch_bounds__(256) void k_prepare(const int32_t* __restrict__ offsets, int B,
+                                                 long long total_tokens, int max_tokens,
+                                                 int32_t* __restrict__ status) {
+  validate_offsets(offsets, B, total_tokens, max_tokens, status);
+}
+
+// The fused calls fold the validation into the norm pass, their first kernel: its
+// first workgroup validates the whole layout and writes the status word for the
+// kernels after it, and every workgroup checks its own image's extent before it reads
+// a token (the norm pass writes to the workspace only, so nothing of the caller's is
+// touched before the status word exists).
+struct NormCheck {
+  int on;                  // 0: read the status word k_prepare wrote
+  int B;
+  long long total_tokens;
+  int max_tokens;
+  int32_t* status;
+};
 
 // One wave per token row.  A lane owns the 4-element groups g = lane + 64 k,
 // k < KMAX, of the row (D <= 256 KMAX).  The squared norm is accumulated in
@@ -97,6 +118,43 @@ struct NormRows {
         }
       }
       q[u] = a;
+    }
+    if constexpr (NB == 4 && !VARIANCE) {
+      // The four rows' 64 partial sums each are added up by a reduce-scatter: two
+      // halving exchanges leave lane group u = lane / 16 with row u's partials, four
+      // steps inside the group finish it (7 additions where four butterflies take
+      // 24).  Square root, reciprocal and the stores then run once for the four rows,
+      // each lane group on its own row.  (bf16 products have 16-bit significands, so
+      // their fp64 sums are exact and no order of additions changes a bit; fp32
+      // products round at 1e-16 of the sum, far below the fp32 score's last bit.)
+      const double mine = group_sum<4>(halve16(halve32(q[0], q[2]), halve32(q[1], q[3])));
+      const int u_own = lane >> 4;                       // = 2 (lane / 32) + (lane / 16) % 2
+      const int r_own = rb + kStep * u_own;
+      const double nrm = sqrt(mine);
+      if ((lane & 15) == 0 && r_own < r1) {
+        norm64[lo + r_own] = nrm;
+        score[lo + r_own] = static_cast<float>(mine);
+        if (norms_out) norms_out[lo + r_own] = static_cast<float>(nrm);
+      }
+      if (dynamic) {
+        const double inv = 1.0 / fmax(nrm, kTinyNorm);
+        if (r_own < r1) wsum += mine * inv * inv;        // per lane group; the groups are added at the end
+        const float inv_own = static_cast<float>(inv);
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          if (rb + kStep * u >= r1) break;
+          const float inv32 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, inv_own), 16 * u));
+#pragma unroll
+          for (int k = 0; k < KMAX; ++k) {
+            forget_origin(raw[u][k]);      // widen again rather than keep 80 floats alive
+            float x[4];
+            unpack4(raw[u][k], x);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc32[k][e] = fmaf(x[e], inv32, acc32[k][e]);
+          }
+        }
+      }
+      return;
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) q[u] = wave_sum_dpp(q[u]);
@@ -168,13 +226,19 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
     const T* __restrict__ tokens, const int32_t* __restrict__ offsets, int D, int dynamic,
     double* __restrict__ norm64, float* __restrict__ score, float* __restrict__ norms_out,
     double* __restrict__ partial, int parts_per_image, int chunks_per_part,
-    const int32_t* __restrict__ status) {
-  if (status[0]) return;
+    NormCheck check) {
   // a workgroup takes `chunks_per_part` consecutive chunks of kNormRowsPerChunk rows
   // of its image and writes one partial vector for all of them
   const int b = blockIdx.y, part = blockIdx.x;
+  if (check.on) {
+    if (b == 0 && part == 0) validate_offsets(offsets, check.B, check.total_tokens, check.max_tokens, check.status);
+  } else if (check.status[0]) {
+    return;
+  }
   const int lo = offsets[b];
   const int n = offsets[b + 1] - lo;
+  if (check.on && (lo < 0 || n < 0 || n > check.max_tokens || static_cast<long long>(lo) + n > check.total_tokens))
+    return;
   if (part * chunks_per_part * kNormRowsPerChunk >= n) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ngroups = D >> 2;
@@ -248,6 +312,8 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
   // (now idle) vector buffer
   __syncthreads();
   double* lds_w = reinterpret_cast<double*>(&lds[0][0]);
+  if (NB == 4 && !VARIANCE)   // each group of 16 lanes has counted its own rows
+    wsum = read_lane(wsum, 0) + read_lane(wsum, 16) + read_lane(wsum, 32) + read_lane(wsum, 48);
   if (lane == 0) lds_w[wave] = wsum;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -270,14 +336,37 @@ __global__ __launch_bounds__(kNormThreads) void k_norms(
 // threshold is found by radix passes (measured: faster from a few hundred tokens on).
 constexpr int kRankCountMaxTokens = 128;
 
+struct SelectArgs {
+  const int32_t* offsets;
+  int D;
+  DevParams p;
+  const float* density;
+  const int32_t* keep_in;
+  const float* score;
+  const double* partial;
+  int parts_per_image, rows_per_part, do_select, max_tokens;
+  float* phi_out;
+  float* ratio_out;
+  int32_t* keep_out;
+  int32_t* sel_idx;
+};
+
+// Image blockIdx.x on a workgroup of NT threads.
 template <int NT>
-__global__ __launch_bounds__(NT) void k_select(
-    const int32_t* __restrict__ offsets, int D, DevParams p, const float* __restrict__ density,
-    const int32_t* __restrict__ keep_in, const float* __restrict__ score,
-    const double* __restrict__ partial, int parts_per_image, int rows_per_part, int do_select, int max_tokens,
-    float* __restrict__ phi_out, float* __restrict__ ratio_out, int32_t* __restrict__ keep_out,
-    int32_t* __restrict__ sel_idx, const int32_t* __restrict__ status) {
-  if (status[0]) return;
+__device__ __forceinline__ void select_image(const SelectArgs& A) {
+  const int32_t* __restrict__ offsets = A.offsets;
+  const int D = A.D;
+  const DevParams& p = A.p;
+  const float* __restrict__ density = A.density;
+  const int32_t* __restrict__ keep_in = A.keep_in;
+  const float* __restrict__ score = A.score;
+  const double* __restrict__ partial = A.partial;
+  const int parts_per_image = A.parts_per_image, rows_per_part = A.rows_per_part, do_select = A.do_select,
+            max_tokens = A.max_tokens;
+  float* __restrict__ phi_out = A.phi_out;
+  float* __restrict__ ratio_out = A.ratio_out;
+  int32_t* __restrict__ keep_out = A.keep_out;
+  int32_t* __restrict__ sel_idx = A.sel_idx;
   // dynamic LDS: 8-byte keys for n_pad = 2 * ceil(max_tokens / 2) tokens, then one flag byte each
   extern __shared__ __attribute__((aligned(16))) unsigned char select_lds[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(select_lds);
@@ -424,12 +513,24 @@ __global__ __launch_bounds__(NT) void k_select(
   }
 }
 
+template <int NT>
+__global__ __launch_bounds__(NT) void k_select(SelectArgs A, const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  select_image<NT>(A);
+}
+
 // Exclusive prefix sums over the images: out_offsets = scan(M_b) (int32),
 // plan_offsets = scan(M_b * R_b) (int64).  One workgroup of 256 threads.
+// `plan_stride` > 0 (the fused calls): plan_offsets[b] = offsets[b] * plan_stride
+// instead, a slot of N_b * plan_stride >= M_b R_b entries per image that needs no
+// sum over the other images (see plan_slot).
+__device__ __forceinline__ long long plan_slot(const int32_t* __restrict__ offsets, int b, long long plan_stride) {
+  return static_cast<long long>(offsets[b]) * plan_stride;
+}
 __device__ __forceinline__ void scan_images(const int32_t* __restrict__ offsets,
                                             const int32_t* __restrict__ keep, int B,
                                             int32_t* __restrict__ out_offsets,
-                                            long long* __restrict__ plan_offsets) {
+                                            long long* __restrict__ plan_offsets, long long plan_stride = 0) {
   __shared__ long long sm[256];
   __shared__ long long sp[256];
   const int tid = threadIdx.x;
@@ -455,7 +556,7 @@ __device__ __forceinline__ void scan_images(const int32_t* __restrict__ offsets,
   long long am = sm[tid] - cm, ap = sp[tid] - cp;
   for (int b = b0; b < b1; ++b) {
     if (out_offsets) out_offsets[b] = static_cast<int32_t>(am);
-    if (plan_offsets) plan_offsets[b] = ap;
+    if (plan_offsets) plan_offsets[b] = plan_stride > 0 ? plan_slot(offsets, b, plan_stride) : ap;
     const long long m = keep[b];
     const long long n = offsets[b + 1] - offsets[b];
     am += m;
@@ -463,7 +564,7 @@ __device__ __forceinline__ void scan_images(const int32_t* __restrict__ offsets,
   }
   if (tid == 255) {
     if (out_offsets) out_offsets[B] = static_cast<int32_t>(sm[255]);
-    if (plan_offsets) plan_offsets[B] = sp[255];
+    if (plan_offsets) plan_offsets[B] = plan_stride > 0 ? plan_slot(offsets, B, plan_stride) : sp[255];
   }
 }
 
