@@ -227,6 +227,32 @@ int rtprune_prune(const rtprune_batch* in, const float* density,
                   float* ratio, void* workspace, size_t workspace_bytes,
                   void* stream);
 
+/* rtprune_prune for callers that cannot allocate device memory or carry a
+ * workspace with them: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  It is rtprune_prune with the workspace
+ * taken from a fixed array of RTPRUNE_STATIC_SCRATCH_BYTES inside the
+ * library's device image (each GPU the library runs on holds one copy until
+ * the process ends); same kernels, same results, bit for bit.  The call
+ * allocates and frees nothing (with the measurement aid below switched off);
+ * the first call on a device looks up the array's address on that device and
+ * is best made before a capture starts.
+ *   - A batch fits when rtprune_workspace_bytes(..., params, &n) gives
+ *     n <= RTPRUNE_STATIC_SCRATCH_BYTES (e.g. 64 images of 400 tokens, width
+ *     1280, at any retention); a larger one is refused with RTP_EWORKSPACE and
+ *     nothing is enqueued.
+ *   - The status word of device-visible errors lives in the array, where the
+ *     caller cannot read it: after such an error out_offsets (and every other
+ *     output) is left untouched, so a caller that wants to detect one presets
+ *     out_offsets[B] to -1.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time
+ *     on the same GPU (different streams, different threads) race and give
+ *     wrong results; calls on one stream, or ordered by events, are fine. */
+#define RTPRUNE_STATIC_SCRATCH_BYTES (64u << 20)
+int rtprune_prune_static(const rtprune_batch* in, const float* density,
+                         const rtprune_params* params, void* out, int32_t* out_offsets,
+                         int32_t* keep_counts, int32_t* sel_idx, int32_t* pair,
+                         float* ratio, void* stream);
+
 /* Text embeddings around each image of a batch, for rtprune_prune_splice.  All
  * rows have the batch's dtype and width D.  A side with no rows anywhere may
  * have NULL pointers and 0 rows. */

@@ -896,6 +896,50 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
                       at<int32_t>(workspace, L.work), s);
 }
 
+// ---- rtprune_prune without a caller's workspace --------------------------------
+// The workspace of this variant is a fixed array in the library's device image (one
+// copy per GPU, held until the process ends).  In host code the array's name only
+// stands for the symbol; its device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[RTPRUNE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once known
+
+// The current device's copy of `scratch`.
+int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTP_EHIP;
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RTP_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return RTP_OK;
+}
+}  // namespace
+
+extern "C" int rtprune_prune_static(const rtprune_batch* in, const float* density,
+                                    const rtprune_params* params, void* out, int32_t* out_offsets,
+                                    int32_t* keep_counts, int32_t* sel_idx, int32_t* pair, float* ratio,
+                                    void* stream) {
+  // sizes first: a batch beyond the array is refused before anything touches the device
+  RTP_TRY(check_batch(in));
+  DevParams p;
+  RTP_TRY(check_params(params, &p));
+  const Layout L = make_layout(in->B, in->total_tokens, in->max_tokens, in->D, params_pruned_bound(p, in->max_tokens));
+  if (L.total > static_cast<size_t>(RTPRUNE_STATIC_SCRATCH_BYTES)) return RTP_EWORKSPACE;
+  void* ws = nullptr;
+  RTP_TRY(static_scratch(&ws));
+  // every kernel of the call writes what it later reads, so the array's old content
+  // (the previous call's) needs no clearing
+  return rtprune_prune(in, density, params, out, out_offsets, keep_counts, sel_idx, pair, ratio, ws,
+                       static_cast<size_t>(RTPRUNE_STATIC_SCRATCH_BYTES), stream);
+}
+
 extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* density,
                                     const rtprune_params* params, const rtprune_text_spans* text,
                                     int32_t position_mode, void* seq, int64_t seq_capacity_rows,

@@ -26,8 +26,9 @@ EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",
     "rtprune_norms_topk", "rtprune_ot_pair", "rtprune_merge", "rtprune_prune", "rtprune_prune_splice",
     "rtprune_profile_enable", "rtprune_profile_summary", "rtprune_profile_only", "rtprune_copy_bytes",
-    "rtprune_text_density_workspace_bytes", "rtprune_text_density",
+    "rtprune_text_density_workspace_bytes", "rtprune_text_density", "rtprune_prune_static",
 )
+RTPRUNE_STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class RtpruneError(RuntimeError):
@@ -92,6 +93,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rtprune_prune_splice.restype = ctypes.c_int
     lib.rtprune_prune_splice.argtypes = [pb, vp, pp, ctypes.POINTER(rtprune_text_spans), i32, vp, ctypes.c_int64,
                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.rtprune_prune_static.restype = ctypes.c_int
+    lib.rtprune_prune_static.argtypes = [pb, vp, pp, vp, vp, vp, vp, vp, vp, vp]
     lib.rtprune_profile_enable.restype = ctypes.c_int
     lib.rtprune_profile_enable.argtypes = [ctypes.c_int]
     lib.rtprune_profile_only.restype = ctypes.c_int
@@ -256,6 +259,14 @@ def rtprune_prune_splice(batch: DeviceBatch, density, params: rtprune_params, te
         _addr(seq), int(seq_capacity_rows), _addr(seq_offsets), _addr(position_ids), _addr(keep_counts),
         _addr(sel_idx), _addr(pair), _addr(ratio), _addr(workspace),
         workspace.numel() if workspace is not None else 0, _stream(stream))
+
+
+def rtprune_prune_static(batch: DeviceBatch, density, params: rtprune_params, out, out_offsets,
+                         keep_counts, sel_idx, pair, ratio, stream=None) -> int:
+    d = batch.desc()
+    return load_library().rtprune_prune_static(
+        ctypes.byref(d), _addr(density), ctypes.byref(params), _addr(out), _addr(out_offsets),
+        _addr(keep_counts), _addr(sel_idx), _addr(pair), _addr(ratio), _stream(stream))
 
 
 def rtprune_profile_enable(on: int) -> int:

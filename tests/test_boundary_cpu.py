@@ -106,6 +106,26 @@ def test_workspace_bytes_follow_the_parameters(lib):
     assert rt.rtprune_workspace_bytes(*shape, rt.make_params(eps=0.0))[0] == rt.RTP_EINVAL
 
 
+def test_static_scratch_variant_refuses_what_does_not_fit(lib):
+    """rtprune_prune_static checks the batch against its fixed array before anything touches a
+    device: a batch that needs more than the array is refused (and so are bad arguments)."""
+    ok = rt.make_params(dynamic=0, ratio=0.84)
+    call = lambda batch, p=ok: rt.rtprune_prune_static(batch, 0x3000, p, 0x4000, 0x5000, None, None, None, None,
+                                                       stream=0)
+    big = _fake_batch(B=1024, total_tokens=409600, max_tokens=400)
+    rc, need = rt.rtprune_workspace_bytes(1024, 409600, 400, 1280, rt.RTP_BF16, ok)
+    assert rc == rt.RTP_OK and need > rt.RTPRUNE_STATIC_SCRATCH_BYTES
+    assert call(big) == rt.RTP_EWORKSPACE
+    rc, need = rt.rtprune_workspace_bytes(64, 25600, 400, 1280, rt.RTP_BF16, rt.make_params(dynamic=1))
+    assert rc == rt.RTP_OK and need <= rt.RTPRUNE_STATIC_SCRATCH_BYTES       # the header's example fits
+    assert call(_fake_batch(B=-1)) == rt.RTP_EINVAL
+    assert call(_fake_batch(D=1290)) == rt.RTP_EUNSUPPORTED
+    assert call(_fake_batch(), rt.make_params(eps=0.0)) == rt.RTP_EINVAL
+    text = open(os.path.join(ROOT, "include", "rtprune.h")).read()
+    m = re.search(r"#define\s+RTPRUNE_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert m and (int(m.group(1)) << int(m.group(2))) == rt.RTPRUNE_STATIC_SCRATCH_BYTES
+
+
 def test_profile_filter_names(lib):
     """The measurement aid takes the names the summary reports, and nothing else."""
     assert rt.rtprune_profile_only("k_merge") == rt.RTP_OK
