@@ -38,6 +38,34 @@ def generate(cfg: int, workers: int):
     return synth.gen_batch_parallel(cfg, max(1, min(workers, 16, (os.cpu_count() or 1))))
 
 
+def _oracle_worker(job):
+    """One worker of the all-cores oracle timing: draws its images (untimed), then times the
+    single-threaded oracle over them.  Runs in a fresh process; touches no GPU."""
+    cfg, images = job
+    from threadpoolctl import threadpool_limits
+    from oracle import rtprune_oracle as orc
+    from paper_2605_00392_amd import synth
+    sub = synth.gen_batch(cfg, images=images)
+    op = orc.Params.from_dict(sub.params)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        orc.prune_batch(sub.tokens, sub.dtype, sub.offsets, sub.density, op)
+        return len(images), time.perf_counter() - t0
+
+
+def oracle_fanout(cfg: int, k: int, workers: int):
+    """The oracle on the first ``k`` images of a workload, one single-threaded worker process per
+    host core (at most 16), each on its share of the images: images/s = k / the slowest worker's time."""
+    import multiprocessing as mp
+    workers = max(1, min(workers, k))
+    shares = [list(range(i, k, workers)) for i in range(workers)]
+    with mp.get_context("spawn").Pool(workers) as pool:
+        done = pool.map(_oracle_worker, [(cfg, sh) for sh in shares])
+    slowest = max(t for _, t in done)
+    return dict(value=round(sum(n for n, _ in done) / slowest, 3), unit="images/s", cores=workers,
+                sample=f"the same {k} images dealt to {workers} single-threaded worker processes, slowest {slowest:.2f} s")
+
+
 def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, iters: int,
                 eps: float = 0.05, z: float = 0.2):
     """Algorithmic work of one launch of a kernel over the batch: (bound, amount, unit, peak).
@@ -47,11 +75,6 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
     """
     r = n - m
     tok_bytes = float(n.sum()) * d * elt
-    # images beyond the register-resident Sinkhorn shapes, when the batch may hold any
-    # (more than 512 tokens): their kernel matrix is streamed once per iteration, in
-    # fp32 when exp's range allows
-    big = ((m + 1 > 512) | (r > 64)) & (r > 0) & (r <= 2048) if n.max(initial=0) > 512 else np.zeros(len(n), bool)
-    kbytes = 4.0 if (max(1.0, z) - min(-1.0, z)) / eps <= 80.0 else 8.0
     if kernel == "k_norms":
         # every token row read once; 4-byte score + 8-byte squared norm written
         return "hbm", tok_bytes + 12.0 * n.sum(), "GB/s", HBM_PEAK_GBS
@@ -97,14 +120,25 @@ def kernel_work(kernel: str, n: np.ndarray, m: np.ndarray, d: int, elt: int, ite
                 return "hbm", nbytes, "GB/s", HBM_PEAK_GBS
             return "mfma", flops, "TFLOP/s", BF16_MFMA_TFLOPS
         return "alu", flops, "TFLOP/s", FP64_VECTOR_TFLOPS
-    if kernel == "k_sinkhorn" and big.any():
-        # sweep kernels: the kernel matrix read once per iteration (it does not fit on chip)
-        return "hbm", kbytes * iters * float((m * r)[big].sum()), "GB/s", HBM_PEAK_GBS
     if kernel in ("k_sinkhorn", "k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn_tall"):
-        # register-resident or single-workgroup kernels: two sweeps of multiply-adds over
-        # the augmented matrix per iteration (counted over the whole batch)
+        # Sinkhorn is arithmetic on the augmented matrix wherever that matrix lives: two sweeps
+        # of multiply-adds per iteration, counted over the whole batch and priced against the
+        # fp64 vector peak.  (What the multi-workgroup kernels of the large pages stream from
+        # memory per iteration is reported beside it, as `streamed`, not as the roofline.)
         return "alu", 2.0 * 2.0 * iters * float(((m + 1) * (r + 1)).sum()), "TFLOP/s", FP64_VECTOR_TFLOPS
     return "hbm", 0.0, "GB/s", HBM_PEAK_GBS
+
+
+def sinkhorn_streamed_bytes(n: np.ndarray, m: np.ndarray, iters: int, eps: float, z: float) -> float:
+    """Bytes the multi-workgroup Sinkhorn kernels read per call: images beyond the
+    register-resident shapes (batches with images above 512 tokens only) have their kernel
+    matrix streamed once per iteration, in fp32 when exp's range allows."""
+    r = n - m
+    if n.max(initial=0) <= 512:
+        return 0.0
+    big = ((m + 1 > 512) | (r > 64)) & (r > 0) & (r <= 2048)
+    kbytes = 4.0 if (max(1.0, z) - min(-1.0, z)) / eps <= 80.0 else 8.0
+    return kbytes * iters * float((m * r)[big].sum())
 
 
 def bench_density(rt, torch, steps: int, unique: int = 16, copies: int = 16):
@@ -151,34 +185,37 @@ def bench_density(rt, torch, steps: int, unique: int = 16, copies: int = 16):
     assert all(got[i] == want[i] for i in range(len(want))), "text density differs from the oracle"
     return {"pages": B, "page": f"{side}x{side}x3 u8", "ms_per_call": round(ms, 4),
             "pages_per_s": round(B / (ms * 1e-3), 1),
-            "kernel": "k_density_sobel (register-window variant for 64-pixel patches)", "kernel_ms": None if sobel is None else round(sobel, 4),
+            "kernel": "k_density_rows (timed under the name k_density_sobel, which covers both density kernels)", "kernel_ms": None if sobel is None else round(sobel, 4),
             "bound": "hbm", "achieved_GBs": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9, 1),
             "peak_GBs": HBM_PEAK_GBS,
             "frac": None if sobel is None else round(B * per / (sobel * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "cpu_oracle_pages_per_s": round(len(want) / (c1 - c0), 2), "bit_exact_vs_oracle": True}
 
 
-def bench_large_pages(rt, torch, synth, steps: int, cfg: int = 8, batch=None):
-    """Time the fused call on a side workload: by default the largest page size of the
-    paper's other OCR models (Table 6: 4512 -> 2783 tokens), the shapes whose Sinkhorn
-    matrix does not fit a workgroup and whose similarity product is a real GEMM."""
+def bench_side(rt, torch, synth, steps: int, cfg: int, batch=None, rooflines: bool = True):
+    """Time the fused call on another workload: the other benchmark workloads (1-4), the
+    largest page size of the paper's other OCR models (Table 6: 4512 -> 2783 tokens, the
+    shapes whose Sinkhorn matrix does not fit a workgroup and whose similarity product is a
+    real GEMM), the benchmark's pages at the paper's own retention."""
     if batch is None:
         batch = synth.gen_batch(cfg)
     w = synth.WORKLOADS[cfg]
     dev = "cuda:0"
     p = rt.make_params(batch.params)
     db = rt.upload(batch, dev)
-    ws = rt.alloc_workspace(db)
+    ws = rt.alloc_workspace(db, p)
     B, total, D = db.B, db.total_tokens, db.D
     out = torch.empty((total, D), dtype=db.tokens.dtype, device=dev)
     out_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
     keep = torch.empty(B, dtype=torch.int32, device=dev)
     pair = torch.empty(total, dtype=torch.int32, device=dev)
+    dens = torch.from_numpy(np.ascontiguousarray(batch.density, dtype=np.float32)).to(dev)
 
     def step():
-        rt.check(rt.rtprune_prune(db, None, p, out, out_off, keep, None, pair, None, ws))
+        rt.check(rt.rtprune_prune(db, dens, p, out, out_off, keep, None, pair, None, ws))
 
-    step()
+    for _ in range(2):
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for _ in range(steps):
@@ -196,18 +233,29 @@ def bench_large_pages(rt, torch, synth, steps: int, cfg: int = 8, batch=None):
     kernels = {r_["kernel"]: r_["total_ms"] / max(1, r_["launches"]) for r_ in prof}
     n_h = np.diff(batch.offsets).astype(np.int64)
     keep_h = keep.cpu().numpy().astype(np.int64)
-    roof = {}
-    for k_ in ("k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn", "k_scores", "k_merge"):
-        if kernels.get(k_, 0.0) < 0.02 * ms:      # a kernel that has nothing to do on this workload
-            continue
-        bound, amount, unit, peak = kernel_work(k_, n_h, keep_h, D, 2, int(batch.params["iters"]),
-                                                float(batch.params["eps"]), float(batch.params["z"]))
-        ach = amount / (kernels[k_] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
-        roof[k_] = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
-    return dict(workload=w.name, images=B, total_tokens=int(total), kept_tokens=int(keep_h.sum()),
-                ms_per_step=round(ms, 3), images_per_s=round(B / (ms * 1e-3), 1),
-                tokens_per_s=round(total / (ms * 1e-3), 1),
-                kernels_ms={k_: round(v, 4) for k_, v in kernels.items()}, roofline=roof)
+    elt = 2 if batch.dtype == "bf16" else 4
+    iters, eps, z = int(batch.params["iters"]), float(batch.params["eps"]), float(batch.params["z"])
+    res = dict(workload=w.name, images=B, total_tokens=int(total), kept_tokens=int(keep_h.sum()),
+               ms_per_step=round(ms, 4), images_per_s=round(B / (ms * 1e-3), 1),
+               tokens_per_s=round(total / (ms * 1e-3), 1),
+               step_hbm_floor_frac=round((float(n_h.sum()) + float(keep_h.sum())) * D * elt
+                                         / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+               kernels_ms={k_: round(v, 4) for k_, v in kernels.items()})
+    if rooflines:
+        roof = {}
+        for k_ in ("k_norms", "k_sinkhorn_regs", "k_sinkhorn_c32", "k_sinkhorn_tall", "k_sinkhorn", "k_scores", "k_merge"):
+            if kernels.get(k_, 0.0) < 0.02 * ms:      # a kernel that has nothing to do on this workload
+                continue
+            bound, amount, unit, peak = kernel_work(k_, n_h, keep_h, D, elt, iters, eps, z)
+            ach = amount / (kernels[k_] * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+            roof[k_] = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
+            if k_ == "k_sinkhorn":
+                streamed = sinkhorn_streamed_bytes(n_h, keep_h, iters, eps, z)
+                if streamed > 0:
+                    roof[k_]["streamed"] = dict(bytes_per_call=streamed, unit="GB/s",
+                                                rate=round(streamed / (kernels[k_] * 1e-3) / 1e9, 1))
+        res["roofline"] = roof
+    return res
 
 
 def main() -> int:
@@ -216,10 +264,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=5, help="synthetic workload 1..9 (5 = 1024 x 400 tokens, the default; 6-8 = 1083/2137/4512-token pages; 9 = workload 5's pages at retention 337/400)")
-    ap.add_argument("--cpu-images", type=int, default=192, help="images the CPU oracle is timed on")
+    ap.add_argument("--cpu-images", type=int, default=384, help="images the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lib", default=None, help="path of an alternative build of librtprune.so")
     ap.add_argument("--no-density", action="store_true", help="skip the textual-density side measurement")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the side measurements on benchmark workloads 1-4")
     ap.add_argument("--no-large-pages", action="store_true",
                     help="skip the side measurement on 4512-token pages")
     ap.add_argument("--gen-workers", type=int, default=16,
@@ -238,6 +288,9 @@ def main() -> int:
     side9 = None
     if not args.no_large_pages and args.workload == 5:
         side9 = generate(9, args.gen_workers)              # the paper-retention side workload, likewise
+    others_h = {}
+    if not args.no_other_workloads and args.workload == 5:
+        others_h = {c: generate(c, args.gen_workers) for c in (1, 2, 3, 4)}
     gen_s = time.time() - t0
 
     import torch
@@ -252,7 +305,7 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     p = rt.make_params(batch.params)
     db = rt.upload(batch, dev)
-    ws = rt.alloc_workspace(db)
+    ws = rt.alloc_workspace(db, p)               # sized for these parameters
     B, total, D = db.B, db.total_tokens, db.D
     out = torch.empty((total, D), dtype=db.tokens.dtype, device=dev)
     out_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
@@ -347,26 +400,27 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import rtprune_oracle as orc
         from tests import harness
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-        except Exception:
-            cores = 1
+        from threadpoolctl import threadpool_limits
         k = min(args.cpu_images, B)
         sub = synth.subset(batch, list(range(k)))
         op = orc.Params.from_dict(batch.params)
-        c0 = time.perf_counter()
-        res = orc.prune_batch(sub.tokens, sub.dtype, sub.offsets, sub.density, op)
-        c1 = time.perf_counter()
-        # the timed oracle results double as a parity check of the timed device outputs
+        # primary number: the oracle as it stands on ONE thread (numpy's BLAS capped for the timed block)
+        with threadpool_limits(limits=1):
+            c0 = time.perf_counter()
+            res = orc.prune_batch(sub.tokens, sub.dtype, sub.offsets, sub.density, op)
+            c1 = time.perf_counter()
+        del res
+        # the timed device outputs are checked against the oracle on a spread of the same images
         gpu = dict(keep=keep_h, out_offsets=out_off.cpu().numpy(), sel=sel.cpu().numpy(),
                    pair=pair.cpu().numpy(), ratio=ratio.cpu().numpy(), out=harness._np(out))
         rep = harness.compare_batch(batch, gpu, images=list(range(0, k, max(1, k // 24))))
-        cpu = dict(value=round(k / (c1 - c0), 3), unit="images/s", cores=int(cores), kind="oracle",
-                   sample=f"first {k} images of {w.name}, float64 numpy oracle, {c1 - c0:.2f} s",
+        # secondary: the same single-threaded function, the images dealt to one worker process per host core
+        fan = oracle_fanout(args.workload, k, harness.host_workers())
+        cpu = dict(value=round(k / (c1 - c0), 3), unit="images/s", cores=1, kind="oracle",
+                   sample=f"first {k} images of {w.name}, float64 numpy oracle on one thread, {c1 - c0:.2f} s",
+                   all_cores=fan, host_cpu_count=os.cpu_count(),
                    parity_checked_images=rep.images,
                    near_ties=rep.selection_near_ties + rep.pairing_near_ties)
-        del res
 
     density = None
     if not args.no_density:
@@ -374,14 +428,22 @@ def main() -> int:
         torch.cuda.empty_cache()
         density = bench_density(rt, torch, max(3, args.steps // 2))
 
+    # the other four benchmark workloads: a few steps each, outside the headline's timed region
+    other = None
+    if not args.no_other_workloads and args.workload == 5:
+        other = {}
+        for cfg_o in (1, 2, 3, 4):
+            other[f"c{cfg_o}"] = bench_side(rt, torch, synth, 10, cfg_o, batch=others_h.get(cfg_o), rooflines=False)
+            torch.cuda.empty_cache()
+
     large = paper_ret = None
     if not args.no_large_pages and args.workload == 5:
         del db
         torch.cuda.empty_cache()
-        large = bench_large_pages(rt, torch, synth, 3)
+        large = bench_side(rt, torch, synth, 3, 8)
         torch.cuda.empty_cache()
         # the benchmark's pages at the paper's own average retention (337 of 400 kept)
-        paper_ret = bench_large_pages(rt, torch, synth, 5, cfg=9, batch=side9)
+        paper_ret = bench_side(rt, torch, synth, 5, 9, batch=side9)
 
     line = {
         "metric": "images/s pruned (fused rtprune_prune, 400-token 1280-d bf16 pages)",
@@ -403,6 +465,7 @@ def main() -> int:
         "step_hbm_floor_frac": round(step_hbm_frac, 5),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "other_workloads": other,
         "text_density": density,
         "large_pages": large,
         "paper_retention_pages": paper_ret,

@@ -68,13 +68,15 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
     double* __restrict__ kmat, long long plan_cap, double* __restrict__ scores_out, int tiles, ScanJob job,
     const int32_t* __restrict__ status) {
   if (status[0]) return;
+  __shared__ __align__(16) bf16_t stage[kScoreBufElems];
   const unsigned linear = blockIdx.x;
   if (job.on && linear == gridDim.x - 1) {
-    scan_images(offsets, keep, B, job.out_offsets, job.plan_offsets, job.stride);
-    classify_images(offsets, keep, B, job.work, job.mode);
+    static_assert(kClassifyLdsBytes <= sizeof(stage) && kScanLdsBytes <= sizeof(stage), "the job works in the stage buffer");
+    scan_images(offsets, keep, B, job.out_offsets, job.plan_offsets, stage, job.stride);
+    __syncthreads();
+    classify_images(offsets, keep, B, job.work, job.mode, stage);
     return;
   }
-  __shared__ __align__(16) bf16_t stage[kScoreBufElems];
   // Images are taken last to first: the norm pass before this one walks them first
   // to last and the merge after it does so again, so each pass starts on the
   // images its predecessor touched last, which are the ones the memory-side cache

@@ -351,11 +351,12 @@ __device__ __forceinline__ void sinkhorn_dual48_image(const SinkhornArgs& A, int
 // Work lists for the register-resident kernels: `work` holds kWorkLists counts
 // (one per shape, indexed by variant id) followed by as many lists of B image
 // indices each.  One workgroup; list order follows image order.
+constexpr int kClassifyLdsBytes = kWorkLists * 256 * 4;   // LDS classify_images works in
 __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offsets,
                                                 const int32_t* __restrict__ keep, int B,
-                                                int32_t* __restrict__ work, int mode) {
+                                                int32_t* __restrict__ work, int mode, void* lds) {
   constexpr int NV = kWorkLists;
-  __shared__ int cnt[NV][256];
+  int (*cnt)[256] = static_cast<int (*)[256]>(lds);   // [NV][256]
   const int tid = threadIdx.x;
   const int span = (B + 255) / 256;
   const int b0 = min(B, tid * span), b1 = min(B, b0 + span);
@@ -411,7 +412,8 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ of
                                                   int32_t* __restrict__ work, int mode,
                                                   const int32_t* __restrict__ status) {
   if (status[0]) return;
-  classify_images(offsets, keep, B, work, mode);
+  __shared__ __align__(16) unsigned char lds[kClassifyLdsBytes];
+  classify_images(offsets, keep, B, work, mode, lds);
 }
 
 // Both of the above in one launch, for the fused calls.
@@ -422,8 +424,11 @@ __global__ __launch_bounds__(256) void k_scan_classify(const int32_t* __restrict
                                                        int32_t* __restrict__ work, int mode,
                                                        const int32_t* __restrict__ status) {
   if (status[0]) return;
-  scan_images(offsets, keep, B, out_offsets, plan_offsets);
-  classify_images(offsets, keep, B, work, mode);
+  __shared__ __align__(16) unsigned char lds[kClassifyLdsBytes];   // (the two run one after the other)
+  static_assert(kScanLdsBytes <= kClassifyLdsBytes, "shared work area");
+  scan_images(offsets, keep, B, out_offsets, plan_offsets, lds);
+  __syncthreads();
+  classify_images(offsets, keep, B, work, mode, lds);
 }
 
 // All register-resident Sinkhorn work of a batch in one launch.  Workgroups are

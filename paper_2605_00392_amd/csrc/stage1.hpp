@@ -527,12 +527,14 @@ __global__ __launch_bounds__(NT) void k_select(SelectArgs A, const int32_t* __re
 __device__ __forceinline__ long long plan_slot(const int32_t* __restrict__ offsets, int b, long long plan_stride) {
   return static_cast<long long>(offsets[b]) * plan_stride;
 }
+constexpr int kScanLdsBytes = 2 * 256 * 8;   // LDS scan_images works in
 __device__ __forceinline__ void scan_images(const int32_t* __restrict__ offsets,
                                             const int32_t* __restrict__ keep, int B,
                                             int32_t* __restrict__ out_offsets,
-                                            long long* __restrict__ plan_offsets, long long plan_stride = 0) {
-  __shared__ long long sm[256];
-  __shared__ long long sp[256];
+                                            long long* __restrict__ plan_offsets, void* lds,
+                                            long long plan_stride = 0) {
+  long long* sm = static_cast<long long*>(lds);   // [256]
+  long long* sp = sm + 256;                       // [256]
   const int tid = threadIdx.x;
   const int span = (B + 255) / 256;
   const int b0 = min(B, tid * span), b1 = min(B, b0 + span);
@@ -574,7 +576,8 @@ __global__ __launch_bounds__(256) void k_scan(const int32_t* __restrict__ offset
                                               long long* __restrict__ plan_offsets,
                                               const int32_t* __restrict__ status) {
   if (status[0]) return;
-  scan_images(offsets, keep, B, out_offsets, plan_offsets);
+  __shared__ __align__(16) unsigned char lds[kScanLdsBytes];
+  scan_images(offsets, keep, B, out_offsets, plan_offsets, lds);
 }
 
 }  // namespace rtp

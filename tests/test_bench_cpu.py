@@ -31,9 +31,23 @@ def test_algorithmic_work_per_kernel():
     big_n, big_m = np.array([4512], dtype=np.int64), np.array([2783], dtype=np.int64)
     bound, amount, unit, peak = bench.kernel_work("k_merge", big_n, big_m, 1280, 2, 100)
     assert (bound, unit, peak) == ("mfma", "TFLOP/s", 2500.0) and amount == 2.0 * 2783 * 1729 * 1280
-    # multi-workgroup Sinkhorn: the fp32 kernel matrix once per iteration
-    bound, amount, unit, _ = bench.kernel_work("k_sinkhorn", big_n, big_m, 1280, 2, 100, 0.05, 0.2)
-    assert (bound, unit) == ("hbm", "GB/s") and amount == 4.0 * 100 * 2783 * 1729
-    # a temperature whose exp range exceeds fp32 keeps the matrix in fp64
-    _, amount64, _, _ = bench.kernel_work("k_sinkhorn", big_n, big_m, 1280, 2, 100, 0.02, 0.2)
-    assert amount64 == 2 * amount
+    # Sinkhorn is priced as fp64 vector work on every workload: two sweeps of multiply-adds
+    # over the augmented matrix per iteration ...
+    bound, amount, unit, peak = bench.kernel_work("k_sinkhorn", big_n, big_m, 1280, 2, 100, 0.05, 0.2)
+    assert (bound, unit, peak) == ("alu", "TFLOP/s", 78.6) and amount == 4.0 * 100 * 2784 * 1730
+    bound, amount, unit, _ = bench.kernel_work("k_sinkhorn_regs", n, m, 1280, 2, 100)
+    assert (bound, unit) == ("alu", "TFLOP/s") and amount == 4.0 * 100 * (391 * 11 + 401 * 1)
+    # ... and what the multi-workgroup kernels stream per call is a figure beside it: the fp32
+    # kernel matrix once per iteration, fp64 when exp's range exceeds fp32, nothing when every
+    # image fits a register-resident shape
+    assert bench.sinkhorn_streamed_bytes(big_n, big_m, 100, 0.05, 0.2) == 4.0 * 100 * 2783 * 1729
+    assert bench.sinkhorn_streamed_bytes(big_n, big_m, 100, 0.02, 0.2) == 8.0 * 100 * 2783 * 1729
+    assert bench.sinkhorn_streamed_bytes(n, m, 100, 0.05, 0.2) == 0.0
+
+
+def test_oracle_fanout_counts_every_image():
+    """The all-cores oracle timing deals the images to worker processes and reports images/s."""
+    sys.path.insert(0, ROOT)
+    import bench
+    fan = bench.oracle_fanout(2, 6, 3)
+    assert fan["cores"] == 3 and fan["unit"] == "images/s" and fan["value"] > 0
