@@ -68,8 +68,14 @@ enum {
   RTP_DEV_OK = 0,
   RTP_DEV_BAD_OFFSETS = 1,   /* offsets not monotone / offsets[0] != 0 / offsets[B] != total_tokens */
   RTP_DEV_IMAGE_TOO_LONG = 2, /* some image has more than max_tokens tokens */
-  RTP_DEV_BAD_IMAGE = 4       /* rtprune_text_density: a page's size is negative, above the stated
+  RTP_DEV_BAD_IMAGE = 4,      /* rtprune_text_density: a page's size is negative, above the stated
                                  maximum, not a multiple of the patch size, or overruns its pixel span */
+  RTP_DEV_SYNC_TIMEOUT = 8    /* the Sinkhorn kernel that spreads a tall image over several workgroups gave
+                                 up waiting for one of them (they must all be resident at once: only a GPU
+                                 kept busy for seconds by other work can cause it); the images it serves
+                                 - in batches with images above 512 tokens, those with 17 to 128 pruned
+                                 tokens that no one-workgroup shape holds - have no valid plan, pairing
+                                 or merged rows in this call's outputs */
 };
 
 /* Importance score of stage 1.  The method uses the l2 norm (Eq. 1); the

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <atomic>
 #include <mutex>
@@ -20,6 +21,7 @@
 #include "sinkhorn_team.hpp"
 #include "sinkhorn_dual.hpp"
 #include "sinkhorn_sweep.hpp"
+#include "sinkhorn_cluster.hpp"
 #include "scores_mfma.hpp"
 #include "scores_tiled.hpp"
 #include "merge_lds.hpp"
@@ -40,6 +42,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t status, norm64, score, partial, phi, ratio, keep, out_off, plan_off, sel, work, kmat, plan, total;
   size_t sw_x, sw_y, sw_colpart, sw_xpart, sw_ysum, sw_ydust, sw_bestv, sw_besti;   // sweep Sinkhorn state
+  size_t cluster_part;   // exchange buffers of the multi-workgroup Sinkhorn kernel
   int chunks_per_image, chunks_per_part, parts_per_image;
   int sweep;            // the batch may hold images beyond the register-resident Sinkhorn shapes
   long long plan_cap;   // entries available in kmat / plan
@@ -74,7 +77,7 @@ Layout make_layout(int B, long long total, int max_tokens, int D, int rmax) {
   L.out_off = take(sizeof(int32_t) * (B + 1));
   L.plan_off = take(sizeof(long long) * (B + 1));
   L.sel = take(sizeof(int32_t) * total);
-  L.work = take(sizeof(int32_t) * kWorkLists * (1 + static_cast<size_t>(B)));
+  L.work = take(sizeof(int32_t) * (kWorkLists * (1 + static_cast<size_t>(B)) + kWorkSyncWords));
   L.kmat = take(sizeof(double) * L.plan_cap);
   L.plan = take(sizeof(float) * L.plan_cap);
   // more than 512 tokens: an image can have more kept tokens than any register shape holds
@@ -89,8 +92,10 @@ Layout make_layout(int B, long long total, int max_tokens, int D, int rmax) {
     L.sw_ydust = take(sizeof(double) * 2 * B);
     L.sw_bestv = take(sizeof(float) * L.strip_cap);
     L.sw_besti = take(sizeof(int32_t) * L.strip_cap);
+    L.cluster_part = take(sizeof(double) * kClusterPartDoubles);
   } else {
     L.sw_x = L.sw_y = L.sw_colpart = L.sw_xpart = L.sw_ysum = L.sw_ydust = L.sw_bestv = L.sw_besti = 0;
+    L.cluster_part = 0;
   }
   L.total = at;
   return L;
@@ -290,13 +295,42 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
   return launched();
 }
 
+// Cluster slots per XCD of the multi-workgroup Sinkhorn kernel on this device: a slot is
+// kClusterMaxGroups compute units of one XCD (eight XCDs assumed; 0: too few compute units).
+int cluster_slots_per_xcd() { return std::min(kClusterMaxSlots / 8, compute_units() / 8 / kClusterMaxGroups); }
+
+// Polls a workgroup of that kernel spends on one wait before it gives up (each a few hundred
+// cycles: the default is seconds).  RTPRUNE_SYNC_SPIN_LIMIT overrides it, for tests of the
+// give-up path.
+int cluster_spin_limit() {
+  if (const char* e = std::getenv("RTPRUNE_SYNC_SPIN_LIMIT")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v > 0 && v < 0x7fffffffL) return static_cast<int>(v);
+  }
+  return 20 * 1000 * 1000;
+}
+
 // Which Sinkhorn kernels a call on this batch launches, and whether the sweep
 // kernels' matrices are stored in fp32 (only batches that may hold images beyond
 // the 512-row register shapes have any).
-void set_sinkhorn_mode(DevParams& p, const Layout& L) {
+void set_sinkhorn_mode(DevParams& p, const Layout& L, const rtprune_batch* in) {
   const int f32 = p.k32 ? kModeF32 : 0;   // exp's range fits fp32: registers may hold the matrix as fp32
-  p.k32 = p.k32 && L.sweep;               // and the sweep kernels' copy in memory is fp32
-  p.mode = (L.sweep ? kModeLarge : 0) | f32;
+  // the multi-workgroup kernel that keeps a matrix on chip runs one workgroup per compute
+  // unit, in clusters of eight per XCD
+  const int cluster = (L.sweep && f32 && cluster_slots_per_xcd() > 0) ? kModeCluster : 0;
+  // The streaming kernels cost two launches per iteration whether or not an image needs them,
+  // and only the device knows the sizes, so they are issued when the batch's shape and the
+  // parameters say that images beyond the on-chip kernels are to be expected: a fixed
+  // retention that prunes more than 128 of the longest image's tokens, or images with more
+  // kept rows than a cluster holds.  Under a dynamic retention (pages prune 2 to 12 % of their
+  // tokens; the clamp at 0.6 is a bound, not the rule) they are not: an image that does end
+  // up beyond the on-chip kernels takes the one-workgroup general kernel, which is right and
+  // slow.  Only the batch's shape and the parameters enter, so that the staged calls choose
+  // the same kernels as the fused ones.
+  const bool many_pruned = !p.dynamic && static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1 > kClusterCols;
+  const int sweep = (L.sweep && (!cluster || many_pruned || in->max_tokens - 1 > kClusterRows)) ? kModeSweep : 0;
+  p.k32 = p.k32 && sweep;                 // the sweep kernels' copy in memory is fp32
+  p.mode = (L.sweep ? kModeLarge : 0) | f32 | cluster | sweep;
 }
 
 // `work` non-null: the same launch also builds the Sinkhorn work lists.
@@ -395,7 +429,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
               const ScanJob& job = ScanJob{0, nullptr, nullptr, nullptr, 0, 0}) {
   if (in->B == 0 || in->total_tokens == 0) return RTP_OK;
   DevParams p = p_in;
-  set_sinkhorn_mode(p, L);
+  set_sinkhorn_mode(p, L, in);
   const double* kmat = at<double>(ws, L.kmat);
   const int32_t* st = at<int32_t>(ws, L.status);
   int32_t* work = at<int32_t>(ws, L.work);
@@ -420,8 +454,15 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
                        in->B, st);
   }
   if (p.mode & kModeLarge) {
+    // the tall one-workgroup shapes and, before them in the same launch, the clusters of
+    // workgroups (one per compute unit of the slots in use: all resident together, which their
+    // waits rely on)
+    const int spx = (p.mode & kModeCluster) ? cluster_slots_per_xcd() : 0;
+    const int cluster_blocks = 8 * spx * kClusterMaxGroups;
+    const ClusterArgs CA{A, work, in->B, work + kWorkLists * (1 + static_cast<size_t>(in->B)),
+                         at<double>(ws, L.cluster_part), spx, cluster_spin_limit(), at<int32_t>(ws, L.status)};
     ProfScope prof(KID_SINKHORN_TALL, s);
-    hipLaunchKernelGGL(k_sinkhorn_tall, dim3(in->B), dim3(kDualThreads), 0, s, A, work, in->B, st);
+    hipLaunchKernelGGL(k_sinkhorn_large, dim3(cluster_blocks + in->B), dim3(kClusterThreads), 0, s, CA, cluster_blocks);
   }
   RTP_TRY(launched());
   // The general kernel takes what no shape above does.  With the fp32-held shapes
@@ -436,7 +477,7 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
                        L.plan_cap, plan, pair, 1, p.mode, st);
     RTP_TRY(launched());
   }
-  if (p.mode & kModeLarge) {
+  if (p.mode & kModeSweep) {
     // large images: two launches per iteration over all of them, then plan and pairing
     SweepArgs SA{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
                 at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<void>(ws, L.sw_colpart),
@@ -885,7 +926,7 @@ extern "C" int rtprune_prune(const rtprune_batch* in, const float* density,
   long long* plan_off = at<long long>(workspace, L.plan_off);
   float* plan = at<float>(workspace, L.plan);
   DevParams pm = p;
-  set_sinkhorn_mode(pm, L);
+  set_sinkhorn_mode(pm, L, in);
   ScanJob job{0, nullptr, nullptr, nullptr, 0, 0};
   RTP_TRY(launch_stage1(in, p, pm.mode, density, ratio, keep, sel, out_offsets, plan_off, L, workspace, s, &job));
   // fixed retention: R <= N - ceil(ratio N - 1e-3) <= (1 - ratio) N + 1 for every image
@@ -978,7 +1019,7 @@ extern "C" int rtprune_prune_splice(const rtprune_batch* in, const float* densit
   // (the text offsets are checked after the norm pass has written the status word and
   // before the first kernel that writes to the caller's arrays)
   DevParams pm = p;
-  set_sinkhorn_mode(pm, L);
+  set_sinkhorn_mode(pm, L, in);
   ScanJob job{0, nullptr, nullptr, nullptr, 0, 0};
   RTP_TRY(launch_stage1(in, p, pm.mode, density, ratio, keep, sel, nullptr, plan_off, L, workspace, s, &job, &t));
   hipLaunchKernelGGL(k_splice_scan, dim3(1), dim3(256), 0, s, t, keep, in->B, seq_offsets, visual_start, status);

@@ -1,0 +1,350 @@
+// Sinkhorn (Appendix C) for images with more kept rows than one workgroup's
+// registers hold and at most 128 pruned tokens (tiled pages pruned harder than
+// most): the kernel matrix stays on chip for all T iterations, spread over a small
+// cluster of workgroups.
+//
+// A cluster is G <= 8 workgroups; workgroup `rank` holds rows 448 rank .. 448 rank +
+// 447 of the kept x pruned kernel matrix as fp32 in its registers (the 448 x 128
+// shape of the one-workgroup kernel: 512 threads as 32 row slots x 16 column slots,
+// 14 x 8 entries per thread, widened at each use; all sums and both scalings fp64).
+// An iteration is one pass over a workgroup's rows - a row's x as soon as its sum is
+// known, then its share of every column sum - followed by the only exchange there
+// is: each workgroup publishes its 128 + 1 partial sums (columns, and the sum of its
+// x), the cluster meets at a barrier, and every workgroup adds the G partials in
+// rank order, which gives all of them the same y bit for bit.  So the matrix is read
+// from memory once per call instead of once per iteration, and an iteration costs a
+// few microseconds of barrier instead of two kernel launches.
+//
+// The barrier.  The workgroups of all clusters are resident together: the kernel is
+// launched with one workgroup per compute unit and no more (each needs a CU's whole
+// register file), and a cluster slot works through its share of the image list with
+// all its workgroups in step.  A slot's workgroups have linear ids of one residue
+// modulo eight, so they share an XCD and its L2.  The exchanged values and the
+// arrival counter are device-scope atomics with relaxed ordering; a workgroup waits
+// for its own stores to complete (a workgroup-scope release: no cache write-back)
+// before one thread counts it in.  Measured: 3.5 to 4.3 us per barrier with eight
+// workgroups, against 6 to 17 us with device-scope fences, whose cache write-backs
+// queue up behind each other.  Every wait is bounded: a workgroup that has polled
+// `spin_limit` times without seeing its cluster complete sets the give-up word, on
+// which all workgroups leave, and RTP_DEV_SYNC_TIMEOUT in the status word.
+#pragma once
+#include "common.hpp"
+#include "sinkhorn_team.hpp"
+#include "sinkhorn_dual.hpp"
+
+namespace rtp {
+
+constexpr int kClusterMaxGroups = 8;                       // workgroups per cluster
+constexpr int kClusterThreads = 512;
+using ClusterShape = TeamWideA;                            // 448 rows x 128 columns per workgroup
+constexpr int kClusterMaxM = kClusterMaxGroups * ClusterShape::kMaxM;   // 3584 kept rows
+constexpr int kClusterMaxR = ClusterShape::kMaxR;
+constexpr int kClusterPart = ClusterShape::TC * (ClusterShape::CPT + 1);   // values a workgroup publishes: 144
+constexpr int kClusterMaxSlots = 64;                       // cluster slots of a launch (8 per XCD)
+// synchronisation words, after the work lists: one arrival counter per slot, then the give-up word
+constexpr int kClusterSyncWords = kClusterMaxSlots + 1;
+static_assert(kClusterSyncWords == kWorkSyncWords, "the list builder zeroes these words");
+static_assert(kClusterMaxM == kClusterRows && kClusterMaxR == kClusterCols, "the shape sinkhorn_variant assumes");
+constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxSlots) * 4 * kClusterMaxGroups * kClusterPart;
+
+struct ClusterArgs {
+  SinkhornArgs S;
+  const int32_t* work;      // work lists (kVariantCluster)
+  int B;
+  int32_t* sync;            // [kClusterSyncWords], zeroed by the kernel that built the lists
+  double* part;             // [slots][4][kClusterMaxGroups][kClusterPart] exchange buffers: two for the sums
+                            // (by iteration parity), two for the pairing keys (by the slot's image parity)
+  int slots_per_xcd;        // launch: 8 XCDs x slots_per_xcd slots x kClusterMaxGroups workgroups
+  int spin_limit;
+  int32_t* status;
+};
+
+// Cluster-wide meeting of the `groups` workgroups of a slot.  `arrived` is the count the slot's
+// counter must reach (every workgroup keeps the same running total).  False: gave up.
+__device__ __forceinline__ bool cluster_meet(int32_t* counter, int32_t* gave_up, int arrived, int spin_limit,
+                                             int32_t* status, int* s_flag) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's published values have completed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int ok = 0;
+    for (int spin = 0; spin < spin_limit; ++spin) {
+      if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= arrived) { ok = 1; break; }
+      if (__hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+      __builtin_amdgcn_s_sleep(2);
+    }
+    if (!ok) {
+      __hip_atomic_store(gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      atomicOr(status, RTP_DEV_SYNC_TIMEOUT);
+    }
+    *s_flag = ok;
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// One image on the `groups` workgroups of a slot; this workgroup is `rank` < groups.  Every
+// workgroup of the cluster takes the same path through the barriers.  `arrived` carries the
+// slot's running arrival count.  False: a wait was given up, leave the kernel.
+__device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int b, int rank, int groups,
+                                                       int32_t* counter, double* part, int& arrived, int seq) {
+  typedef ClusterShape S;
+  constexpr int TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T, LOG_TC = S::LOG_TC, W = S::W;
+  static_assert(T == kClusterThreads, "workgroup shape");
+  const SinkhornArgs& A = C.S;
+  const DevParams& p = A.p;
+  const int tt = threadIdx.x, tw = tt >> 6, lane = tt & 63;
+  const int lo = A.offsets[b];
+  const int n = A.offsets[b + 1] - lo;
+  const int m = min(max(A.keep[b], 0), n), r = n - m;        // (the list holds images with n > 0, r > 0 only)
+  const long long po = A.plan_offsets[b];
+  const double* __restrict__ Kg = A.kmat + po;
+  float* __restrict__ plan_out = A.plan_out;
+  int32_t* __restrict__ pair_out = A.pair_out;
+  int32_t* gave_up = C.sync + kClusterMaxSlots;
+  const int row_base = rank * S::kMaxM;                      // this workgroup's first row
+  const int m_loc = min(max(m - row_base, 0), S::kMaxM);     // rows it holds (>= 1: groups = ceil(m / 448))
+  if (pair_out)
+    for (int i = tt; i < m_loc; i += T) pair_out[lo + row_base + i] = row_base + i;
+
+  const int cslot = tt & (TC - 1);
+  const int rslot = tt >> LOG_TC;
+
+  __shared__ double xw[W][TC][CPT + 1];
+  __shared__ double xtot[TC][CPT + 1];
+  __shared__ double xs[TR][RPT];
+  __shared__ float pv[W][TC][CPT];
+  __shared__ int pi[W][TC][CPT];
+  __shared__ int s_flag;
+
+  // the matrix: unconditional loads from clamped positions, four rows at a time, narrowed
+  // before the next four are requested
+  float K[RPT][CPT];
+#pragma unroll
+  for (int a0 = 0; a0 < RPT; a0 += 4) {
+    double v[4][CPT];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = row_base + min(rslot + TR * (a0 + u), m_loc - 1);
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * r + min(cslot + TC * c, r - 1)];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+        if (a0 + u < RPT) {
+          float k = (rslot + TR * (a0 + u) < m_loc && cslot + TC * c < r) ? static_cast<float>(v[u][c]) : 0.f;
+          forget_origin(k);
+          K[a0 + u][c] = k;
+        }
+  }
+
+  const double kz = exp((p.z - p.shift) / p.eps);
+  double y[CPT];
+  const double x_init = exp(p.shift / p.eps);      // T = 0 leaves u = 0
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) y[c] = (cslot + TC * c < r) ? 1.0 : 0.0;
+  double x_dust = x_init, y_dust = 1.0;
+  double sum_y = static_cast<double>(r) + 1.0;
+  if (cslot == 0) {
+#pragma unroll
+    for (int a = 0; a < RPT; ++a) xs[rslot][a] = (rslot + TR * a < m_loc) ? x_init : 0.0;   // what T = 0 leaves
+  }
+
+  for (int it = 0; it < p.iters; ++it) {
+    double t[CPT + 1];
+    const double row_dust = kz * y_dust;
+#pragma unroll
+    for (int c = 0; c <= CPT; ++c) t[c] = 0.0;
+#pragma unroll
+    for (int a = 0; a < RPT; ++a) {
+      if (TR * a >= m_loc) {                 // no row of this pass exists (the same for every thread)
+        xs[rslot][a] = 0.0;
+        continue;
+      }
+      double kd[CPT];
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        forget_origin(K[a][c]);
+        kd[c] = static_cast<double>(K[a][c]);
+      }
+      double acc = 0.0;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) acc = fma(kd[c], y[c], acc);
+      acc = group_sum<LOG_TC>(acc);
+      const double xa = (rslot + TR * a < m_loc) ? rcp64(acc + row_dust) : 0.0;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) t[c] = fma(kd[c], xa, t[c]);
+      t[CPT] += xa;
+      xs[rslot][a] = xa;
+      if (a % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    x_dust = static_cast<double>(r) * rcp64(kz * sum_y);
+    // this workgroup's column sums: over the row slots of a wave by lane exchanges, over its waves in LDS
+#pragma unroll
+    for (int c = 0; c <= CPT; ++c) t[c] = cross_sum<LOG_TC>(t[c]);
+    if (lane < TC) {
+#pragma unroll
+      for (int c = 0; c <= CPT; ++c) xw[tw][lane][c] = t[c];
+    }
+    __syncthreads();
+    // ... published, and after the cluster has met, every workgroup's sums added in rank order
+    double* mine = part + ((it & 1) * kClusterMaxGroups + rank) * kClusterPart;
+    if (tt < kClusterPart) {
+      const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
+      double acc = 0.0;
+#pragma unroll
+      for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
+      __hip_atomic_store(mine + tt, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    arrived += groups;
+    if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
+    if (tt < kClusterPart) {
+      const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
+      const double* all = part + (it & 1) * kClusterMaxGroups * kClusterPart + tt;
+      double acc = 0.0;
+      for (int g = 0; g < groups; ++g)
+        acc += __hip_atomic_load(all + g * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      xtot[cs][c] = acc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c <= CPT; ++c) t[c] = xtot[cslot][c];
+    const double col_dust = kz * x_dust;
+    double ly = 0.0;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      y[c] = (cslot + TC * c < r) ? rcp64(t[c] + col_dust) : 0.0;
+      ly += y[c];
+    }
+    y_dust = static_cast<double>(m) * rcp64(kz * (t[CPT] + x_dust));
+    ly = group_sum<LOG_TC>(ly);
+    sum_y = ly + y_dust;
+  }
+  __syncthreads();                                     // xs as the last pass left it (or as set up, T = 0)
+
+  // ---- plan and this workgroup's best partner per column ----
+  float bv[CPT];
+  int bi[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) { bv[c] = -1.f; bi[c] = 0x7fffffff; }
+  float* P = plan_out ? plan_out + po : nullptr;
+  int rslot_p = rslot, cslot_p = cslot;
+  forget_origin(rslot_p);
+  forget_origin(cslot_p);
+#pragma unroll
+  for (int a = 0; a < RPT; ++a) {
+    const int il = rslot_p + TR * a;
+    const double xa = xs[rslot][a];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = cslot_p + TC * c;
+      if (il < m_loc && j < r) {
+        const float v = static_cast<float>(xa * static_cast<double>(K[a][c]) * y[c]);
+        if (P) P[static_cast<long long>(row_base + il) * r + j] = v;
+        if (v > bv[c]) { bv[c] = v; bi[c] = row_base + il; }
+      }
+    }
+  }
+  // each workgroup's best per column goes out as a key (value bits, then the lower row), like
+  // the sums; after one more meeting the first workgroup picks the cluster's best and sets it
+  // against the dustbin row.  (The cluster meets here even when no pairing is asked for: it
+  // keeps a fast workgroup's next image out of the buffers a slow one is still reading.)
+  long long* mine = reinterpret_cast<long long*>(part + ((2 + (seq & 1)) * kClusterMaxGroups + rank) * kClusterPart);
+  if (pair_out) {
+#pragma unroll
+    for (int mask = TC; mask < kWave; mask <<= 1)
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const float ov = __shfl_xor(bv[c], mask, kWave);
+        const int oi = __shfl_xor(bi[c], mask, kWave);
+        if (ov > bv[c] || (ov == bv[c] && oi < bi[c])) { bv[c] = ov; bi[c] = oi; }
+      }
+    if (lane < TC) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) { pv[tw][lane][c] = bv[c]; pi[tw][lane][c] = bi[c]; }
+    }
+    __syncthreads();
+    if (tt < TC) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+          const float ov = pv[w][tt][c];
+          const int oi = pi[w][tt][c];
+          if (ov > bv[c] || (ov == bv[c] && oi < bi[c])) { bv[c] = ov; bi[c] = oi; }
+        }
+        // plan entries are >= 0, so their bit patterns order like their values; "no row" (-1) is below all
+        const long long key = (static_cast<long long>(__float_as_int(bv[c])) << 32) | static_cast<unsigned>(0x7fffffff - bi[c]);
+        __hip_atomic_store(mine + tt * CPT + c, key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  arrived += groups;
+  if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
+  if (pair_out && rank == 0 && tt < TC) {
+    const long long* all = reinterpret_cast<const long long*>(part + (2 + (seq & 1)) * kClusterMaxGroups * kClusterPart);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = cslot + TC * c;
+      if (j < r) {
+        long long best = __hip_atomic_load(all + tt * CPT + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int g = 1; g < groups; ++g) {
+          const long long k = __hip_atomic_load(all + g * kClusterPart + tt * CPT + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          best = k > best ? k : best;
+        }
+        const float v = __int_as_float(static_cast<int>(best >> 32));
+        const int i = 0x7fffffff - static_cast<int>(best);
+        const float dust = static_cast<float>(x_dust * kz * y[c]);
+        pair_out[lo + m + j] = dust > v ? -1 : i;
+      }
+    }
+  }
+  return true;
+}
+
+// Workgroup `block` of the cluster part of the launch: 8 XCDs x slots_per_xcd slots x
+// kClusterMaxGroups workgroups; slot s takes images s, s + slots, ... of the list.
+__device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int block) {
+  const int x = block & 7, local = block >> 3;
+  const int slot_in_xcd = local / kClusterMaxGroups, rank = local % kClusterMaxGroups;
+  if (slot_in_xcd >= C.slots_per_xcd) return;
+  const int slots = 8 * C.slots_per_xcd, slot = x * C.slots_per_xcd + slot_in_xcd;
+  int32_t* counter = C.sync + slot;
+  double* part = C.part + static_cast<size_t>(slot) * 4 * kClusterMaxGroups * kClusterPart;
+  const SinkhornArgs& A = C.S;
+  const int count = C.work[kVariantCluster];
+  int arrived = 0, seq = 0;
+  for (int k = slot; k < count; k += slots, ++seq) {
+    const int b = C.work[kWorkLists + kVariantCluster * C.B + k];
+    const int n = A.offsets[b + 1] - A.offsets[b];
+    const int m = min(max(A.keep[b], 0), max(n, 0)), r = max(n, 0) - m;
+    // (every workgroup of the slot takes the same decisions: they read the same words)
+    if (m <= 0 || r <= 0 || sinkhorn_variant(m, r, A.p.mode) != kVariantCluster) continue;
+    if (!plan_fits(A.plan_offsets[b], m, r, A.plan_cap)) continue;
+    const int groups = (m + ClusterShape::kMaxM - 1) / ClusterShape::kMaxM;
+    if (rank < groups) {
+      if (!sinkhorn_cluster_image(C, b, rank, groups, counter, part, arrived, seq)) return;
+    } else {
+      arrived += groups * (A.p.iters + 1);             // what the meetings it stays out of add to the count
+    }
+  }
+}
+
+// The Sinkhorn work of a batch with large images that one launch can hold beside
+// k_sinkhorn_regs: first the cluster workgroups (`cluster_blocks` of them, one per
+// compute unit of the slots in use; lowest ids, so they are handed out first and are
+// resident together whatever follows), then the tall shapes, one image per
+// workgroup.  The two kinds of image are independent, so a few clustered images'
+// barrier-bound iterations run beside the tall ones instead of after them.
+__global__ __launch_bounds__(kClusterThreads) void k_sinkhorn_large(ClusterArgs C, int cluster_blocks) {
+  static_assert(kClusterThreads == kDualThreads, "one workgroup shape for both parts");
+  if (C.status[0]) return;
+  const int blk = blockIdx.x;
+  if (blk < cluster_blocks) sinkhorn_cluster_block(C, blk);
+  else sinkhorn_tall_block(C.S, C.work, C.B, blk - cluster_blocks);
+}
+
+}  // namespace rtp

@@ -405,6 +405,8 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
 #pragma unroll
     for (int v = 0; v < NV; ++v) work[v] = cnt[v][255];
   }
+  // the cluster kernel's arrival counters and give-up word start at zero
+  if (tid < kWorkSyncWords) work[NV * (1 + B) + tid] = 0;
 }
 
 __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,
@@ -499,15 +501,11 @@ __global__ __launch_bounds__(kDualThreads) void k_sinkhorn_regs(SinkhornArgs A,
 }
 
 // The tall shapes (more than 512 rows), one image per workgroup, the longer-running
-// role first.  Launched only for batches that can hold such images.  A kernel of
-// its own so that its LDS and registers do not count against the kernel above.
-__global__ __launch_bounds__(kDualThreads) void k_sinkhorn_tall(SinkhornArgs A,
-                                                               const int32_t* __restrict__ work, int B,
-                                                               const int32_t* __restrict__ status) {
-  if (status[0]) return;
+// role first: workgroup `blk` of that part of k_sinkhorn_large's launch (sinkhorn_cluster.hpp).
+__device__ __forceinline__ void sinkhorn_tall_block(const SinkhornArgs& A, const int32_t* __restrict__ work, int B,
+                                                    int blk) {
   constexpr int NV = kWorkLists;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int blk = blockIdx.x;
   int cnt = work[kVariantTeamTall];
   if (blk < cnt) {
     const int img = work[NV + kVariantTeamTall * B + blk];

@@ -108,15 +108,23 @@ constexpr int kSinkhornBlockWaves = 8;   // waves of a k_sinkhorn_regs workgroup
 constexpr int kDualRows = 512, kDualCols = 32;
 constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3, kVariantC = 4,
               kVariantPair = 5, kVariantSweep = 6, kVariantTall = 7, kVariantTeamTall = 8, kVariantWideA = 9,
-              kVariantWideB = 10, kVariantWideC = 11, kVariantC32 = 12, kGeneralVariant = 13;
+              kVariantWideB = 10, kVariantWideC = 11, kVariantC32 = 12, kVariantCluster = 13, kGeneralVariant = 14;
 // The work lists k_classify builds: one per register-resident shape above, and
 // one of the images whose scores and merge go to the tiled matrix-core kernels.
-constexpr int kListTiled = 13, kListMid = 14, kWorkLists = 15;
+constexpr int kListTiled = 14, kListMid = 15, kWorkLists = 16;
+// after the lists: synchronisation words of the multi-workgroup Sinkhorn kernel (arrival counters
+// of its cluster slots, a give-up word), zeroed by whoever builds the lists
+constexpr int kWorkSyncWords = 65;
 // What a call launches besides the 512-row register shapes, as the kernels
 // receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
 // tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the
 // kernel matrix's range fits fp32 (the shapes that hold it as fp32 may be used).
-constexpr int kModeLarge = 1, kModeF32 = 2;
+// kModeCluster: the device has compute units enough for the multi-workgroup kernel that keeps
+// taller matrices on chip (sinkhorn_cluster.hpp).
+// kModeSweep: the launches of the streaming multi-workgroup kernels (sinkhorn_sweep.hpp) are issued.
+constexpr int kModeLarge = 1, kModeF32 = 2, kModeCluster = 4, kModeSweep = 8;
+// (that kernel's shape: up to eight workgroups of 448 rows, at most 128 pruned tokens)
+constexpr int kClusterRows = 8 * 448, kClusterCols = 128;
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
 // pruned tokens.
 constexpr int kSweepMaxPruned = 2048;
@@ -129,10 +137,14 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
   if ((mode & kModeLarge) && TallShape::fits(m, r)) return kVariantTall;
   if ((mode & kModeLarge) && (mode & kModeF32) && TeamTall::fits(m, r)) return kVariantTeamTall;
+  // at most 128 pruned tokens and rows beyond the shapes above: a cluster of workgroups (one, for
+  // up to 448 rows) that keeps the matrix on chip
+  if ((mode & kModeLarge) && (mode & kModeF32) && (mode & kModeCluster) && m <= kClusterRows && r <= kClusterCols)
+    return kVariantCluster;
   // when the sweep kernels run anyway (their launches are paid for) they also
   // take the images of the slowest register shapes, which otherwise set the
   // duration of the register-resident launch
-  if ((mode & kModeLarge) && r <= kSweepMaxPruned) return kVariantSweep;
+  if ((mode & kModeSweep) && r <= kSweepMaxPruned) return kVariantSweep;
   if (m + 1 <= kDualRows && r + 1 <= 48) return kVariantDual48;
   if (TeamB::fits(m, r)) return kVariantB;
   if ((mode & kModeF32) && TeamC32::fits(m, r)) return kVariantC32;

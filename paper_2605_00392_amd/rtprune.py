@@ -20,7 +20,7 @@ RTP_OK, RTP_EINVAL, RTP_EUNSUPPORTED, RTP_EWORKSPACE, RTP_EHIP = range(5)
 RTP_F32, RTP_BF16 = 0, 1
 RTP_METRIC_L2NORM, RTP_METRIC_VARIANCE = 0, 1
 RTP_POSITIONS_CONSECUTIVE, RTP_POSITIONS_ORIGINAL = 0, 1
-RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE = 1, 2, 4
+RTP_DEV_BAD_OFFSETS, RTP_DEV_IMAGE_TOO_LONG, RTP_DEV_BAD_IMAGE, RTP_DEV_SYNC_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = (
     "rtprune_status_string", "rtprune_workspace_bytes", "rtprune_dynamic_ratio",

@@ -220,6 +220,61 @@ def test_tall_register_shapes_at_their_edges():
     assert rep.max_score_abs <= hz.SCORE_ATOL
 
 
+@pytest.mark.parametrize("override", [dict(), dict(iters=0), dict(iters=1), dict(iters=7), dict(eps=0.02),
+                                      dict(eps=1.0, z=1.0, alpha=0.4)])
+def test_multi_workgroup_resident_sinkhorn_at_its_edges(override):
+    """At most 128 pruned tokens and more rows than the one-workgroup shapes of a large-image batch
+    take: the kernel that keeps the matrix on chip
+    across a cluster of workgroups (448 rows each, up to eight), on both sides of its limits and of
+    its row strips; with eps = 0.02 exp's range does not fit fp32 and the streaming kernels take
+    them all.  An odd and an even iteration count (the exchange buffers alternate)."""
+    shapes = [(513, 100), (896, 128), (897, 128), (896, 129), (1300, 40), (600, 65), (1217, 64), (1216, 64),
+              (449, 127), (3584, 128), (3585, 100), (2000, 17)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 35, **dict(dict(iters=40), **override))
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    assert s["status"] == 0
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, f"cluster shapes {override}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
+def test_multi_workgroup_resident_sinkhorn_through_the_fused_call_many_images():
+    """More such images than the launch has cluster slots (each slot takes several in turn), of
+    different heights, through the fused call; fused = staged bit for bit."""
+    rng = np.random.default_rng(36)
+    counts = [int(c) for c in rng.integers(620, 1500, size=40)]
+    batch = _clustered(counts, 1024, "bf16", 36, ratio=0.93, iters=21)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    pruned = np.diff(batch.offsets) - f["keep"]
+    assert (pruned > 16).all() and (pruned <= 128).all() and (f["keep"] > 512).all()
+    rep = hz.compare_batch(batch, f, images=range(0, 40, 3))
+    _log(rep, "cluster fused, 40 images")
+    s = hz.run_staged(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+    g = hz.run_prune(batch)                                      # run-to-run determinism
+    np.testing.assert_array_equal(f["out"], g["out"])
+
+
+def test_multi_workgroup_sinkhorn_gives_up_instead_of_waiting_for_ever(monkeypatch):
+    """The cluster kernel's waits are bounded.  With the bound set to a single poll (the host-side
+    test switch) a workgroup that does not find its cluster complete at once gives up: the call
+    returns, every kernel ends, and the status word says that the wait timed out.  The next call,
+    with the usual bound, is right again."""
+    batch = _clustered([700, 900, 1200, 650], 1024, "bf16", 37, ratio=0.93, iters=30)
+    monkeypatch.setenv("RTPRUNE_SYNC_SPIN_LIMIT", "1")
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0
+    assert f["status"] & rt.RTP_DEV_SYNC_TIMEOUT, f["status"]
+    monkeypatch.delenv("RTPRUNE_SYNC_SPIN_LIMIT")
+    g = hz.run_prune(batch)
+    assert g["rc"] == 0 and g["status"] == 0
+    _log(hz.compare_batch(batch, g), "after a timed-out call")
+
+
 @pytest.mark.parametrize("override", [dict(), dict(eps=0.02), dict(iters=0), dict(iters=1)])
 def test_wide_register_shapes_at_their_edges(override):
     """Images of at most 512 tokens with 65 to 225 pruned ones, on both sides of the
