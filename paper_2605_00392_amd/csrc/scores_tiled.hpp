@@ -73,6 +73,9 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   if (!plan_fits(plan_offsets[b], m, r, plan_cap)) return;
   const long long po = plan_offsets[b];
   const bool k_f32 = kernel_is_f32(p, m, r);
+  // the sweep kernels' images take exp through the fp32 unit; the on-chip shapes' entries are
+  // the fp64 exp rounded once, as those kernels themselves used to round them on load
+  const bool fast_exp = k_f32 && sinkhorn_variant(m, r, p.mode) == kVariantSweep;
   const int32_t* sel = sel_idx + lo;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;          // the wave's 64 x 32 part of the tile
@@ -200,7 +203,9 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
           const double sc = acc[t][u][v] * rni[t][v] * rnj;
           const long long at = static_cast<long long>(i) * r + j;
           const double x = (sc - p.shift) * inv_eps;
-          if (k_f32) {
+          if (!fast_exp && k_f32) {
+            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(exp(x));
+          } else if (k_f32) {
             const double y = x * 1.4426950408889634;
             const double k = rint(y);
             const float frac = __builtin_amdgcn_exp2f(static_cast<float>(y - k));

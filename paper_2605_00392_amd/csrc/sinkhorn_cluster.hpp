@@ -98,7 +98,8 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   const int n = A.offsets[b + 1] - lo;
   const int m = min(max(A.keep[b], 0), n), r = n - m;        // (the list holds images with n > 0, r > 0 only)
   const long long po = A.plan_offsets[b];
-  const double* __restrict__ Kg = A.kmat + po;
+  const float* __restrict__ Kg = k32_base(A.kmat, po);        // stored as fp32 (kKernelRowsF32)
+  const int pitch = k32_pitch(r);
   float* __restrict__ plan_out = A.plan_out;
   int32_t* __restrict__ pair_out = A.pair_out;
   int32_t* gave_up = C.sync + kClusterMaxSlots;
@@ -122,20 +123,20 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   float K[RPT][CPT];
 #pragma unroll
   for (int a0 = 0; a0 < RPT; a0 += 4) {
-    double v[4][CPT];
+    float v[4][CPT];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = row_base + min(rslot + TR * (a0 + u), m_loc - 1);
 #pragma unroll
       for (int c = 0; c < CPT; ++c)
-        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * r + min(cslot + TC * c, r - 1)];
+        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * pitch + min(cslot + TC * c, r - 1)];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int c = 0; c < CPT; ++c)
         if (a0 + u < RPT) {
-          float k = (rslot + TR * (a0 + u) < m_loc && cslot + TC * c < r) ? static_cast<float>(v[u][c]) : 0.f;
+          float k = (rslot + TR * (a0 + u) < m_loc && cslot + TC * c < r) ? v[u][c] : 0.f;
           forget_origin(k);
           K[a0 + u][c] = k;
         }

@@ -161,10 +161,12 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
 // workspace (plan_offsets[b], m r doubles); the score kernels write it and the
 // Sinkhorn kernel that serves the image reads it, both deciding by this function.
 //   kKernelRowsF64  row-major fp64, entry (i, j) at i r + j.
-//   kKernelRowsF32  the sweep kernels' images when the range allows (p.k32): fp32,
-//                   rows padded (k32_pitch).  A relative rounding of 6e-8 on K is an
-//                   absolute perturbation of eps * 6e-8 on the score S, below the
-//                   scores' own error, and it halves the bytes every iteration streams.
+//   kKernelRowsF32  the images of the shapes that hold the matrix as fp32 anyway (the fp32
+//                   team shapes, the multi-workgroup kernel) and, when the range allows
+//                   (p.k32), the sweep kernels': fp32, rows padded (k32_pitch).  A relative
+//                   rounding of 6e-8 on K is an absolute perturbation of eps * 6e-8 on the
+//                   score S, below the scores' own error; it halves the bytes the score
+//                   pass writes and the Sinkhorn pass reads (every iteration, for the sweep).
 //   kKernelColsF64  the one-, two- and eight-wave shapes, whose lanes own rows:
 //                   column-major fp64, entry (i, j) at j m + i, so that the 64 lanes of
 //                   a load read 64 consecutive entries (row-major, they read 64 cache
@@ -173,6 +175,10 @@ constexpr int kKernelRowsF64 = 0, kKernelRowsF32 = 1, kKernelColsF64 = 2;
 __device__ __forceinline__ int kernel_layout(const DevParams& p, int m, int r) {
   const int v = sinkhorn_variant(m, r, p.mode);
   if (v == kVariantSweep) return p.k32 ? kKernelRowsF32 : kKernelRowsF64;
+  // (these are only chosen under kModeF32)
+  if (v == kVariantTeamTall || v == kVariantWideA || v == kVariantWideB || v == kVariantWideC || v == kVariantC32 ||
+      v == kVariantCluster)
+    return kKernelRowsF32;
   return (v == kVariantA || v == kVariantPair || v == kVariantTall) ? kKernelColsF64 : kKernelRowsF64;
 }
 __device__ __forceinline__ bool kernel_is_f32(const DevParams& p, int m, int r) {
@@ -228,14 +234,18 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
   if (r <= 0 || m <= 0) return;
   if (!plan_fits(plan_offsets[b], m, r, A.plan_cap)) return;
   const long long po = plan_offsets[b];
-  const double* Kg = kmat + po;
+  // KT = float: the registers hold rounded entries, widened again at each use
+  // (the compiler must not keep the widened copies, hence `forget_origin`); the score
+  // pass has stored them rounded already (kKernelRowsF32)
+  constexpr bool kNarrow = std::is_same<KT, float>::value;
+  const KT* Kg;
+  int pitch;
+  if constexpr (kNarrow) { Kg = k32_base(kmat, po); pitch = k32_pitch(r); }
+  else { Kg = kmat + po; pitch = r; }
 
   const int cslot = tt & (TC - 1);
   const int rslot = tt >> LOG_TC;
 
-  // KT = float: the registers hold rounded entries, widened again at each use
-  // (the compiler must not keep the widened copies, hence `forget_origin`)
-  constexpr bool kNarrow = std::is_same<KT, float>::value;
   KT K[RPT][CPT];
   // Loads are unconditional (from a clamped position), so that a thread's loads
   // overlap instead of each waiting inside its own branch; they go four rows at
@@ -243,20 +253,20 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
   // requested, so that the loads in flight need no more registers than the matrix.
 #pragma unroll
   for (int a0 = 0; a0 < RPT; a0 += 4) {
-    double v[4][CPT];
+    KT v[4][CPT];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = min(rslot + TR * (a0 + u), m - 1);
 #pragma unroll
       for (int c = 0; c < CPT; ++c)
-        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * r + min(cslot + TC * c, r - 1)];
+        if (a0 + u < RPT) v[u][c] = Kg[static_cast<long long>(i) * pitch + min(cslot + TC * c, r - 1)];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int c = 0; c < CPT; ++c)
         if (a0 + u < RPT) {
-          KT k = (rslot + TR * (a0 + u) < m && cslot + TC * c < r) ? static_cast<KT>(v[u][c]) : KT(0);
+          KT k = (rslot + TR * (a0 + u) < m && cslot + TC * c < r) ? v[u][c] : KT(0);
           if constexpr (kNarrow) forget_origin(k);
           K[a0 + u][c] = k;
         }
