@@ -94,6 +94,37 @@ __device__ __forceinline__ void store4(float* p, const float (&x)[4]) {
   *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
 }
 
+// The same as streaming stores, for the rows of the output: nothing in the call reads them
+// again, and left in the caches as ordinary dirty lines they are written back while the next
+// call's first pass reads (measured on 1024 pages of 400 tokens: that pass 229 -> 204 us).
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store4_stream(bf16_t* p, const float (&x)[4]) {
+  const u32x2_t u = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+  __builtin_nontemporal_store(u, reinterpret_cast<u32x2_t*>(p));
+}
+__device__ __forceinline__ void store4_stream(float* p, const float (&x)[4]) {
+  const f32x4_t u = {x[0], x[1], x[2], x[3]};
+  __builtin_nontemporal_store(u, reinterpret_cast<f32x4_t*>(p));
+}
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream(void* p, const uint2& v) {
+  const u32x2_t u = {v.x, v.y};
+  __builtin_nontemporal_store(u, static_cast<u32x2_t*>(p));
+}
+__device__ __forceinline__ void store_stream(void* p, const uint4& v) {
+  const u32x4_t u = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(u, static_cast<u32x4_t*>(p));
+}
+__device__ __forceinline__ uint2 load_stream(const uint2* p) {
+  const u32x2_t u = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_uint2(u.x, u.y);
+}
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+  const f32x4_t u = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(u.x, u.y, u.z, u.w);
+}
+
 // A 4-element group of a token row as it sits in memory, and its widening.
 template <typename T> struct Raw4;
 template <> struct Raw4<bf16_t> { typedef uint2 type; };

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void k_merge_lds(
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int g = lane + kWave * k;
-        if (EXACT || g < ngroups) raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * g);
+        if (EXACT || g < ngroups) raw[u][k] = load_stream(reinterpret_cast<const raw_t*>(row + 4 * g));
         else raw[u][k] = raw_t{};
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[u][k][e] = 0.f;
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void k_merge_lds(
           unpack4(raw[u][k], x);
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = fmaf(alpha, acc[u][k][e], x[e]);
-          store4(out + (obase + ia + u) * D + 4 * g, o);
+          store4_stream(out + (obase + ia + u) * D + 4 * g, o);
         }
       }
     }

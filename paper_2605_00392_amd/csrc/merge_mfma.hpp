@@ -208,8 +208,8 @@ __device__ __forceinline__ void merge_mid_tile(const MergeMidArgs& A, int b, int
             const uint2 o = make_uint2(pack_bf16x2(fmaf(A.alpha, acc[0][v], x0), fmaf(A.alpha, acc[1][v], x1)),
                                        pack_bf16x2(fmaf(A.alpha, acc[2][v], x2), fmaf(A.alpha, acc[3][v], x3)));
             if (live[rb][v])
-              *reinterpret_cast<uint2*>(obase + ooff + static_cast<uint32_t>((16 * rb + v) * D) * 2u +
-                                        static_cast<uint32_t>(it * SPI + ss) * kStepBytes) = o;
+              store_stream(obase + ooff + static_cast<uint32_t>((16 * rb + v) * D) * 2u +
+                               static_cast<uint32_t>(it * SPI + ss) * kStepBytes, o);
           }
         }
       }

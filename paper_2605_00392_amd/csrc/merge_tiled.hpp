@@ -199,7 +199,7 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
         const float x0 = __uint_as_float(kw[e] << 16), x1 = __uint_as_float(kw[e] & 0xffff0000u);
         ow[e] = pack_bf16x2(fmaf(alpha, src[2 * e], x0), fmaf(alpha, src[2 * e + 1], x1));
       }
-      *reinterpret_cast<uint4*>(out + (obase + i) * D + d0 + dd) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+      store_stream(out + (obase + i) * D + d0 + dd, make_uint4(ow[0], ow[1], ow[2], ow[3]));
     }
   }
 }

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void k_splice_text(TextSpans t, const int32_t*
     if (lane == 0 && position_ids) position_ids[base + k] = pos;
     if (src) {
       uint4* dst = reinterpret_cast<uint4*>(seq + static_cast<size_t>(base + k) * D);
-      for (int g = lane; g < pieces; g += 64) dst[g] = src[g];
+      for (int g = lane; g < pieces; g += 64) store_stream(dst + g, src[g]);
     }
   }
 }

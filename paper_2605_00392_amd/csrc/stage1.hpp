@@ -86,7 +86,7 @@ struct NormRows {
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int g = lane + kWave * k;
-        raw[u][k] = *reinterpret_cast<const raw_t*>(row + 4 * (k < KFULL ? g : min(g, ngroups - 1)));
+        raw[u][k] = load_stream(reinterpret_cast<const raw_t*>(row + 4 * (k < KFULL ? g : min(g, ngroups - 1))));
       }
     }
   }

@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256) void k_merge(
         load4(tokens + static_cast<size_t>(lo + clamp_index(sel[i0 + a], n)) * D + 4 * g, xi);
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = fmaf(alpha, acc[a][e], xi[e]);
-        store4(out + (obase + i0 + a) * D + 4 * g, o);
+        store4_stream(out + (obase + i0 + a) * D + 4 * g, o);
       }
     }
   }
