@@ -43,7 +43,7 @@ constexpr int kClusterPart = ClusterShape::TC * (ClusterShape::CPT + 1);   // va
 constexpr int kClusterMaxSlots = 64;                       // cluster slots of a launch (8 per XCD)
 // synchronisation words, after the work lists: one arrival counter per slot, then the give-up word
 constexpr int kClusterSyncWords = kClusterMaxSlots + 1;
-static_assert(kClusterSyncWords == kWorkSyncWords, "the list builder zeroes these words");
+static_assert(kClusterSyncWords == kWorkStreamWord, "the list builder zeroes these words (the next one is the sweep kernels')");
 static_assert(kClusterMaxM == kClusterRows && kClusterMaxR == kClusterCols, "the shape sinkhorn_variant assumes");
 constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxSlots) * 4 * kClusterMaxGroups * kClusterPart;
 

@@ -363,6 +363,10 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
   int c[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) c[v] = 0;
+  __shared__ unsigned long long sweep_cells;      // entries of the sweep kernels' matrices, padding included
+  if (tid == 0) sweep_cells = 0;
+  __syncthreads();
+  unsigned long long cells = 0;
   for (int b = b0; b < b1; ++b) {
     const int n = offsets[b + 1] - offsets[b];
     const int m = min(max(keep[b], 0), max(n, 0));
@@ -371,11 +375,13 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
 #pragma unroll
       for (int u = 0; u < NV; ++u) c[u] += (u == v);
     }
+    if (n > 0 && v == kVariantSweep) cells += static_cast<unsigned long long>(m) * k32_pitch(n - m);
     if (n > 0 && n - m > kTiledMinPruned) c[kListTiled] += 1;
     if (n > 0 && merge_is_mid(n - m)) c[kListMid] += 1;
   }
 #pragma unroll
   for (int v = 0; v < NV; ++v) cnt[v][tid] = c[v];
+  if (cells) atomicAdd(&sweep_cells, cells);
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {
     int add[NV];
@@ -406,7 +412,14 @@ __device__ __forceinline__ void classify_images(const int32_t* __restrict__ offs
     for (int v = 0; v < NV; ++v) work[v] = cnt[v][255];
   }
   // the cluster kernel's arrival counters and give-up word start at zero
-  if (tid < kWorkSyncWords) work[NV * (1 + B) + tid] = 0;
+  if (tid < kWorkStreamWord) work[NV * (1 + B) + tid] = 0;
+  if (tid == kWorkStreamWord) {
+    // (the matrices are fp32 when the range allows and the sweep kernels run, else fp64)
+    const double bytes = static_cast<double>(sweep_cells) * (((mode & kModeF32) && (mode & kModeSweep)) ? 4.0 : 8.0);
+    const double over = bytes > static_cast<double>(kSweepResidentBytes)
+                            ? 1.0 - static_cast<double>(kSweepResidentBytes) / bytes : 0.0;
+    work[NV * (1 + B) + kWorkStreamWord] = static_cast<int>(ceil(16.0 * over));
+  }
 }
 
 __global__ __launch_bounds__(256) void k_classify(const int32_t* __restrict__ offsets,

@@ -125,6 +125,8 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
   // out-of-range entries are zeroed afterwards.
   KT K[kSweepRows][CH * VEC];
   double yv[CH * VEC];
+  // this strip's share of what the memory-side cache cannot keep is read with streaming loads
+  const bool stream = (strip & 15) < A.work[kWorkLists * (1 + A.B) + kWorkStreamWord];
   auto column = [&](int cv) { return VEC == 4 ? 4 * ct + cv : ct + CG * cv; };   // of register slot cv
   if (VEC == 4) {
     const int pitch = k32_pitch(r);
@@ -132,7 +134,8 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
     const int j4 = min(4 * ct, pitch - 4);             // a whole aligned group inside the padded row
 #pragma unroll
     for (int a = 0; a < kSweepRows; ++a) {
-      const float4 v = *reinterpret_cast<const float4*>(Kg + static_cast<long long>(min(i0 + a, m - 1)) * pitch + j4);
+      const float4* src = reinterpret_cast<const float4*>(Kg + static_cast<long long>(min(i0 + a, m - 1)) * pitch + j4);
+      const float4 v = stream ? load_stream(src) : *src;
       K[a][0] = static_cast<KT>(v.x);
       K[a][1 % (CH * VEC)] = static_cast<KT>(v.y);
       K[a][2 % (CH * VEC)] = static_cast<KT>(v.z);
@@ -149,7 +152,10 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
       const int j = min(ct + CG * c, r - 1);
 #pragma unroll
       for (int a = 0; a < kSweepRows; ++a)
-        K[a][c] = Kg[static_cast<long long>(min(i0 + a, m - 1)) * pitch + j];
+      {
+        const KT* src = Kg + static_cast<long long>(min(i0 + a, m - 1)) * pitch + j;
+        K[a][c] = stream ? __builtin_nontemporal_load(src) : *src;
+      }
     }
   }
 #pragma unroll

@@ -113,8 +113,15 @@ constexpr int kVariantA = 0, kVariantDual = 1, kVariantDual48 = 2, kVariantB = 3
 // one of the images whose scores and merge go to the tiled matrix-core kernels.
 constexpr int kListTiled = 14, kListMid = 15, kWorkLists = 16;
 // after the lists: synchronisation words of the multi-workgroup Sinkhorn kernel (arrival counters
-// of its cluster slots, a give-up word), zeroed by whoever builds the lists
-constexpr int kWorkSyncWords = 65;
+// of its cluster slots, a give-up word), zeroed by whoever builds the lists, and one word for the
+// sweep kernels: how many of every 16 strips they read with streaming loads (kWorkStreamWord)
+constexpr int kWorkSyncWords = 66, kWorkStreamWord = 65;
+// The sweep kernels read every kernel matrix once per iteration.  The memory-side cache
+// (256 MB) keeps a working set that fits and keeps nothing of one that does not (it is read
+// round and round), so of a larger set only this much is read with ordinary loads and the rest
+// with streaming ones, which leave no lines behind.  16 pages of 4512 tokens (308 MB): 7.5 ->
+// 6.6 ms for 100 iterations at 25 to 37 % streamed, 7.9 ms with everything streamed.
+constexpr long long kSweepResidentBytes = 200ll * 1000 * 1000;
 // What a call launches besides the 512-row register shapes, as the kernels
 // receive it (`mode`).  kModeLarge: the batch may hold images with more than 512
 // tokens, so the tall shapes' kernel and the sweep kernels run.  kModeF32: the
