@@ -166,21 +166,19 @@ constexpr int kDensityBand = 62;          // column groups a wave produces
 constexpr int kDensityAhead = 6;          // rows in flight; a multiple of 3, so the three-row window
                                           // rotates through statically named registers
 
-__global__ __launch_bounds__(256) void k_density_rows(
-    const unsigned char* __restrict__ pixels, const long long* __restrict__ pixel_offsets,
-    const int32_t* __restrict__ heights, const int32_t* __restrict__ widths, int patch_h, int patch_w,
-    int patches_max, float thr2_lo, float thr2_hi, double thr2, int32_t* __restrict__ counts,
-    const int32_t* __restrict__ status) {
-  if (status[0]) return;
-  const int b = blockIdx.z;
-  const int h = heights[b], w = widths[b];
+// ALIGNED: the page starts on a 4-byte boundary (rows are a multiple of 12 bytes long), so a
+// lane's twelve bytes are three dwords.  The choice is made once per page, outside the row
+// loop: as a branch around every row's loads it made the compiler copy the whole ring of
+// prefetched rows at each row (a quarter of the loop's vector instructions).
+template <bool ALIGNED>
+__device__ __forceinline__ void density_rows_body(
+    const unsigned char* __restrict__ img, int b, int h, int w, int patch_h, int patch_w,
+    int patches_max, float thr2_lo, float thr2_hi, double thr2, int32_t* __restrict__ counts) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ngroups = w >> 2;                           // w is a multiple of patch_w, hence of 4
   const int g0 = (blockIdx.x * 4 + wave) * kDensityBand;
   const int y0 = blockIdx.y * patch_h;
   if (g0 >= ngroups || y0 >= h) return;                 // uniform over the wave
-  const unsigned char* img = pixels + pixel_offsets[b];
-  const bool aligned = (reinterpret_cast<uintptr_t>(img) & 3u) == 0;
   const int gl = g0 - 1 + lane;                         // this lane's column group (may lie outside)
   const int gc = min(max(gl, 0), ngroups - 1);
   const bool produces = lane >= 1 && lane <= kDensityBand && gl < ngroups;
@@ -190,7 +188,7 @@ __global__ __launch_bounds__(256) void k_density_rows(
   auto load_row = [&](int k, uint32_t (&d)[3]) {
     const int y = min(max(y0 - 1 + min(k, nrows - 1), 0), h - 1);
     const unsigned char* p = img + y * pitch + 12 * static_cast<size_t>(gc);
-    if (aligned) {
+    if (ALIGNED) {
       const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
       d[0] = q[0]; d[1] = q[1]; d[2] = q[2];
     } else {
@@ -247,9 +245,10 @@ __global__ __launch_bounds__(256) void k_density_rows(
           gx[c] = fmaf(2.f, hd[s1][c], hd[s0][c]) + hd[s2][c];
           gy[c] = hs[s0][c] - hs[s2][c];
           const float fx = gx[c], fy = gy[c];
-          const float f = fmaf(fx, fx, fy * fy);
-          active += f > thr2_hi ? 1 : 0;
-          unsure = unsure || (!(f > thr2_hi) && !(f < thr2_lo));
+          const float f = fmaf(fx, fx, fy * fy);     // (never a NaN: finite integers)
+          const bool above = f > thr2_hi, reaches = f >= thr2_lo;
+          active += above ? 1 : 0;
+          unsure = unsure || (above != reaches);
         }
         if (unsure) {                                   // within 2e-6 of the threshold: exact, in fp64
 #pragma unroll
@@ -269,6 +268,20 @@ __global__ __launch_bounds__(256) void k_density_rows(
     const int pcols = w / patch_w;
     atomicAdd(&counts[static_cast<long long>(b) * patches_max + blockIdx.y * pcols + (4 * gl) / patch_w], active);
   }
+}
+
+__global__ __launch_bounds__(256) void k_density_rows(
+    const unsigned char* __restrict__ pixels, const long long* __restrict__ pixel_offsets,
+    const int32_t* __restrict__ heights, const int32_t* __restrict__ widths, int patch_h, int patch_w,
+    int patches_max, float thr2_lo, float thr2_hi, double thr2, int32_t* __restrict__ counts,
+    const int32_t* __restrict__ status) {
+  if (status[0]) return;
+  const int b = blockIdx.z;
+  const unsigned char* img = pixels + pixel_offsets[b];
+  if ((reinterpret_cast<uintptr_t>(img) & 3u) == 0)
+    density_rows_body<true>(img, b, heights[b], widths[b], patch_h, patch_w, patches_max, thr2_lo, thr2_hi, thr2, counts);
+  else
+    density_rows_body<false>(img, b, heights[b], widths[b], patch_h, patch_w, patches_max, thr2_lo, thr2_hi, thr2, counts);
 }
 
 // rho_k = count_k / (patch area) and rho = mean over patches, one workgroup per image.
