@@ -103,23 +103,41 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   const double inv_eps = 1.0 / p.eps;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int iw = i0 + 32 * wave;                       // the wave's first kept row
-  const bool active = iw < m;                          // else the wave only helps with the pruned rows
+  const bool active = iw < m;                          // the wave has kept rows
   const int ntiles = (r + 15) >> 4;                    // column tiles of 16 pruned rows that exist
+  // Wave w brings in the pruned rows of column tile w.  A wave with neither kept rows nor a
+  // column tile ends here (it no longer counts at the barriers): a workgroup's step costs a
+  // memory latency whatever its size, so the 16 kept rows that a 400-token page leaves for
+  // its fourth workgroup should hold one wave's registers, not four waves'.
+  const bool feeds = wave < ntiles;
+  if (!active && !feeds) return;
   constexpr int kPitch = kScorePitch;
+  // 1 / max(norm, tiny) of the workgroup's rows, for the end: pruned rows 0 .. 63, then the 128
+  // kept rows.  Fetched now by the first wave (which always stays), so that the two dependent
+  // loads behind each value are not waited for after the last step.
+  __shared__ double rnorm[64 + kScoreRows];
+  if (wave == 0) {
+#pragma unroll
+    for (int q = 0; q < (64 + kScoreRows) / 64; ++q) {
+      const int e = lane + 64 * q;
+      const int pos = e < 64 ? m + min(e, r - 1) : min(i0 + e - 64, m - 1);
+      rnorm[e] = 1.0 / fmax(norm64[lo + clamp_index(sel[pos], n)], kTinyNorm);
+    }
+  }
 
-  // reading: eight lanes per row.  Pruned rows t / 8 and t / 8 + 32 by the whole
-  // workgroup; kept rows l / 8 + 8 q (q = 0 .. 3) of the wave's 32 by each wave.
+  // reading: eight lanes per row.  Pruned rows 16 w + l / 8 + 8 q (q = 0, 1) by wave w when
+  // that column tile exists; kept rows l / 8 + 8 q (q = 0 .. 3) of the wave's 32 by each wave.
   const char* base = reinterpret_cast<const char*>(tokens + static_cast<size_t>(lo) * D);
   const int chunk = tid & 7;
   uint32_t poff[2], koff[4];                           // byte offsets within the image (at most 8192 rows of 8 KB)
 #pragma unroll
   for (int q = 0; q < 2; ++q)
-    poff[q] = static_cast<uint32_t>(clamp_index(sel[m + min((tid >> 3) + 32 * q, r - 1)], n) * D + 8 * chunk) * 2u;
+    poff[q] = static_cast<uint32_t>(clamp_index(sel[m + min(16 * wave + (lane >> 3) + 8 * q, r - 1)], n) * D + 8 * chunk) * 2u;
 #pragma unroll
   for (int q = 0; q < 4; ++q)
     koff[q] = static_cast<uint32_t>(clamp_index(sel[min(iw + (lane >> 3) + 8 * q, m - 1)], n) * D + 8 * chunk) * 2u;
   // LDS rows 0 .. 63: pruned; 64 + 32 wave ..: the wave's kept rows
-  const int wr_p = (tid >> 3) * kPitch + 8 * chunk;                        // + 32 q rows
+  const int wr_p = (16 * wave + (lane >> 3)) * kPitch + 8 * chunk;          // + 8 q rows
   const int wr_k = (64 + 32 * wave + (lane >> 3)) * kPitch + 8 * chunk;    // + 8 q rows
   // (instruction h of a step contracts elements 16 g + 8 h .. + 7, g = 0 .. 3; which 32
   // of the 64 is immaterial as long as both operands use the same assignment)
@@ -133,18 +151,26 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
 
-  u32x4_t gp[2], gk[4];
+  u32x4_t gp[2] = {}, gk[4] = {};
   auto load_step = [&](int k0, u32x4_t (&gp)[2], u32x4_t (&gk)[4]) {
+    if (feeds) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) gp[q] = *reinterpret_cast<const u32x4_t*>(base + poff[q] + 2 * k0);
+      for (int q = 0; q < 2; ++q) gp[q] = *reinterpret_cast<const u32x4_t*>(base + poff[q] + 2 * k0);
+    }
+    if (active) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) gk[q] = *reinterpret_cast<const u32x4_t*>(base + koff[q] + 2 * k0);
+      for (int q = 0; q < 4; ++q) gk[q] = *reinterpret_cast<const u32x4_t*>(base + koff[q] + 2 * k0);
+    }
   };
   auto stage_step = [&](bf16_t* buf, const u32x4_t (&gp)[2], const u32x4_t (&gk)[4]) {
+    if (feeds) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_p + 32 * q * kPitch) = gp[q];
+      for (int q = 0; q < 2; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_p + 8 * q * kPitch) = gp[q];
+    }
+    if (active) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_k + 8 * q * kPitch) = gk[q];
+      for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4_t*>(buf + wr_k + 8 * q * kPitch) = gk[q];
+    }
   };
   const int last = D - 64;
   load_step(0, gp, gk);
@@ -161,7 +187,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
         for (int t = 0; t < 2; ++t)
           a[t] = *reinterpret_cast<const bf16x8_t*>(cur + (64 + 32 * wave + 16 * t) * kPitch + 8 * h);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) bb[u] = *reinterpret_cast<const bf16x8_t*>(cur + 16 * u * kPitch + 8 * h);
+        for (int u = 0; u < 4; ++u)
+          if (u < ntiles) bb[u] = *reinterpret_cast<const bf16x8_t*>(cur + 16 * u * kPitch + 8 * h);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           if (u < ntiles) {
@@ -182,22 +209,22 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   if (!active) return;
 
   // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile
+  // (rnorm was written before the first of the loop's barriers)
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
+    if (u >= ntiles) break;
     const int j = 16 * u + (lane & 15);
-    if (j >= r) continue;
-    const double nj = norm64[lo + clamp_index(sel[m + j], n)];
+    const double rnj = rnorm[j];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int i = iw + 16 * t + 4 * (lane >> 4) + v;
-        if (i < m) {
-          const double ni = norm64[lo + clamp_index(sel[i], n)];
-          const double sc = acc[t][u][v] / fmax(ni * nj, kTinyNorm * kTinyNorm);
-          const long long at = static_cast<long long>(i) * r + j;
-          store_kernel(kmat, po, i, j, m, r, exp((sc - p.shift) * inv_eps), k_layout);
-          if (scores_out) scores_out[po + at] = sc;
+        const int il = 32 * wave + 16 * t + 4 * (lane >> 4) + v, i = i0 + il;
+        const double sc = acc[t][u][v] * rnorm[64 + il] * rnj;
+        const double kv = exp_nonpositive((sc - p.shift) * inv_eps);
+        if (i < m && j < r) {
+          store_kernel(kmat, po, i, j, m, r, kv, k_layout);
+          if (scores_out) scores_out[po + static_cast<long long>(i) * r + j] = sc;
         }
       }
   }

@@ -204,14 +204,14 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
           const long long at = static_cast<long long>(i) * r + j;
           const double x = (sc - p.shift) * inv_eps;
           if (!fast_exp && k_f32) {
-            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(exp(x));
+            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(exp_nonpositive(x));
           } else if (k_f32) {
             const double y = x * 1.4426950408889634;
             const double k = rint(y);
             const float frac = __builtin_amdgcn_exp2f(static_cast<float>(y - k));
             k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = ldexpf(frac, static_cast<int>(k));
           } else {
-            kmat[po + at] = exp(x);
+            kmat[po + at] = exp_nonpositive(x);
           }
           if (scores_out) scores_out[po + at] = sc;
         }

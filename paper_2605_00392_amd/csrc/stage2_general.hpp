@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void k_scores(
         const double nj = norm64[lo + tj];
         const double s = dot / fmax(ni * nj, kTinyNorm * kTinyNorm);
         const long long at = static_cast<long long>(i) * r + j;
-        store_kernel(kmat, po, i, j, m, r, exp((s - p.shift) * inv_eps), k_layout);
+        store_kernel(kmat, po, i, j, m, r, exp_nonpositive((s - p.shift) * inv_eps), k_layout);
         if (scores_out) scores_out[po + at] = s;
       }
     }
