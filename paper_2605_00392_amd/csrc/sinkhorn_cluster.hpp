@@ -208,16 +208,17 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
       double acc = 0.0;
       for (int g = 0; g < groups; ++g)
         acc += __hip_atomic_load(all + g * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // (the column's reciprocal here, once per workgroup, instead of once per row slot)
+      if (c < CPT) acc = (cs + TC * c < r) ? rcp64(acc + kz * x_dust) : 0.0;
       xtot[cs][c] = acc;
     }
     __syncthreads();
 #pragma unroll
     for (int c = 0; c <= CPT; ++c) t[c] = xtot[cslot][c];
-    const double col_dust = kz * x_dust;
     double ly = 0.0;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      y[c] = (cslot + TC * c < r) ? rcp64(t[c] + col_dust) : 0.0;
+      y[c] = t[c];
       ly += y[c];
     }
     y_dust = static_cast<double>(m) * rcp64(kz * (t[CPT] + x_dust));

@@ -399,11 +399,15 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
         }
         __syncthreads();
       }
+      // (the thread that adds a column's partials also takes the reciprocal: once per
+      // workgroup instead of once per row slot)
+      const double col_dust_w = kz * x_dust;
       if (tt < TC * (CPT + 1)) {
         const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
         double acc = 0.0;
 #pragma unroll
         for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
+        if (c < CPT) acc = (cs + TC * c < r) ? rcp64(acc + col_dust_w) : 0.0;
         xtot[cs][c] = acc;
       }
       __syncthreads();
@@ -414,7 +418,8 @@ __device__ __forceinline__ void sinkhorn_team_image(const SinkhornArgs& A, int b
     double ly = 0.0;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      y[c] = (cslot + TC * c < r) ? rcp64(t[c] + col_dust) : 0.0;
+      if constexpr (W > 1) y[c] = t[c];
+      else y[c] = (cslot + TC * c < r) ? rcp64(t[c] + col_dust) : 0.0;
       ly += y[c];
     }
     y_dust = static_cast<double>(m) * rcp64(kz * (t[CPT] + x_dust));
