@@ -436,11 +436,14 @@ def main() -> int:
             other[f"c{cfg_o}"] = bench_side(rt, torch, synth, 10, cfg_o, batch=others_h.get(cfg_o), rooflines=False)
             torch.cuda.empty_cache()
 
-    large = paper_ret = None
+    large = paper_ret = large_other = None
     if not args.no_large_pages and args.workload == 5:
         del db
         torch.cuda.empty_cache()
         large = bench_side(rt, torch, synth, 3, 8)
+        torch.cuda.empty_cache()
+        # the two smaller page sizes of the same table (1083 -> 560 and 2137 -> 1238 tokens)
+        large_other = {f"c{c}": bench_side(rt, torch, synth, 3, c, rooflines=False) for c in (6, 7)}
         torch.cuda.empty_cache()
         # the benchmark's pages at the paper's own average retention (337 of 400 kept)
         paper_ret = bench_side(rt, torch, synth, 5, 9, batch=side9)
@@ -468,6 +471,7 @@ def main() -> int:
         "other_workloads": other,
         "text_density": density,
         "large_pages": large,
+        "large_pages_other_sizes": large_other,
         "paper_retention_pages": paper_ret,
     }
     print(json.dumps(line))

@@ -315,7 +315,7 @@ __device__ __forceinline__ bool plan_fits(long long off, int m, int r, long long
 // Kept count M = ceil(retention * N - 1e-3) clamped to [1, N] (0 for N = 0).
 // The product and the subtraction are rounded separately (no fused multiply-add)
 // so that the integer is the same one a host evaluation in doubles gives.
-__device__ __forceinline__ int kept_count(float retention, int n) {
+__host__ __device__ inline int kept_count(float retention, int n) {
 #pragma clang fp contract(off)
   if (n <= 0) return 0;
   if (!(retention == retention)) return n;

@@ -297,7 +297,7 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
 
 // Cluster slots per XCD of the multi-workgroup Sinkhorn kernel on this device: a slot is
 // kClusterMaxGroups compute units of one XCD (eight XCDs assumed; 0: too few compute units).
-int cluster_slots_per_xcd() { return std::min(kClusterMaxSlots / 8, compute_units() / 8 / kClusterMaxGroups); }
+int cluster_slots_per_xcd(int groups) { return std::min(kClusterMaxSlots / 8, compute_units() / 8 / std::max(groups, 1)); }
 
 // Polls a workgroup of that kernel spends on one wait before it gives up (each a few hundred
 // cycles: the default is seconds).  RTPRUNE_SYNC_SPIN_LIMIT overrides it, for tests of the
@@ -317,18 +317,25 @@ void set_sinkhorn_mode(DevParams& p, const Layout& L, const rtprune_batch* in) {
   const int f32 = p.k32 ? kModeF32 : 0;   // exp's range fits fp32: registers may hold the matrix as fp32
   // the multi-workgroup kernel that keeps a matrix on chip runs one workgroup per compute
   // unit, in clusters of eight per XCD
-  const int cluster = (L.sweep && f32 && cluster_slots_per_xcd() > 0) ? kModeCluster : 0;
+  // Under a fixed retention the largest image the batch can hold bounds the others' kept and
+  // pruned counts; when the multi-workgroup kernel can take it, a cluster slot needs no more
+  // workgroups than that image does (more slots then share the chip), and no image is beyond the
+  // on-chip kernels.
+  const int m_top = p.dynamic ? 0 : kept_count(p.ratio, in->max_tokens), r_top = in->max_tokens - m_top;
+  const bool top_fits = !p.dynamic && m_top > 0 && cluster_fits(m_top, r_top);
+  const int groups = top_fits ? cluster_groups(m_top, std::max(r_top, 1)) : kClusterMaxGroups;
+  const int cluster = (L.sweep && f32 && cluster_slots_per_xcd(groups) > 0) ? (kModeCluster | (groups << kModeGroupsShift)) : 0;
   // The streaming kernels cost two launches per iteration whether or not an image needs them,
   // and only the device knows the sizes, so they are issued when the batch's shape and the
   // parameters say that images beyond the on-chip kernels are to be expected: a fixed
-  // retention that prunes more than 128 of the longest image's tokens, or images with more
-  // kept rows than a cluster holds.  Under a dynamic retention (pages prune 2 to 12 % of their
+  // retention under which the longest image fits no cluster shape, or images with more kept
+  // rows than a cluster holds.  Under a dynamic retention (pages prune 2 to 12 % of their
   // tokens; the clamp at 0.6 is a bound, not the rule) they are not: an image that does end
   // up beyond the on-chip kernels takes the one-workgroup general kernel, which is right and
   // slow.  Only the batch's shape and the parameters enter, so that the staged calls choose
   // the same kernels as the fused ones.
-  const bool many_pruned = !p.dynamic && static_cast<int>((1.0 - static_cast<double>(p.ratio)) * in->max_tokens) + 1 > kClusterCols;
-  const int sweep = (L.sweep && (!cluster || many_pruned || in->max_tokens - 1 > kClusterRows)) ? kModeSweep : 0;
+  const bool beyond = p.dynamic ? in->max_tokens - 1 > kClusterRows : !top_fits;
+  const int sweep = (L.sweep && (!cluster || beyond)) ? kModeSweep : 0;
   p.k32 = p.k32 && sweep;                 // the sweep kernels' copy in memory is fp32
   p.mode = (L.sweep ? kModeLarge : 0) | f32 | cluster | sweep;
 }
@@ -457,10 +464,11 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     // the tall one-workgroup shapes and, before them in the same launch, the clusters of
     // workgroups (one per compute unit of the slots in use: all resident together, which their
     // waits rely on)
-    const int spx = (p.mode & kModeCluster) ? cluster_slots_per_xcd() : 0;
-    const int cluster_blocks = 8 * spx * kClusterMaxGroups;
+    const int groups = std::max(mode_cluster_groups(p.mode), 1);
+    const int spx = (p.mode & kModeCluster) ? cluster_slots_per_xcd(groups) : 0;
+    const int cluster_blocks = 8 * spx * groups;
     const ClusterArgs CA{A, work, in->B, work + kWorkLists * (1 + static_cast<size_t>(in->B)),
-                         at<double>(ws, L.cluster_part), spx, cluster_spin_limit(), at<int32_t>(ws, L.status)};
+                         at<double>(ws, L.cluster_part), spx, groups, cluster_spin_limit(), at<int32_t>(ws, L.status)};
     ProfScope prof(KID_SINKHORN_TALL, s);
     hipLaunchKernelGGL(k_sinkhorn_large, dim3(cluster_blocks + in->B), dim3(kClusterThreads), 0, s, CA, cluster_blocks);
   }

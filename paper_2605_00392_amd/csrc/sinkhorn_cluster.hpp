@@ -15,6 +15,13 @@
 // from memory once per call instead of once per iteration, and an iteration costs a
 // few microseconds of barrier instead of two kernel launches.
 //
+// Images with more than 128 pruned tokens (up to 576, and up to 1152 kept rows: the
+// 1083-token pages of which 560 are kept) take strips of 144 rows instead: a wave per row
+// slot with its 64 lanes across the columns, 18 x 9 entries per thread, and 576 + 1
+// partial sums per workgroup and iteration.  A slot has as many workgroups as the
+// largest image of the launch needs (the host knows it under a fixed retention), so that
+// more slots share the chip: four for those pages, 64 of them at a time.
+//
 // The barrier.  The workgroups of all clusters are resident together: the kernel is
 // launched with one workgroup per compute unit and no more (each needs a CU's whole
 // register file), and a cluster slot works through its share of the image list with
@@ -37,9 +44,21 @@ namespace rtp {
 constexpr int kClusterMaxGroups = 8;                       // workgroups per cluster
 constexpr int kClusterThreads = 512;
 using ClusterShape = TeamWideA;                            // 448 rows x 128 columns per workgroup
+using ClusterShapeWide = TeamStripWide;                    // 144 rows x 576 columns per workgroup
 constexpr int kClusterMaxM = kClusterMaxGroups * ClusterShape::kMaxM;   // 3584 kept rows
 constexpr int kClusterMaxR = ClusterShape::kMaxR;
-constexpr int kClusterPart = ClusterShape::TC * (ClusterShape::CPT + 1);   // values a workgroup publishes: 144
+static_assert(kClusterMaxGroups * ClusterShapeWide::kMaxM == kClusterWideRows && ClusterShapeWide::kMaxR == kClusterWideCols,
+              "the shape sinkhorn_variant assumes");
+template <typename S> constexpr int cluster_part_of() { return S::TC * (S::CPT + 1); }   // values a workgroup publishes
+constexpr int kClusterPart = cluster_part_of<ClusterShapeWide>();          // 640 (144 for the 448-row strips)
+static_assert(cluster_part_of<ClusterShape>() <= kClusterPart, "exchange buffers are sized for the wider shape");
+// LDS of a cluster workgroup: the waves' partial column sums (reused for the pairing's
+// candidates), their totals, the latest x per row, a flag
+template <typename S> constexpr int cluster_lds_of() {
+  return (S::W * S::TC * (S::CPT + 1) + S::TC * (S::CPT + 1) + S::TR * S::RPT) * 8 + 16;
+}
+constexpr int kClusterLdsBytes = cluster_lds_of<ClusterShapeWide>() > cluster_lds_of<ClusterShape>()
+                                     ? cluster_lds_of<ClusterShapeWide>() : cluster_lds_of<ClusterShape>();
 constexpr int kClusterMaxSlots = 64;                       // cluster slots of a launch (8 per XCD)
 // synchronisation words, after the work lists: one arrival counter per slot, then the give-up word
 constexpr int kClusterSyncWords = kClusterMaxSlots + 1;
@@ -54,7 +73,8 @@ struct ClusterArgs {
   int32_t* sync;            // [kClusterSyncWords], zeroed by the kernel that built the lists
   double* part;             // [slots][4][kClusterMaxGroups][kClusterPart] exchange buffers: two for the sums
                             // (by iteration parity), two for the pairing keys (by the slot's image parity)
-  int slots_per_xcd;        // launch: 8 XCDs x slots_per_xcd slots x kClusterMaxGroups workgroups
+  int slots_per_xcd;        // launch: 8 XCDs x slots_per_xcd slots x groups_per_slot workgroups
+  int groups_per_slot;      // at most kClusterMaxGroups
   int spin_limit;
   int32_t* status;
 };
@@ -63,7 +83,13 @@ struct ClusterArgs {
 // counter must reach (every workgroup keeps the same running total).  False: gave up.
 __device__ __forceinline__ bool cluster_meet(int32_t* counter, int32_t* gave_up, int arrived, int spin_limit,
                                              int32_t* status, int* s_flag) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's published values have completed
+  // This thread's published values must have reached the L2 before anybody is told that the
+  // workgroup has arrived.  A workgroup-scope release does not wait for stores to be acknowledged
+  // (waves of a workgroup share their caches), so wait for the store counter explicitly; found
+  // with 640 values per workgroup, where the last stores are issued just before this point and
+  // another workgroup read the previous iteration's sums.
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -83,13 +109,39 @@ __device__ __forceinline__ bool cluster_meet(int32_t* counter, int32_t* gave_up,
   return *s_flag != 0;
 }
 
+// The same wait without arriving: a workgroup of the slot that has no strip of the current image
+// stays here until the image's workgroups have all been through its last meeting.  (If it went on
+// to the slot's next image at once, its first arrival there would be counted into a meeting of the
+// current image, which would then let a workgroup through before all its partners' sums are out.)
+__device__ __forceinline__ bool cluster_wait(int32_t* counter, int32_t* gave_up, int arrived, int spin_limit,
+                                             int32_t* status, int* s_flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int ok = 0;
+    for (int spin = 0; spin < spin_limit; ++spin) {
+      if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= arrived) { ok = 1; break; }
+      if (__hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+      __builtin_amdgcn_s_sleep(8);
+    }
+    if (!ok) {
+      __hip_atomic_store(gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      atomicOr(status, RTP_DEV_SYNC_TIMEOUT);
+    }
+    *s_flag = ok;
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
 // One image on the `groups` workgroups of a slot; this workgroup is `rank` < groups.  Every
 // workgroup of the cluster takes the same path through the barriers.  `arrived` carries the
 // slot's running arrival count.  False: a wait was given up, leave the kernel.
+template <typename S>
 __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int b, int rank, int groups,
-                                                       int32_t* counter, double* part, int& arrived, int seq) {
-  typedef ClusterShape S;
+                                                       int32_t* counter, double* part, int& arrived, int seq,
+                                                       void* lds) {
   constexpr int TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T, LOG_TC = S::LOG_TC, W = S::W;
+  constexpr int kPart = cluster_part_of<S>();               // (buffers are kClusterPart apart whatever the shape)
   static_assert(T == kClusterThreads, "workgroup shape");
   const SinkhornArgs& A = C.S;
   const DevParams& p = A.p;
@@ -111,12 +163,14 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   const int cslot = tt & (TC - 1);
   const int rslot = tt >> LOG_TC;
 
-  __shared__ double xw[W][TC][CPT + 1];
-  __shared__ double xtot[TC][CPT + 1];
-  __shared__ double xs[TR][RPT];
-  __shared__ float pv[W][TC][CPT];
-  __shared__ int pi[W][TC][CPT];
-  __shared__ int s_flag;
+  double (*xw)[TC][CPT + 1] = static_cast<double (*)[TC][CPT + 1]>(lds);                 // [W]
+  double (*xtot)[CPT + 1] = reinterpret_cast<double (*)[CPT + 1]>(xw + W);               // [TC]
+  double (*xs)[RPT] = reinterpret_cast<double (*)[RPT]>(xtot + TC);                      // [TR]
+  int& s_flag = *reinterpret_cast<int*>(xs + TR);
+  // the pairing's candidates, once the iterations are over, where the partial sums were
+  float (*pv)[TC][CPT] = static_cast<float (*)[TC][CPT]>(lds);                           // [W]
+  int (*pi)[TC][CPT] = reinterpret_cast<int (*)[TC][CPT]>(pv + W);                       // [W]
+  static_assert(sizeof(float) * 2 * W * TC * CPT <= sizeof(double) * W * TC * (CPT + 1), "candidates fit the sums' area");
 
   // the matrix: unconditional loads from clamped positions, four rows at a time, narrowed
   // before the next four are requested
@@ -193,21 +247,26 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
     __syncthreads();
     // ... published, and after the cluster has met, every workgroup's sums added in rank order
     double* mine = part + ((it & 1) * kClusterMaxGroups + rank) * kClusterPart;
-    if (tt < kClusterPart) {
-      const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
+    for (int e = tt; e < kPart; e += T) {
+      const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
       double acc = 0.0;
 #pragma unroll
       for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
-      __hip_atomic_store(mine + tt, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(mine + e, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     arrived += groups;
     if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
-    if (tt < kClusterPart) {
-      const int cs = tt / (CPT + 1), c = tt - cs * (CPT + 1);
-      const double* all = part + (it & 1) * kClusterMaxGroups * kClusterPart + tt;
+    for (int e = tt; e < kPart; e += T) {
+      const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
+      const double* all = part + (it & 1) * kClusterMaxGroups * kClusterPart + e;
+      // all workgroups' values requested together (from a clamped position past the last), added in rank order
+      double v[kClusterMaxGroups];
+#pragma unroll
+      for (int g = 0; g < kClusterMaxGroups; ++g)
+        v[g] = __hip_atomic_load(all + min(g, groups - 1) * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       double acc = 0.0;
-      for (int g = 0; g < groups; ++g)
-        acc += __hip_atomic_load(all + g * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int g = 0; g < kClusterMaxGroups; ++g) acc += g < groups ? v[g] : 0.0;
       // (the column's reciprocal here, once per workgroup, instead of once per row slot)
       if (c < CPT) acc = (cs + TC * c < r) ? rcp64(acc + kz * x_dust) : 0.0;
       xtot[cs][c] = acc;
@@ -308,10 +367,11 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
 }
 
 // Workgroup `block` of the cluster part of the launch: 8 XCDs x slots_per_xcd slots x
-// kClusterMaxGroups workgroups; slot s takes images s, s + slots, ... of the list.
-__device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int block) {
+// groups_per_slot workgroups; slot s takes images s, s + slots, ... of the list.
+__device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int block, void* lds) {
   const int x = block & 7, local = block >> 3;
-  const int slot_in_xcd = local / kClusterMaxGroups, rank = local % kClusterMaxGroups;
+  const int per_slot = C.groups_per_slot;
+  const int slot_in_xcd = local / per_slot, rank = local % per_slot;
   if (slot_in_xcd >= C.slots_per_xcd) return;
   const int slots = 8 * C.slots_per_xcd, slot = x * C.slots_per_xcd + slot_in_xcd;
   int32_t* counter = C.sync + slot;
@@ -326,11 +386,17 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
     // (every workgroup of the slot takes the same decisions: they read the same words)
     if (m <= 0 || r <= 0 || sinkhorn_variant(m, r, A.p.mode) != kVariantCluster) continue;
     if (!plan_fits(A.plan_offsets[b], m, r, A.plan_cap)) continue;
-    const int groups = (m + ClusterShape::kMaxM - 1) / ClusterShape::kMaxM;
+    const int groups = cluster_groups(m, r);           // (at most per_slot: sinkhorn_variant has seen to it)
     if (rank < groups) {
-      if (!sinkhorn_cluster_image(C, b, rank, groups, counter, part, arrived, seq)) return;
+      const bool ok = r <= kClusterCols
+                          ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, lds)
+                          : sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, lds);
+      if (!ok) return;
     } else {
       arrived += groups * (A.p.iters + 1);             // what the meetings it stays out of add to the count
+      if (k + slots >= count) return;                  // the slot's last image: nothing to wait for, the CU is free
+      int* flag = reinterpret_cast<int*>(static_cast<unsigned char*>(lds) + kClusterLdsBytes - 16);
+      if (!cluster_wait(counter, C.sync + kClusterMaxSlots, arrived, C.spin_limit, C.status, flag)) return;
     }
   }
 }
@@ -344,8 +410,9 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
 __global__ __launch_bounds__(kClusterThreads) void k_sinkhorn_large(ClusterArgs C, int cluster_blocks) {
   static_assert(kClusterThreads == kDualThreads, "one workgroup shape for both parts");
   if (C.status[0]) return;
+  __shared__ __align__(16) unsigned char cluster_lds[kClusterLdsBytes];
   const int blk = blockIdx.x;
-  if (blk < cluster_blocks) sinkhorn_cluster_block(C, blk);
+  if (blk < cluster_blocks) sinkhorn_cluster_block(C, blk, cluster_lds);
   else sinkhorn_tall_block(C.S, C.work, C.B, blk - cluster_blocks);
 }
 

@@ -85,6 +85,9 @@ using TeamTall32 = TeamShape<8, 3, 19, 4>;  // R <= 32
 using TeamWideA = TeamShape<8, 4, 14, 8>;   // M <= 448, R <= 128
 using TeamWideB = TeamShape<8, 5, 24, 6>;   // M <= 384, R <= 192
 using TeamWideC = TeamShape<8, 5, 20, 7>;   // M <= 320, R <= 224
+// A strip of a larger image in the multi-workgroup kernel (sinkhorn_cluster.hpp) when it has
+// more than 128 pruned tokens: a wave per row slot, the 64 lanes across the columns.
+using TeamStripWide = TeamShape<8, 6, 18, 9>;   // 144 rows x 576 columns per workgroup
 // The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
 // lane, kCols augmented columns.
 struct WaveShape {
@@ -130,8 +133,22 @@ constexpr long long kSweepResidentBytes = 200ll * 1000 * 1000;
 // taller matrices on chip (sinkhorn_cluster.hpp).
 // kModeSweep: the launches of the streaming multi-workgroup kernels (sinkhorn_sweep.hpp) are issued.
 constexpr int kModeLarge = 1, kModeF32 = 2, kModeCluster = 4, kModeSweep = 8;
-// (that kernel's shape: up to eight workgroups of 448 rows, at most 128 pruned tokens)
+// bits 8-11 of `mode`: workgroups per cluster slot of the multi-workgroup kernel in this launch
+// (1 to 8); an image that would need more is not that kernel's
+constexpr int kModeGroupsShift = 8;
+__host__ __device__ inline int mode_cluster_groups(int mode) { return (mode >> kModeGroupsShift) & 15; }
+// (that kernel's shapes: up to eight workgroups of 448 rows with at most 128 pruned tokens, or of
+// 144 rows with at most 576)
 constexpr int kClusterRows = 8 * 448, kClusterCols = 128;
+constexpr int kClusterWideRows = 8 * 144, kClusterWideCols = 576;
+__host__ __device__ inline bool cluster_fits(int m, int r) {
+  return (m <= kClusterRows && r <= kClusterCols) || (m <= kClusterWideRows && r <= kClusterWideCols);
+}
+// workgroups the kernel spreads such an image over: strips of 448 rows, or of 144 when it has
+// more than 128 pruned tokens
+__host__ __device__ inline int cluster_groups(int m, int r) {
+  return r <= kClusterCols ? (m + 447) / 448 : (m + 143) / 144;
+}
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
 // pruned tokens.
 constexpr int kSweepMaxPruned = 2048;
@@ -144,9 +161,10 @@ __host__ __device__ inline int sinkhorn_variant(int m, int r, int mode) {
   if (m + 1 <= kDualRows && r + 1 <= kDualCols) return kVariantDual;
   if ((mode & kModeLarge) && TallShape::fits(m, r)) return kVariantTall;
   if ((mode & kModeLarge) && (mode & kModeF32) && TeamTall::fits(m, r)) return kVariantTeamTall;
-  // at most 128 pruned tokens and rows beyond the shapes above: a cluster of workgroups (one, for
-  // up to 448 rows) that keeps the matrix on chip
-  if ((mode & kModeLarge) && (mode & kModeF32) && (mode & kModeCluster) && m <= kClusterRows && r <= kClusterCols)
+  // rows beyond the shapes above with at most 128 pruned tokens, or up to 1152 rows with at most
+  // 576: a cluster of workgroups that keeps the matrix on chip
+  if ((mode & kModeLarge) && (mode & kModeF32) && (mode & kModeCluster) && cluster_fits(m, r) &&
+      cluster_groups(m, r) <= mode_cluster_groups(mode))
     return kVariantCluster;
   // when the sweep kernels run anyway (their launches are paid for) they also
   // take the images of the slowest register shapes, which otherwise set the

@@ -43,6 +43,7 @@ def run_prune(batch: synth.Batch, params: Optional[Dict] = None, device="cuda:0"
     p = rt.make_params(batch.params if params is None else params)
     db = rt.upload(batch, device)
     ws = rt.alloc_workspace(db)
+    ws.fill_(0xFF)     # the workspace is scratch: a value read before it is written must not be a plausible one
     B, total = db.B, db.total_tokens
     out = torch.zeros((max(total, 1), db.D), dtype=db.tokens.dtype, device=device)
     out_off = torch.full((B + 1,), -7, dtype=torch.int32, device=device)
@@ -66,6 +67,7 @@ def run_staged(batch: synth.Batch, params: Optional[Dict] = None, keep_counts_in
     p = rt.make_params(pd)
     db = rt.upload(batch, device)
     ws = rt.alloc_workspace(db)
+    ws.fill_(0xFF)     # the workspace is scratch: a value read before it is written must not be a plausible one
     B, total = db.B, db.total_tokens
     i32 = dict(dtype=torch.int32, device=device)
     f32 = dict(dtype=torch.float32, device=device)

@@ -239,6 +239,51 @@ def test_multi_workgroup_resident_sinkhorn_at_its_edges(override):
     assert rep.max_score_abs <= hz.SCORE_ATOL
 
 
+@pytest.mark.parametrize("override", [dict(), dict(iters=0), dict(iters=1), dict(iters=8)])
+def test_multi_workgroup_resident_sinkhorn_wide_strips_at_their_edges(override):
+    """More than 128 pruned tokens: the same kernel with strips of 144 rows x 576 columns (up to
+    eight workgroups, 1152 rows), on both sides of its limits and of its strips; what lies beyond
+    goes to the streaming kernels."""
+    shapes = [(560, 523), (144, 576), (145, 129), (288, 300), (289, 300), (1152, 576), (1153, 576), (1152, 577),
+              (1008, 129), (700, 200), (513, 130)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 38, **dict(dict(iters=31), **override))
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    assert s["status"] == 0
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, f"cluster wide strips {override}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
+def test_multi_workgroup_resident_sinkhorn_wide_strips_fill_the_chip():
+    """A fixed retention under which the longest image takes four strips: slots of four workgroups,
+    64 of them, more images than slots, through the fused call (no launches of the streaming
+    kernels: the profile says which kernels ran); fused = staged bit for bit."""
+    rng = np.random.default_rng(39)
+    counts = [int(c) for c in rng.integers(700, 1084, size=70)] + [1083]
+    batch = _clustered(counts, 256, "bf16", 39, ratio=560.0 / 1083.0, iters=12)
+    rt.rtprune_profile_only(None)
+    rt.rtprune_profile_enable(1)
+    f = hz.run_prune(batch)
+    rc, prof = rt.rtprune_profile_summary()
+    rt.rtprune_profile_enable(0)
+    assert f["rc"] == 0 and f["status"] == 0 and rc == 0
+    ms = {r["kernel"]: r["total_ms"] for r in prof}
+    # (the streaming kernels' 2 T + 3 launches are recorded under k_sinkhorn, with the general
+    # kernel's one: far more than the 0.1 ms allowed here if they were issued)
+    assert "k_sinkhorn_tall" in ms and ms.get("k_sinkhorn", 0.0) < 0.1, ms
+    rep = hz.compare_batch(batch, f, images=list(range(0, 71, 6)) + [70])
+    _log(rep, "cluster wide strips, fused, 71 images")
+    s = hz.run_staged(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+    for _ in range(3):                                           # run-to-run determinism of the exchange
+        g = hz.run_prune(batch)
+        np.testing.assert_array_equal(f["out"], g["out"])
+        np.testing.assert_array_equal(f["pair"], g["pair"])
+
+
 def test_multi_workgroup_resident_sinkhorn_through_the_fused_call_many_images():
     """More such images than the launch has cluster slots (each slot takes several in turn), of
     different heights, through the fused call; fused = staged bit for bit."""
