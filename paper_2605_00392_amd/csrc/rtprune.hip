@@ -299,6 +299,17 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
 // kClusterMaxGroups compute units of one XCD (eight XCDs assumed; 0: too few compute units).
 int cluster_slots_per_xcd(int groups) { return std::min(kClusterMaxSlots / 8, compute_units() / 8 / std::max(groups, 1)); }
 
+// RTPRUNE_SWEEP_STREAM_16THS = 0 .. 16 fixes the share of strips that the sweep kernels read with
+// streaming loads (for tests: a batch whose matrices exceed the memory-side cache takes seconds
+// of oracle time); unset, the share follows from the matrices' size.
+int sweep_stream_override() {
+  if (const char* e = std::getenv("RTPRUNE_SWEEP_STREAM_16THS")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 0 && v <= 16) return static_cast<int>(v);
+  }
+  return -1;
+}
+
 // Polls a workgroup of that kernel spends on one wait before it gives up (each a few hundred
 // cycles: the default is seconds).  RTPRUNE_SYNC_SPIN_LIMIT overrides it, for tests of the
 // give-up path.
@@ -490,7 +501,8 @@ int launch_ot(const rtprune_batch* in, const DevParams& p_in, const int32_t* sel
     SweepArgs SA{in->offsets, keep, plan_off, work, in->B, p, kmat, L.plan_cap,
                 at<double>(ws, L.sw_x), at<double>(ws, L.sw_y), at<void>(ws, L.sw_colpart),
                 at<double>(ws, L.sw_xpart), at<double>(ws, L.sw_ysum), at<double>(ws, L.sw_ydust),
-                at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair};
+                at<float>(ws, L.sw_bestv), at<int32_t>(ws, L.sw_besti), in->total_tokens, plan, pair,
+                sweep_stream_override()};
     const int strips = (in->max_tokens + kSweepRows - 1) / kSweepRows;
     const int cols = (std::min(in->max_tokens, kSweepMaxR) + kSweepCols - 1) / kSweepCols;
     const dim3 grows(strips, in->B), gcols(cols, in->B);

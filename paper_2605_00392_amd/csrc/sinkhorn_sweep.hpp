@@ -54,6 +54,8 @@ struct SweepArgs {
   long long total;
   float* plan_out;     // may be null
   int32_t* pair_out;   // may be null
+  int stream_16ths;    // >= 0: that many of every 16 strips are read with streaming loads, whatever the
+                       // list builder worked out (a switch for tests); < 0: its figure
 };
 
 // Where image b's per-strip arrays start: ceil(m/16) r <= m r / 16 + r entries
@@ -126,7 +128,7 @@ __device__ __forceinline__ void sweep_rows_body(const SweepArgs& A, const SweepI
   KT K[kSweepRows][CH * VEC];
   double yv[CH * VEC];
   // this strip's share of what the memory-side cache cannot keep is read with streaming loads
-  const bool stream = (strip & 15) < A.work[kWorkLists * (1 + A.B) + kWorkStreamWord];
+  const bool stream = (strip & 15) < (A.stream_16ths >= 0 ? A.stream_16ths : A.work[kWorkLists * (1 + A.B) + kWorkStreamWord]);
   auto column = [&](int cv) { return VEC == 4 ? 4 * ct + cv : ct + CG * cv; };   // of register slot cv
   if (VEC == 4) {
     const int pitch = k32_pitch(r);

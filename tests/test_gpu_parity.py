@@ -206,6 +206,25 @@ def test_multi_workgroup_sinkhorn_variants(override):
     np.testing.assert_array_equal(f["pair"], s["pair"])
 
 
+@pytest.mark.parametrize("share", ["0", "5", "16"])
+def test_streaming_kernels_with_a_share_of_streaming_loads(monkeypatch, share):
+    """The streaming Sinkhorn kernels read the part of their matrices that the memory-side cache
+    cannot keep with streaming loads.  The share is worked out from the matrices' size on the
+    device; here it is fixed from the host (none, some, all of every 16 strips), on images wide
+    and narrow enough for both load paths of the row kernel: the same bits each time, and right."""
+    batch = _clustered([1800, 1500, 700, 2400], 256, "bf16", 41, ratio=0.45, iters=9)
+    monkeypatch.delenv("RTPRUNE_SWEEP_STREAM_16THS", raising=False)
+    ref = hz.run_prune(batch)
+    assert ref["rc"] == 0 and ref["status"] == 0
+    monkeypatch.setenv("RTPRUNE_SWEEP_STREAM_16THS", share)
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    np.testing.assert_array_equal(ref["out"], f["out"])
+    np.testing.assert_array_equal(ref["pair"], f["pair"])
+    if share == "5":
+        _log(hz.compare_batch(batch, f, images=[2, 3]), "sweep, 5/16 streamed")
+
+
 def test_tall_register_shapes_at_their_edges():
     """Kept and pruned counts on both sides of the limits of the two shapes that hold
     a tall image (more than 512 rows) in one workgroup's registers: 1535 x 15
@@ -498,6 +517,7 @@ def test_merge_without_workspace():
     dict(iters=1),
     dict(ratio=0.5),
     dict(ratio=0.25, iters=20),         # more pruned than kept
+    dict(eps=0.0034, iters=30),         # the kernel matrix's exponents down to -588: the accepted range's end
 ])
 def test_parameter_variants_c2_subset(override):
     batch = synth.gen_batch(2, images=range(4))
