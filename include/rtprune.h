@@ -73,10 +73,18 @@ enum {
   RTP_DEV_SYNC_TIMEOUT = 8    /* the Sinkhorn kernel that spreads a tall image over several workgroups gave
                                  up waiting for one of them (they must all be resident at once: only a GPU
                                  kept busy for seconds by other work can cause it); the images it serves
-                                 - in batches with images above 512 tokens, those with 17 to 128 pruned
-                                 tokens that no one-workgroup shape holds - have no valid plan, pairing
-                                 or merged rows in this call's outputs */
+                                 - in batches with images above 512 tokens, those that no one-workgroup
+                                 shape holds, with up to 128 pruned tokens and 3584 kept ones or up to
+                                 576 and 1152 - have no valid plan, pairing or merged rows in this
+                                 call's outputs */
 };
+
+/* Two environment variables are read at each call, for tests only (they change no result):
+ *   RTPRUNE_SYNC_SPIN_LIMIT      polls a workgroup of that kernel spends on one wait before it gives
+ *                                up (default: 20 000 000, seconds); a value of 1 forces the give-up path
+ *   RTPRUNE_SWEEP_STREAM_16THS   0 .. 16: how many of every 16 strips the streaming Sinkhorn kernels
+ *                                read with non-temporal loads (default: worked out on the device from
+ *                                the size of their matrices against the memory-side cache) */
 
 /* Importance score of stage 1.  The method uses the l2 norm (Eq. 1); the
  * variance of a token's D feature values is the alternative the paper's
