@@ -148,6 +148,21 @@ def test_c9_full_batch_against_oracle():
     assert rep.images == 1024 and rep.pairs_checked == 1024 * 63
 
 
+def test_c6_full_batch_against_oracle():
+    """The 1083-token pages (Table 6: 560 kept), whole batch in the benchmark's launch
+    configuration: 64 images on the 64 four-workgroup slots of the kernel that keeps their
+    Sinkhorn matrices on chip, every image compared."""
+    batch = synth.gen_batch_parallel(6)
+    assert batch.batch == 64 and batch.max_tokens == 1083
+    f = hz.run_prune(batch)
+    assert f["rc"] == 0 and f["status"] == 0
+    assert (f["keep"] == 560).all()
+    rep = hz.compare_batch_parallel(batch, f, chunk=2)            # every image
+    _log(rep, "c6 fused (all 64 images)")
+    _log_counts(rep, "c6")
+    assert rep.images == 64 and rep.pairs_checked == 64 * 523
+
+
 # ------------------------------------------- other OCR models' token counts (Table 6)
 @pytest.mark.parametrize("cfg,images,kept", [(6, 3, 560), (7, 2, 1238), (8, 1, 2783), (9, 6, 337)])
 def test_large_pages(cfg, images, kept):
