@@ -74,9 +74,9 @@ enum {
                                  up waiting for one of them (they must all be resident at once: only a GPU
                                  kept busy for seconds by other work can cause it); the images it serves
                                  - in batches with images above 512 tokens, those that no one-workgroup
-                                 shape holds, with up to 128 pruned tokens and 3584 kept ones or up to
-                                 576 and 1152 - have no valid plan, pairing or merged rows in this
-                                 call's outputs */
+                                 shape holds, with up to 128 pruned tokens and 3584 kept ones, up to
+                                 576 and 1152, or up to 960 and 1280 - have no valid plan, pairing or
+                                 merged rows in this call's outputs */
 };
 
 /* Two environment variables are read at each call, for tests only (they change no result):

@@ -296,8 +296,11 @@ int launch_select(const rtprune_batch* in, const DevParams& p, const float* dens
 }
 
 // Cluster slots per XCD of the multi-workgroup Sinkhorn kernel on this device: a slot is
-// kClusterMaxGroups compute units of one XCD (eight XCDs assumed; 0: too few compute units).
-int cluster_slots_per_xcd(int groups) { return std::min(kClusterMaxSlots / 8, compute_units() / 8 / std::max(groups, 1)); }
+// `groups` compute units of one XCD (eight XCDs assumed; 0: too few compute units).
+int cluster_slots_per_xcd(int groups) {
+  const int per_xcd = std::min(compute_units(), kClusterMaxBlocks) / 8;   // (the exchange buffers are sized for 256 workgroups)
+  return std::min(kClusterMaxSlots / 8, per_xcd / std::max(groups, 1));
+}
 
 // RTPRUNE_SWEEP_STREAM_16THS = 0 .. 16 fixes the share of strips that the sweep kernels read with
 // streaming loads (for tests: a batch whose matrices exceed the memory-side cache takes seconds
@@ -334,7 +337,7 @@ void set_sinkhorn_mode(DevParams& p, const Layout& L, const rtprune_batch* in) {
   // on-chip kernels.
   const int m_top = p.dynamic ? 0 : kept_count(p.ratio, in->max_tokens), r_top = in->max_tokens - m_top;
   const bool top_fits = !p.dynamic && m_top > 0 && cluster_fits(m_top, r_top);
-  const int groups = top_fits ? cluster_groups(m_top, std::max(r_top, 1)) : kClusterMaxGroups;
+  const int groups = top_fits ? cluster_groups(m_top, std::max(r_top, 1)) : kClusterDefaultGroups;
   const int cluster = (L.sweep && f32 && cluster_slots_per_xcd(groups) > 0) ? (kModeCluster | (groups << kModeGroupsShift)) : 0;
   // The streaming kernels cost two launches per iteration whether or not an image needs them,
   // and only the device knows the sizes, so they are issued when the batch's shape and the

@@ -41,37 +41,43 @@
 
 namespace rtp {
 
-constexpr int kClusterMaxGroups = 8;                       // workgroups per cluster
+constexpr int kClusterMaxGroups = 16;                      // workgroups per cluster slot, at most
+constexpr int kClusterDefaultGroups = 8;                   // when the host cannot bound the images' sizes
 constexpr int kClusterThreads = 512;
 using ClusterShape = TeamWideA;                            // 448 rows x 128 columns per workgroup
 using ClusterShapeWide = TeamStripWide;                    // 144 rows x 576 columns per workgroup
-constexpr int kClusterMaxM = kClusterMaxGroups * ClusterShape::kMaxM;   // 3584 kept rows
-constexpr int kClusterMaxR = ClusterShape::kMaxR;
-static_assert(kClusterMaxGroups * ClusterShapeWide::kMaxM == kClusterWideRows && ClusterShapeWide::kMaxR == kClusterWideCols,
-              "the shape sinkhorn_variant assumes");
+using ClusterShapeWider = TeamStripWider;                  // 80 rows x 960 columns per workgroup
+static_assert(8 * ClusterShape::kMaxM == kClusterRows && ClusterShape::kMaxR == kClusterCols &&
+              8 * ClusterShapeWide::kMaxM == kClusterWideRows && ClusterShapeWide::kMaxR == kClusterWideCols &&
+              16 * ClusterShapeWider::kMaxM == kClusterWiderRows && ClusterShapeWider::kMaxR == kClusterWiderCols,
+              "the shapes sinkhorn_variant assumes");
 template <typename S> constexpr int cluster_part_of() { return S::TC * (S::CPT + 1); }   // values a workgroup publishes
-constexpr int kClusterPart = cluster_part_of<ClusterShapeWide>();          // 640 (144 for the 448-row strips)
-static_assert(cluster_part_of<ClusterShape>() <= kClusterPart, "exchange buffers are sized for the wider shape");
+constexpr int kClusterPart = cluster_part_of<ClusterShapeWider>();         // 1024 (640 and 144 for the other two)
+static_assert(cluster_part_of<ClusterShape>() <= kClusterPart && cluster_part_of<ClusterShapeWide>() <= kClusterPart,
+              "exchange buffers are sized for the widest shape");
 // LDS of a cluster workgroup: the waves' partial column sums (reused for the pairing's
 // candidates), their totals, the latest x per row, a flag
 template <typename S> constexpr int cluster_lds_of() {
   return (S::W * S::TC * (S::CPT + 1) + S::TC * (S::CPT + 1) + S::TR * S::RPT) * 8 + 16;
 }
-constexpr int kClusterLdsBytes = cluster_lds_of<ClusterShapeWide>() > cluster_lds_of<ClusterShape>()
-                                     ? cluster_lds_of<ClusterShapeWide>() : cluster_lds_of<ClusterShape>();
+constexpr int cluster_max(int a, int b) { return a > b ? a : b; }
+constexpr int kClusterLdsBytes = cluster_max(cluster_lds_of<ClusterShapeWider>(),
+                                             cluster_max(cluster_lds_of<ClusterShapeWide>(), cluster_lds_of<ClusterShape>()));
 constexpr int kClusterMaxSlots = 64;                       // cluster slots of a launch (8 per XCD)
 // synchronisation words, after the work lists: one arrival counter per slot, then the give-up word
 constexpr int kClusterSyncWords = kClusterMaxSlots + 1;
 static_assert(kClusterSyncWords == kWorkStreamWord, "the list builder zeroes these words (the next one is the sweep kernels')");
-static_assert(kClusterMaxM == kClusterRows && kClusterMaxR == kClusterCols, "the shape sinkhorn_variant assumes");
-constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxSlots) * 4 * kClusterMaxGroups * kClusterPart;
+// exchange buffers: four per workgroup of the launch (slots x workgroups per slot <= one per compute
+// unit: 256 at most, more than that many compute units are not put to use)
+constexpr int kClusterMaxBlocks = 256;
+constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxBlocks) * 4 * kClusterPart;
 
 struct ClusterArgs {
   SinkhornArgs S;
   const int32_t* work;      // work lists (kVariantCluster)
   int B;
   int32_t* sync;            // [kClusterSyncWords], zeroed by the kernel that built the lists
-  double* part;             // [slots][4][kClusterMaxGroups][kClusterPart] exchange buffers: two for the sums
+  double* part;             // [slots][4][groups_per_slot][kClusterPart] exchange buffers: two for the sums
                             // (by iteration parity), two for the pairing keys (by the slot's image parity)
   int slots_per_xcd;        // launch: 8 XCDs x slots_per_xcd slots x groups_per_slot workgroups
   int groups_per_slot;      // at most kClusterMaxGroups
@@ -142,6 +148,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
                                                        void* lds) {
   constexpr int TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T, LOG_TC = S::LOG_TC, W = S::W;
   constexpr int kPart = cluster_part_of<S>();               // (buffers are kClusterPart apart whatever the shape)
+  const int per_slot = C.groups_per_slot;
   static_assert(T == kClusterThreads, "workgroup shape");
   const SinkhornArgs& A = C.S;
   const DevParams& p = A.p;
@@ -219,19 +226,29 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
         xs[rslot][a] = 0.0;
         continue;
       }
-      double kd[CPT];
+      // (the widest shape widens a row's entries a second time for the column sums rather than
+      // hold 15 widened values across the row's reduction: registers)
+      constexpr bool kWidenTwice = CPT > 9;
+      double kd[kWidenTwice ? 1 : CPT];
+      double acc = 0.0;
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         forget_origin(K[a][c]);
-        kd[c] = static_cast<double>(K[a][c]);
+        const double k = static_cast<double>(K[a][c]);
+        if constexpr (!kWidenTwice) kd[c] = k;
+        acc = fma(k, y[c], acc);
       }
-      double acc = 0.0;
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) acc = fma(kd[c], y[c], acc);
       acc = group_sum<LOG_TC>(acc);
       const double xa = (rslot + TR * a < m_loc) ? rcp64(acc + row_dust) : 0.0;
 #pragma unroll
-      for (int c = 0; c < CPT; ++c) t[c] = fma(kd[c], xa, t[c]);
+      for (int c = 0; c < CPT; ++c) {
+        if constexpr (kWidenTwice) {
+          forget_origin(K[a][c]);
+          t[c] = fma(static_cast<double>(K[a][c]), xa, t[c]);
+        } else {
+          t[c] = fma(kd[c], xa, t[c]);
+        }
+      }
       t[CPT] += xa;
       xs[rslot][a] = xa;
       if (a % 2 == 1) __builtin_amdgcn_sched_barrier(0);
@@ -246,7 +263,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
     }
     __syncthreads();
     // ... published, and after the cluster has met, every workgroup's sums added in rank order
-    double* mine = part + ((it & 1) * kClusterMaxGroups + rank) * kClusterPart;
+    double* mine = part + ((it & 1) * per_slot + rank) * kClusterPart;
     for (int e = tt; e < kPart; e += T) {
       const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
       double acc = 0.0;
@@ -258,15 +275,16 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
     if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
     for (int e = tt; e < kPart; e += T) {
       const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
-      const double* all = part + (it & 1) * kClusterMaxGroups * kClusterPart + e;
+      const double* all = part + (it & 1) * per_slot * kClusterPart + e;
       // all workgroups' values requested together (from a clamped position past the last), added in rank order
-      double v[kClusterMaxGroups];
+      constexpr int kGroups = S::kMaxM >= 144 ? 8 : kClusterMaxGroups;   // as many as the shape's images can have
+      double v[kGroups];
 #pragma unroll
-      for (int g = 0; g < kClusterMaxGroups; ++g)
+      for (int g = 0; g < kGroups; ++g)
         v[g] = __hip_atomic_load(all + min(g, groups - 1) * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       double acc = 0.0;
 #pragma unroll
-      for (int g = 0; g < kClusterMaxGroups; ++g) acc += g < groups ? v[g] : 0.0;
+      for (int g = 0; g < kGroups; ++g) acc += g < groups ? v[g] : 0.0;
       // (the column's reciprocal here, once per workgroup, instead of once per row slot)
       if (c < CPT) acc = (cs + TC * c < r) ? rcp64(acc + kz * x_dust) : 0.0;
       xtot[cs][c] = acc;
@@ -313,7 +331,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   // the sums; after one more meeting the first workgroup picks the cluster's best and sets it
   // against the dustbin row.  (The cluster meets here even when no pairing is asked for: it
   // keeps a fast workgroup's next image out of the buffers a slow one is still reading.)
-  long long* mine = reinterpret_cast<long long*>(part + ((2 + (seq & 1)) * kClusterMaxGroups + rank) * kClusterPart);
+  long long* mine = reinterpret_cast<long long*>(part + ((2 + (seq & 1)) * per_slot + rank) * kClusterPart);
   if (pair_out) {
 #pragma unroll
     for (int mask = TC; mask < kWave; mask <<= 1)
@@ -346,7 +364,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   arrived += groups;
   if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
   if (pair_out && rank == 0 && tt < TC) {
-    const long long* all = reinterpret_cast<const long long*>(part + (2 + (seq & 1)) * kClusterMaxGroups * kClusterPart);
+    const long long* all = reinterpret_cast<const long long*>(part + (2 + (seq & 1)) * per_slot * kClusterPart);
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       const int j = cslot + TC * c;
@@ -375,7 +393,7 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
   if (slot_in_xcd >= C.slots_per_xcd) return;
   const int slots = 8 * C.slots_per_xcd, slot = x * C.slots_per_xcd + slot_in_xcd;
   int32_t* counter = C.sync + slot;
-  double* part = C.part + static_cast<size_t>(slot) * 4 * kClusterMaxGroups * kClusterPart;
+  double* part = C.part + static_cast<size_t>(slot) * 4 * per_slot * kClusterPart;
   const SinkhornArgs& A = C.S;
   const int count = C.work[kVariantCluster];
   int arrived = 0, seq = 0;
@@ -388,9 +406,10 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
     if (!plan_fits(A.plan_offsets[b], m, r, A.plan_cap)) continue;
     const int groups = cluster_groups(m, r);           // (at most per_slot: sinkhorn_variant has seen to it)
     if (rank < groups) {
-      const bool ok = r <= kClusterCols
-                          ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, lds)
-                          : sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, lds);
+      const int shape = cluster_shape(m, r);
+      const bool ok = shape == 0   ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, lds)
+                      : shape == 1 ? sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, lds)
+                                   : sinkhorn_cluster_image<ClusterShapeWider>(C, b, rank, groups, counter, part, arrived, seq, lds);
       if (!ok) return;
     } else {
       arrived += groups * (A.p.iters + 1);             // what the meetings it stays out of add to the count

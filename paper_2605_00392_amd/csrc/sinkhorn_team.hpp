@@ -88,6 +88,7 @@ using TeamWideC = TeamShape<8, 5, 20, 7>;   // M <= 320, R <= 224
 // A strip of a larger image in the multi-workgroup kernel (sinkhorn_cluster.hpp) when it has
 // more than 128 pruned tokens: a wave per row slot, the 64 lanes across the columns.
 using TeamStripWide = TeamShape<8, 6, 18, 9>;   // 144 rows x 576 columns per workgroup
+using TeamStripWider = TeamShape<8, 6, 10, 15>;  // 80 rows x 960 columns per workgroup
 // The one- and two-wave kernels (sinkhorn_wave.hpp): kRows augmented rows per
 // lane, kCols augmented columns.
 struct WaveShape {
@@ -133,21 +134,27 @@ constexpr long long kSweepResidentBytes = 200ll * 1000 * 1000;
 // taller matrices on chip (sinkhorn_cluster.hpp).
 // kModeSweep: the launches of the streaming multi-workgroup kernels (sinkhorn_sweep.hpp) are issued.
 constexpr int kModeLarge = 1, kModeF32 = 2, kModeCluster = 4, kModeSweep = 8;
-// bits 8-11 of `mode`: workgroups per cluster slot of the multi-workgroup kernel in this launch
-// (1 to 8); an image that would need more is not that kernel's
+// bits 8-12 of `mode`: workgroups per cluster slot of the multi-workgroup kernel in this launch
+// (1 to 16); an image that would need more is not that kernel's
 constexpr int kModeGroupsShift = 8;
-__host__ __device__ inline int mode_cluster_groups(int mode) { return (mode >> kModeGroupsShift) & 15; }
-// (that kernel's shapes: up to eight workgroups of 448 rows with at most 128 pruned tokens, or of
-// 144 rows with at most 576)
+__host__ __device__ inline int mode_cluster_groups(int mode) { return (mode >> kModeGroupsShift) & 31; }
+// (that kernel's shapes: up to eight workgroups of 448 rows with at most 128 pruned tokens, up to
+// eight of 144 rows with at most 576, up to sixteen of 80 rows with at most 960)
 constexpr int kClusterRows = 8 * 448, kClusterCols = 128;
 constexpr int kClusterWideRows = 8 * 144, kClusterWideCols = 576;
-__host__ __device__ inline bool cluster_fits(int m, int r) {
-  return (m <= kClusterRows && r <= kClusterCols) || (m <= kClusterWideRows && r <= kClusterWideCols);
+constexpr int kClusterWiderRows = 16 * 80, kClusterWiderCols = 960;
+// which of them an image takes (0, 1, 2; -1: none)
+__host__ __device__ inline int cluster_shape(int m, int r) {
+  if (m <= kClusterRows && r <= kClusterCols) return 0;
+  if (m <= kClusterWideRows && r <= kClusterWideCols) return 1;
+  if (m <= kClusterWiderRows && r <= kClusterWiderCols) return 2;
+  return -1;
 }
-// workgroups the kernel spreads such an image over: strips of 448 rows, or of 144 when it has
-// more than 128 pruned tokens
+__host__ __device__ inline bool cluster_fits(int m, int r) { return cluster_shape(m, r) >= 0; }
+// workgroups the kernel spreads such an image over
 __host__ __device__ inline int cluster_groups(int m, int r) {
-  return r <= kClusterCols ? (m + 447) / 448 : (m + 143) / 144;
+  const int shape = cluster_shape(m, r);
+  return shape == 0 ? (m + 447) / 448 : shape == 1 ? (m + 143) / 144 : (m + 79) / 80;
 }
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
 // pruned tokens.

@@ -289,6 +289,24 @@ def test_multi_workgroup_resident_sinkhorn_wide_strips_at_their_edges(override):
     assert rep.max_score_abs <= hz.SCORE_ATOL
 
 
+@pytest.mark.parametrize("override", [dict(), dict(iters=0), dict(iters=1), dict(iters=6)])
+def test_multi_workgroup_resident_sinkhorn_widest_strips_at_their_edges(override):
+    """More than 576 pruned tokens (or more than 1152 kept rows with more than 128): strips of 80
+    rows x 960 columns, up to sixteen workgroups.  Under the retention of these parameters the
+    longest image fits, so a slot has sixteen workgroups; what lies beyond the shape goes to the
+    one-workgroup general kernel."""
+    shapes = [(1238, 899), (1280, 960), (80, 960), (81, 577), (1153, 300), (1280, 129), (640, 700), (1200, 961),
+              (1281, 600), (560, 523), (700, 100)]
+    batch = _clustered([m + r for m, r in shapes], 128, "bf16", 40, **dict(dict(iters=17, ratio=1280.0 / 2240.0), **override))
+    assert batch.max_tokens == 2240                      # 1280 + 960: the retention keeps 1280 of them
+    keep = [m for m, _ in shapes]
+    s = hz.run_staged(batch, keep_counts_in=keep)
+    assert s["status"] == 0
+    rep = hz.compare_batch(batch, s, staged=True, keep_counts=keep)
+    _log(rep, f"cluster widest strips {override}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+
+
 def test_multi_workgroup_resident_sinkhorn_wide_strips_fill_the_chip():
     """A fixed retention under which the longest image takes four strips: slots of four workgroups,
     64 of them, more images than slots, through the fused call (no launches of the streaming
