@@ -1,39 +1,44 @@
 // Sinkhorn (Appendix C) for images with more kept rows than one workgroup's
-// registers hold and at most 128 pruned tokens (tiled pages pruned harder than
-// most): the kernel matrix stays on chip for all T iterations, spread over a small
+// registers hold (tiled pages pruned harder than most, the page sizes of other OCR
+// models): the kernel matrix stays on chip for all T iterations, spread over a small
 // cluster of workgroups.
 //
-// A cluster is G <= 8 workgroups; workgroup `rank` holds rows 448 rank .. 448 rank +
+// With at most 128 pruned tokens a cluster is G <= 8 workgroups; workgroup `rank` holds rows 448 rank .. 448 rank +
 // 447 of the kept x pruned kernel matrix as fp32 in its registers (the 448 x 128
 // shape of the one-workgroup kernel: 512 threads as 32 row slots x 16 column slots,
 // 14 x 8 entries per thread, widened at each use; all sums and both scalings fp64).
 // An iteration is one pass over a workgroup's rows - a row's x as soon as its sum is
 // known, then its share of every column sum - followed by the only exchange there
-// is: each workgroup publishes its 128 + 1 partial sums (columns, and the sum of its
-// x), the cluster meets at a barrier, and every workgroup adds the G partials in
-// rank order, which gives all of them the same y bit for bit.  So the matrix is read
-// from memory once per call instead of once per iteration, and an iteration costs a
-// few microseconds of barrier instead of two kernel launches.
+// is: each workgroup publishes its partial sums (columns, and the sum of its x) and
+// adds all the workgroups' partials in rank order, which gives all of them the same
+// y bit for bit.  So the matrix is read from memory once per call instead of once
+// per iteration, and an iteration costs a few microseconds of exchange instead of
+// two kernel launches.
 //
-// Images with more than 128 pruned tokens (up to 576, and up to 1152 kept rows: the
-// 1083-token pages of which 560 are kept) take strips of 144 rows instead: a wave per row
-// slot with its 64 lanes across the columns, 18 x 9 entries per thread, and 576 + 1
-// partial sums per workgroup and iteration.  A slot has as many workgroups as the
-// largest image of the launch needs (the host knows it under a fixed retention), so that
-// more slots share the chip: four for those pages, 64 of them at a time.
+// Images with more than 128 pruned tokens take other strips: 144 rows x 576 columns
+// (the 1083-token pages of which 560 are kept: four workgroups) or 80 rows x 960
+// columns (the 2137-token pages: sixteen workgroups, half an XCD), a wave per row slot
+// with its 64 lanes across the columns.  A slot has as many workgroups as the largest
+// image of the launch needs (the host knows it under a fixed retention), so that more
+// slots share the chip.
 //
-// The barrier.  The workgroups of all clusters are resident together: the kernel is
+// The exchange.  The workgroups of all slots are resident together: the kernel is
 // launched with one workgroup per compute unit and no more (each needs a CU's whole
-// register file), and a cluster slot works through its share of the image list with
-// all its workgroups in step.  A slot's workgroups have linear ids of one residue
-// modulo eight, so they share an XCD and its L2.  The exchanged values and the
-// arrival counter are device-scope atomics with relaxed ordering; a workgroup waits
-// for its own stores to complete (a workgroup-scope release: no cache write-back)
-// before one thread counts it in.  Measured: 3.5 to 4.3 us per barrier with eight
-// workgroups, against 6 to 17 us with device-scope fences, whose cache write-backs
-// queue up behind each other.  Every wait is bounded: a workgroup that has polled
-// `spin_limit` times without seeing its cluster complete sets the give-up word, on
-// which all workgroups leave, and RTP_DEV_SYNC_TIMEOUT in the status word.
+// register file), and a slot works through its share of the image list with all its
+// workgroups in step.  A slot's workgroups have linear ids of one residue modulo
+// eight, so they share an XCD and its L2.  Sums travel as device-scope atomics with
+// relaxed ordering, and a sum's place holds a "not yet" pattern until the sum is
+// there: a reader polls the places it reads, so an iteration needs neither an arrival
+// counter nor a barrier across workgroups (with them it took 3.5 to 4.3 us more per
+// iteration; with device-scope fences, whose cache write-backs queue up behind each
+// other, 6 to 17 us).  The places are in four buffers used in turn; sinkhorn_cluster_image
+// says why the buffer two iterations back can be given its "not yet" again.  Between
+// images, and before the first, all of a slot's workgroups put "not yet" into all
+// their places and meet at an arrival counter (a workgroup waits until its stores
+// have been acknowledged before it arrives: a workgroup-scope release alone does not
+// wait for that).  Every wait is bounded: a workgroup that has polled `spin_limit`
+// times in vain sets the give-up word, on which all workgroups leave, and
+// RTP_DEV_SYNC_TIMEOUT in the status word.
 #pragma once
 #include "common.hpp"
 #include "sinkhorn_team.hpp"
@@ -67,18 +72,22 @@ constexpr int kClusterMaxSlots = 64;                       // cluster slots of a
 // synchronisation words, after the work lists: one arrival counter per slot, then the give-up word
 constexpr int kClusterSyncWords = kClusterMaxSlots + 1;
 static_assert(kClusterSyncWords == kWorkStreamWord, "the list builder zeroes these words (the next one is the sweep kernels')");
-// exchange buffers: four per workgroup of the launch (slots x workgroups per slot <= one per compute
+// exchange buffers: six per workgroup of the launch (slots x workgroups per slot <= one per compute
 // unit: 256 at most, more than that many compute units are not put to use)
 constexpr int kClusterMaxBlocks = 256;
-constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxBlocks) * 4 * kClusterPart;
+constexpr int kClusterSumBufs = 4, kClusterKeyBufs = 2, kClusterBufs = kClusterSumBufs + kClusterKeyBufs;
+constexpr size_t kClusterPartDoubles = static_cast<size_t>(kClusterMaxBlocks) * kClusterBufs * kClusterPart;
+// what a partial sum's place holds until the sum has been published: no sum has this bit pattern (a NaN)
+constexpr long long kClusterNotYet = -1;
 
 struct ClusterArgs {
   SinkhornArgs S;
   const int32_t* work;      // work lists (kVariantCluster)
   int B;
   int32_t* sync;            // [kClusterSyncWords], zeroed by the kernel that built the lists
-  double* part;             // [slots][4][groups_per_slot][kClusterPart] exchange buffers: two for the sums
-                            // (by iteration parity), two for the pairing keys (by the slot's image parity)
+  double* part;             // [slots][6][groups_per_slot][kClusterPart] exchange buffers: four for the sums
+                            // (by the slot's iteration count modulo four), two for the pairing keys (by the
+                            // slot's image parity)
   int slots_per_xcd;        // launch: 8 XCDs x slots_per_xcd slots x groups_per_slot workgroups
   int groups_per_slot;      // at most kClusterMaxGroups
   int spin_limit;
@@ -145,7 +154,7 @@ __device__ __forceinline__ bool cluster_wait(int32_t* counter, int32_t* gave_up,
 template <typename S>
 __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int b, int rank, int groups,
                                                        int32_t* counter, double* part, int& arrived, int seq,
-                                                       void* lds) {
+                                                       int& gi, void* lds) {
   constexpr int TC = S::TC, TR = S::TR, RPT = S::RPT, CPT = S::CPT, T = S::T, LOG_TC = S::LOG_TC, W = S::W;
   constexpr int kPart = cluster_part_of<S>();               // (buffers are kClusterPart apart whatever the shape)
   const int per_slot = C.groups_per_slot;
@@ -261,27 +270,52 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
 #pragma unroll
       for (int c = 0; c <= CPT; ++c) xw[tw][lane][c] = t[c];
     }
+    int& seen_all = (&s_flag)[1 + (it & 1)];           // (two words in turn: the next write of one is a whole iteration away)
+    if (tt == 0) seen_all = 1;
     __syncthreads();
-    // ... published, and after the cluster has met, every workgroup's sums added in rank order
-    double* mine = part + ((it & 1) * per_slot + rank) * kClusterPart;
-    for (int e = tt; e < kPart; e += T) {
-      const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
-      double acc = 0.0;
+    // ... published; every workgroup then adds all the workgroups' sums in rank order.  A sum's
+    // place holds kClusterNotYet until the sum is there, so the readers need no word that says
+    // "all are out" and no barrier: each polls the places it reads.  Four buffers in turn, by the
+    // slot's iteration count: a workgroup that publishes iteration i has seen everybody's sums of
+    // iteration i - 1, whose owners had by then finished reading iteration i - 2, so the buffer of
+    // i - 2 (= i + 2 modulo four) is free and gets its "not yet" back now; that store is
+    // acknowledged (the wait below, one iteration later) before the sums of iteration i + 1 go
+    // out, and nobody looks at the buffer of i + 2 before having seen those.
+    __builtin_amdgcn_s_waitcnt(0);
+    {
+      double* mine = part + ((gi & 3) * per_slot + rank) * kClusterPart;
+      long long* ahead = reinterpret_cast<long long*>(part + (((gi + 2) & 3) * per_slot + rank) * kClusterPart);
+      for (int e = tt; e < kPart; e += T) {
+        const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
+        double acc = 0.0;
 #pragma unroll
-      for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
-      __hip_atomic_store(mine + e, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int w = 0; w < W; ++w) acc += xw[w][cs][c];
+        __hip_atomic_store(ahead + e, kClusterNotYet, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + e, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
-    arrived += groups;
-    if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
+    bool seen = true;
     for (int e = tt; e < kPart; e += T) {
       const int cs = e / (CPT + 1), c = e - cs * (CPT + 1);
-      const double* all = part + (it & 1) * per_slot * kClusterPart + e;
+      const double* all = part + (gi & 3) * per_slot * kClusterPart + e;
       // all workgroups' values requested together (from a clamped position past the last), added in rank order
       constexpr int kGroups = S::kMaxM >= 144 ? 8 : kClusterMaxGroups;   // as many as the shape's images can have
       double v[kGroups];
+      for (int spin = 0;; ++spin) {
+        bool ready = true;
 #pragma unroll
-      for (int g = 0; g < kGroups; ++g)
-        v[g] = __hip_atomic_load(all + min(g, groups - 1) * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int g = 0; g < kGroups; ++g)
+          v[g] = __hip_atomic_load(all + min(g, groups - 1) * kClusterPart, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) ready = ready && __double_as_longlong(v[g]) != kClusterNotYet;
+        if (ready) break;
+        if (spin >= C.spin_limit ||
+            ((spin & 63) == 63 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          seen = false;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
       double acc = 0.0;
 #pragma unroll
       for (int g = 0; g < kGroups; ++g) acc += g < groups ? v[g] : 0.0;
@@ -289,7 +323,16 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
       if (c < CPT) acc = (cs + TC * c < r) ? rcp64(acc + kz * x_dust) : 0.0;
       xtot[cs][c] = acc;
     }
+    if (!seen) seen_all = 0;
+    ++gi;
     __syncthreads();
+    if (!seen_all) {                                   // a wait was given up (here or elsewhere): everybody leaves
+      if (tt == 0) {
+        __hip_atomic_store(gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        atomicOr(C.status, RTP_DEV_SYNC_TIMEOUT);
+      }
+      return false;
+    }
 #pragma unroll
     for (int c = 0; c <= CPT; ++c) t[c] = xtot[cslot][c];
     double ly = 0.0;
@@ -331,7 +374,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   // the sums; after one more meeting the first workgroup picks the cluster's best and sets it
   // against the dustbin row.  (The cluster meets here even when no pairing is asked for: it
   // keeps a fast workgroup's next image out of the buffers a slow one is still reading.)
-  long long* mine = reinterpret_cast<long long*>(part + ((2 + (seq & 1)) * per_slot + rank) * kClusterPart);
+  long long* mine = reinterpret_cast<long long*>(part + ((kClusterSumBufs + (seq & 1)) * per_slot + rank) * kClusterPart);
   if (pair_out) {
 #pragma unroll
     for (int mask = TC; mask < kWave; mask <<= 1)
@@ -364,7 +407,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   arrived += groups;
   if (!cluster_meet(counter, gave_up, arrived, C.spin_limit, C.status, &s_flag)) return false;
   if (pair_out && rank == 0 && tt < TC) {
-    const long long* all = reinterpret_cast<const long long*>(part + (2 + (seq & 1)) * per_slot * kClusterPart);
+    const long long* all = reinterpret_cast<const long long*>(part + (kClusterSumBufs + (seq & 1)) * per_slot * kClusterPart);
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       const int j = cslot + TC * c;
@@ -384,8 +427,26 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   return true;
 }
 
+// "Not yet" into this workgroup's places of the slot's four buffers of sums, then a meeting of
+// all the slot's workgroups: after it no place of the slot holds an old sum.
+__device__ __forceinline__ bool cluster_clear(const ClusterArgs& C, int rank, int32_t* counter, double* part,
+                                              int& arrived, int* s_flag) {
+  const int per_slot = C.groups_per_slot;
+  for (int buf = 0; buf < kClusterSumBufs; ++buf) {
+    long long* mine = reinterpret_cast<long long*>(part + (buf * per_slot + rank) * kClusterPart);
+    for (int e = threadIdx.x; e < kClusterPart; e += kClusterThreads)
+      __hip_atomic_store(mine + e, kClusterNotYet, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  arrived += per_slot;
+  return cluster_meet(counter, C.sync + kClusterMaxSlots, arrived, C.spin_limit, C.status, s_flag);
+}
+
 // Workgroup `block` of the cluster part of the launch: 8 XCDs x slots_per_xcd slots x
-// groups_per_slot workgroups; slot s takes images s, s + slots, ... of the list.
+// groups_per_slot workgroups; slot s takes images s, s + slots, ... of the list.  The slot's
+// arrival counter runs on through all its meetings: one of all its workgroups before the first
+// image (the buffers of sums cleared), one of an image's workgroups at the image's end (the
+// pairing keys out; the others wait for it without arriving), one of all again before the next
+// image (the buffers cleared again, also by those that had no strip: they may have one next).
 __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int block, void* lds) {
   const int x = block & 7, local = block >> 3;
   const int per_slot = C.groups_per_slot;
@@ -393,10 +454,13 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
   if (slot_in_xcd >= C.slots_per_xcd) return;
   const int slots = 8 * C.slots_per_xcd, slot = x * C.slots_per_xcd + slot_in_xcd;
   int32_t* counter = C.sync + slot;
-  double* part = C.part + static_cast<size_t>(slot) * 4 * per_slot * kClusterPart;
+  double* part = C.part + static_cast<size_t>(slot) * kClusterBufs * per_slot * kClusterPart;
   const SinkhornArgs& A = C.S;
   const int count = C.work[kVariantCluster];
-  int arrived = 0, seq = 0;
+  if (slot >= count) return;                           // (the same for all the slot's workgroups)
+  int* flag = reinterpret_cast<int*>(static_cast<unsigned char*>(lds) + kClusterLdsBytes - 16);
+  int arrived = 0, seq = 0, gi = 0;
+  if (!cluster_clear(C, rank, counter, part, arrived, flag)) return;
   for (int k = slot; k < count; k += slots, ++seq) {
     const int b = C.work[kWorkLists + kVariantCluster * C.B + k];
     const int n = A.offsets[b + 1] - A.offsets[b];
@@ -405,18 +469,20 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
     if (m <= 0 || r <= 0 || sinkhorn_variant(m, r, A.p.mode) != kVariantCluster) continue;
     if (!plan_fits(A.plan_offsets[b], m, r, A.plan_cap)) continue;
     const int groups = cluster_groups(m, r);           // (at most per_slot: sinkhorn_variant has seen to it)
+    const bool last = k + slots >= count;
     if (rank < groups) {
       const int shape = cluster_shape(m, r);
-      const bool ok = shape == 0   ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, lds)
-                      : shape == 1 ? sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, lds)
-                                   : sinkhorn_cluster_image<ClusterShapeWider>(C, b, rank, groups, counter, part, arrived, seq, lds);
+      const bool ok = shape == 0   ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
+                      : shape == 1 ? sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
+                                   : sinkhorn_cluster_image<ClusterShapeWider>(C, b, rank, groups, counter, part, arrived, seq, gi, lds);
       if (!ok) return;
     } else {
-      arrived += groups * (A.p.iters + 1);             // what the meetings it stays out of add to the count
-      if (k + slots >= count) return;                  // the slot's last image: nothing to wait for, the CU is free
-      int* flag = reinterpret_cast<int*>(static_cast<unsigned char*>(lds) + kClusterLdsBytes - 16);
+      arrived += groups;                               // what the image's meeting, which it stays out of, adds to the count
+      gi += A.p.iters;
+      if (last) return;                                // nothing to wait for: the CU is free for others
       if (!cluster_wait(counter, C.sync + kClusterMaxSlots, arrived, C.spin_limit, C.status, flag)) return;
     }
+    if (!last && !cluster_clear(C, rank, counter, part, arrived, flag)) return;
   }
 }
 
