@@ -7,6 +7,8 @@
 // 447 of the kept x pruned kernel matrix as fp32 in its registers (the 448 x 128
 // shape of the one-workgroup kernel: 512 threads as 32 row slots x 16 column slots,
 // 14 x 8 entries per thread, widened at each use; all sums and both scalings fp64).
+// (Strips of 224 rows, 7 x 8 entries per thread, while eight of them cover the image: half the
+// arithmetic per workgroup and iteration for the same exchange.)
 // An iteration is one pass over a workgroup's rows - a row's x as soon as its sum is
 // known, then its share of every column sum - followed by the only exchange there
 // is: each workgroup publishes its partial sums (columns, and the sum of its x) and
@@ -50,9 +52,11 @@ constexpr int kClusterMaxGroups = 16;                      // workgroups per clu
 constexpr int kClusterDefaultGroups = 8;                   // when the host cannot bound the images' sizes
 constexpr int kClusterThreads = 512;
 using ClusterShape = TeamWideA;                            // 448 rows x 128 columns per workgroup
+using ClusterShapeHalf = TeamShape<8, 4, 7, 8>;            // 224 rows x 128 columns per workgroup
 using ClusterShapeWide = TeamStripWide;                    // 144 rows x 576 columns per workgroup
 using ClusterShapeWider = TeamStripWider;                  // 80 rows x 960 columns per workgroup
 static_assert(8 * ClusterShape::kMaxM == kClusterRows && ClusterShape::kMaxR == kClusterCols &&
+              8 * ClusterShapeHalf::kMaxM == kClusterHalfRows && ClusterShapeHalf::kMaxR == kClusterCols &&
               8 * ClusterShapeWide::kMaxM == kClusterWideRows && ClusterShapeWide::kMaxR == kClusterWideCols &&
               16 * ClusterShapeWider::kMaxM == kClusterWiderRows && ClusterShapeWider::kMaxR == kClusterWiderCols,
               "the shapes sinkhorn_variant assumes");
@@ -472,7 +476,8 @@ __device__ __forceinline__ void sinkhorn_cluster_block(const ClusterArgs& C, int
     const bool last = k + slots >= count;
     if (rank < groups) {
       const int shape = cluster_shape(m, r);
-      const bool ok = shape == 0   ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
+      const bool ok = shape == 0   ? sinkhorn_cluster_image<ClusterShapeHalf>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
+                      : shape == 3 ? sinkhorn_cluster_image<ClusterShape>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
                       : shape == 1 ? sinkhorn_cluster_image<ClusterShapeWide>(C, b, rank, groups, counter, part, arrived, seq, gi, lds)
                                    : sinkhorn_cluster_image<ClusterShapeWider>(C, b, rank, groups, counter, part, arrived, seq, gi, lds);
       if (!ok) return;

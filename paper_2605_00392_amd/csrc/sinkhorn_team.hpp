@@ -138,14 +138,18 @@ constexpr int kModeLarge = 1, kModeF32 = 2, kModeCluster = 4, kModeSweep = 8;
 // (1 to 16); an image that would need more is not that kernel's
 constexpr int kModeGroupsShift = 8;
 __host__ __device__ inline int mode_cluster_groups(int mode) { return (mode >> kModeGroupsShift) & 31; }
-// (that kernel's shapes: up to eight workgroups of 448 rows with at most 128 pruned tokens, up to
-// eight of 144 rows with at most 576, up to sixteen of 80 rows with at most 960)
+// (that kernel's shapes: up to eight workgroups of 224 or 448 rows with at most 128 pruned tokens,
+// up to eight of 144 rows with at most 576, up to sixteen of 80 rows with at most 960)
 constexpr int kClusterRows = 8 * 448, kClusterCols = 128;
+constexpr int kClusterHalfRows = 8 * 224;
 constexpr int kClusterWideRows = 8 * 144, kClusterWideCols = 576;
 constexpr int kClusterWiderRows = 16 * 80, kClusterWiderCols = 960;
-// which of them an image takes (0, 1, 2; -1: none)
+// which of them an image takes (0 .. 3; -1: none).  With at most 128 pruned tokens the strips are
+// 224 rows high while eight of them cover the image (half the arithmetic per workgroup and
+// iteration for the same exchange), else 448.
 __host__ __device__ inline int cluster_shape(int m, int r) {
-  if (m <= kClusterRows && r <= kClusterCols) return 0;
+  if (m <= kClusterHalfRows && r <= kClusterCols) return 0;
+  if (m <= kClusterRows && r <= kClusterCols) return 3;
   if (m <= kClusterWideRows && r <= kClusterWideCols) return 1;
   if (m <= kClusterWiderRows && r <= kClusterWiderCols) return 2;
   return -1;
@@ -154,7 +158,7 @@ __host__ __device__ inline bool cluster_fits(int m, int r) { return cluster_shap
 // workgroups the kernel spreads such an image over
 __host__ __device__ inline int cluster_groups(int m, int r) {
   const int shape = cluster_shape(m, r);
-  return shape == 0 ? (m + 447) / 448 : shape == 1 ? (m + 143) / 144 : (m + 79) / 80;
+  return shape == 0 ? (m + 223) / 224 : shape == 3 ? (m + 447) / 448 : shape == 1 ? (m + 143) / 144 : (m + 79) / 80;
 }
 // The multi-workgroup sweep kernels (sinkhorn_sweep.hpp) take up to this many
 // pruned tokens.

@@ -259,11 +259,11 @@ def test_tall_register_shapes_at_their_edges():
 def test_multi_workgroup_resident_sinkhorn_at_its_edges(override):
     """At most 128 pruned tokens and more rows than the one-workgroup shapes of a large-image batch
     take: the kernel that keeps the matrix on chip
-    across a cluster of workgroups (448 rows each, up to eight), on both sides of its limits and of
-    its row strips; with eps = 0.02 exp's range does not fit fp32 and the streaming kernels take
+    across a cluster of workgroups (224 rows each while eight cover the image, else 448), on both
+    sides of its limits and of its row strips; with eps = 0.02 exp's range does not fit fp32 and the streaming kernels take
     them all.  An odd and an even iteration count (the exchange buffers alternate)."""
     shapes = [(513, 100), (896, 128), (897, 128), (896, 129), (1300, 40), (600, 65), (1217, 64), (1216, 64),
-              (449, 127), (3584, 128), (3585, 100), (2000, 17)]
+              (449, 127), (3584, 128), (3585, 100), (2000, 17), (1792, 128), (1793, 100), (673, 90), (672, 128)]
     batch = _clustered([m + r for m, r in shapes], 128, "bf16", 35, **dict(dict(iters=40), **override))
     keep = [m for m, _ in shapes]
     s = hz.run_staged(batch, keep_counts_in=keep)
