@@ -61,8 +61,9 @@ static_assert(8 * ClusterShape::kMaxM == kClusterRows && ClusterShape::kMaxR == 
               16 * ClusterShapeWider::kMaxM == kClusterWiderRows && ClusterShapeWider::kMaxR == kClusterWiderCols,
               "the shapes sinkhorn_variant assumes");
 template <typename S> constexpr int cluster_part_of() { return S::TC * (S::CPT + 1); }   // values a workgroup publishes
-constexpr int kClusterPart = cluster_part_of<ClusterShapeWider>();         // 1024 (640 and 144 for the other two)
-static_assert(cluster_part_of<ClusterShape>() <= kClusterPart && cluster_part_of<ClusterShapeWide>() <= kClusterPart,
+constexpr int kClusterPart = cluster_part_of<ClusterShapeWider>();         // 1024 (640 and 144 for the others)
+static_assert(cluster_part_of<ClusterShape>() <= kClusterPart && cluster_part_of<ClusterShapeWide>() <= kClusterPart &&
+                  cluster_part_of<ClusterShapeHalf>() <= kClusterPart,
               "exchange buffers are sized for the widest shape");
 // LDS of a cluster workgroup: the waves' partial column sums (reused for the pairing's
 // candidates), their totals, the latest x per row, a flag
@@ -104,9 +105,7 @@ __device__ __forceinline__ bool cluster_meet(int32_t* counter, int32_t* gave_up,
                                              int32_t* status, int* s_flag) {
   // This thread's published values must have reached the L2 before anybody is told that the
   // workgroup has arrived.  A workgroup-scope release does not wait for stores to be acknowledged
-  // (waves of a workgroup share their caches), so wait for the store counter explicitly; found
-  // with 640 values per workgroup, where the last stores are issued just before this point and
-  // another workgroup read the previous iteration's sums.
+  // (waves of a workgroup share their caches), so the store counter is waited for explicitly.
   __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
@@ -176,7 +175,7 @@ __device__ __forceinline__ bool sinkhorn_cluster_image(const ClusterArgs& C, int
   int32_t* __restrict__ pair_out = A.pair_out;
   int32_t* gave_up = C.sync + kClusterMaxSlots;
   const int row_base = rank * S::kMaxM;                      // this workgroup's first row
-  const int m_loc = min(max(m - row_base, 0), S::kMaxM);     // rows it holds (>= 1: groups = ceil(m / 448))
+  const int m_loc = min(max(m - row_base, 0), S::kMaxM);     // rows it holds (>= 1: groups = ceil(m / rows per strip))
   if (pair_out)
     for (int i = tt; i < m_loc; i += T) pair_out[lo + row_base + i] = row_base + i;
 
