@@ -1,7 +1,8 @@
 """rtprune_prune_static, the variant of rtprune_prune that brings its own workspace (a fixed
 array inside the library's device image) for callers that cannot allocate: its outputs must
 equal rtprune_prune's bit for bit (same kernels), on calls in a row that reuse the array,
-the later ones on smaller inputs, and a batch beyond the array must be refused."""
+the later ones on smaller inputs, a batch beyond the array must be refused, and the call
+recorded into a HIP graph must give the same on every replay."""
 import numpy as np
 import pytest
 
@@ -83,3 +84,41 @@ def test_static_scratch_variant_refuses_a_batch_beyond_its_array():
     torch.cuda.synchronize()
     assert rc == rt.RTP_EWORKSPACE
     assert (out_off.cpu().numpy() == -7).all()                        # nothing was enqueued
+
+
+def test_static_scratch_variant_replays_from_a_captured_graph():
+    # the callers this entry point is for: the whole call recorded into a HIP graph once,
+    # then replayed, with the program's own eager work and waits between the replays;
+    # every replay must give what the eager call gives
+    batch = synth.gen_batch(3, images=range(24))
+    other = synth.gen_batch(2, images=range(4))
+    ref = hz.run_prune(batch)
+    assert ref["rc"] == 0 and ref["status"] == 0
+    device = "cuda:0"
+    p = rt.make_params(batch.params)
+    db = rt.upload(batch, device)
+    B, total = db.B, db.total_tokens
+    out = torch.zeros((total, db.D), dtype=db.tokens.dtype, device=device)
+    out_off = torch.zeros((B + 1,), dtype=torch.int32, device=device)
+    keep = torch.zeros((B,), dtype=torch.int32, device=device)
+    sel = torch.zeros((total,), dtype=torch.int32, device=device)
+    pair = torch.zeros((total,), dtype=torch.int32, device=device)
+    ratio = torch.zeros((B,), dtype=torch.float32, device=device)
+    dens = torch.from_numpy(np.ascontiguousarray(batch.density, dtype=np.float32)).to(device)
+    outs = (out, out_off, keep, sel, pair, ratio)
+    assert _run_static(batch)["rc"] == rt.RTP_OK          # first call on the device: set-up done
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rc = rt.rtprune_prune_static(db, dens, p, *outs)  # on the capturing (current) stream
+    assert rc == rt.RTP_OK
+    for replay in range(3):
+        print(f"graph replay {replay}", flush=True)
+        for t in outs:                                    # fill kernels, not memset nodes;
+            t.fill_(0 if t is out else -7)                # rows past the packed end stay as filled
+        _same(_run_static(other), hz.run_prune(other), "eager call between replays")
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dict(out=hz._np(out), out_offsets=hz._np(out_off), keep=hz._np(keep),
+                   sel=hz._np(sel), pair=hz._np(pair), ratio=hz._np(ratio))
+        _same(got, ref, f"replay {replay}")
