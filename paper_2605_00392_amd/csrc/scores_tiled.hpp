@@ -30,7 +30,6 @@ constexpr int kTileCols = 64;          // pruned rows per workgroup tile
 constexpr int kTileStep = 64;          // contraction elements per step (128 bytes per row)
 constexpr int kTilePitch = 144;        // LDS bytes per staged row
 constexpr int kTiledThreads = 256;
-constexpr int kTiledChain = 1;         // steps (of two 32-term partial products each) between fp64 flushes
 
 __host__ __device__ inline bool score_is_tiled(int r) { return r > kTiledMinPruned; }
 
@@ -102,31 +101,42 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // the next step's rows are requested from memory before this step's arithmetic
   // and go to the other LDS buffer after it
   const int steps = D / kTileStep;                   // even: D is a multiple of 128 on this path
-  uint4 sa[QA], sb[QB];
+  // (named registers, not arrays: an array that lives across the step loop can end up in
+  // LDS, with a wait for the rows right behind their request)
+  static_assert(QA == 4 && QB == 2, "the staging below is written out for these counts");
+  uint4 sa0, sa1, sa2, sa3, sb0, sb1;
   auto fetch = [&](int k0) {
-#pragma unroll
-    for (int q = 0; q < QA; ++q) sa[q] = *reinterpret_cast<const uint4*>(aptr[q] + k0);
-#pragma unroll
-    for (int q = 0; q < QB; ++q) sb[q] = *reinterpret_cast<const uint4*>(bptr[q] + k0);
+    sa0 = *reinterpret_cast<const uint4*>(aptr[0] + k0);
+    sa1 = *reinterpret_cast<const uint4*>(aptr[1] + k0);
+    sa2 = *reinterpret_cast<const uint4*>(aptr[2] + k0);
+    sa3 = *reinterpret_cast<const uint4*>(aptr[3] + k0);
+    sb0 = *reinterpret_cast<const uint4*>(bptr[0] + k0);
+    sb1 = *reinterpret_cast<const uint4*>(bptr[1] + k0);
   };
+  const int stage_off = srow * kTilePitch + 16 * piece;
   auto stage = [&](int buf) {
-#pragma unroll
-    for (int q = 0; q < QA; ++q)
-      *reinterpret_cast<uint4*>(&lds_a[buf][(srow + 32 * q) * kTilePitch + 16 * piece]) = sa[q];
-#pragma unroll
-    for (int q = 0; q < QB; ++q)
-      *reinterpret_cast<uint4*>(&lds_b[buf][(srow + 32 * q) * kTilePitch + 16 * piece]) = sb[q];
+    unsigned char* a = &lds_a[buf][stage_off];
+    unsigned char* b = &lds_b[buf][stage_off];
+    *reinterpret_cast<uint4*>(a) = sa0;
+    *reinterpret_cast<uint4*>(a + 32 * kTilePitch) = sa1;
+    *reinterpret_cast<uint4*>(a + 64 * kTilePitch) = sa2;
+    *reinterpret_cast<uint4*>(a + 96 * kTilePitch) = sa3;
+    *reinterpret_cast<uint4*>(b) = sb0;
+    *reinterpret_cast<uint4*>(b + 32 * kTilePitch) = sb1;
   };
 
-  // fp64 sums of the flushed partials and the fp32 accumulators of the matrix
-  // instructions between two flushes
+  // fp64 sums of the flushed partials, and two sets of fp32 accumulators for the matrix
+  // instructions: while a step's instructions fill one set, the previous step's partials
+  // leave the other for the fp64 sums, so that the vector unit's conversions and additions
+  // run under the matrix unit's work instead of after it
   double acc[4][2][4];
-  floatx4_t part[4][2];
+  floatx4_t part0[4][2], part1[4][2];
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      part[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      part0[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      part1[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc[t][u][v] = 0.0;
     }
@@ -135,9 +145,14 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // at row l % 16, elements 16 (l / 16) + 8 h .. + 7 of the step - the same
   // assignment of contraction elements to lanes for both operands
   const int frag_off = (lane & 15) * kTilePitch + 32 * (lane >> 4);
-  auto compute = [&](int buf) {
-    const unsigned char* A = &lds_a[buf][wm * 64 * kTilePitch + frag_off];
-    const unsigned char* B = &lds_b[buf][wn * 32 * kTilePitch + frag_off];
+  const unsigned char* frag_a = &lds_a[0][wm * 64 * kTilePitch + frag_off];
+  const unsigned char* frag_b = &lds_b[0][wn * 32 * kTilePitch + frag_off];
+  // one step: the two matrix instructions per 16 x 16 tile of the wave, the first on a zero
+  // accumulator, into `now`; and `before`, the previous step's partials, added to the sums
+  auto step = [&](int buf, floatx4_t (&now)[4][2], const floatx4_t (&before)[4][2]) {
+    const unsigned char* A = frag_a + buf * (kTileRows * kTilePitch);
+    const unsigned char* B = frag_b + buf * (kTileCols * kTilePitch);
+    const floatx4_t zero{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       uint4 fa[4], fb[2];
@@ -149,32 +164,46 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-          part[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8_t, fa[t]), __builtin_bit_cast(bf16x8_t, fb[u]), part[t][u], 0, 0, 0);
+          now[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, fa[t]), __builtin_bit_cast(bf16x8_t, fb[u]),
+              h == 0 ? zero : now[t][u], 0, 0, 0);
     }
-  };
-  auto flush = [&]() {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(part[t][u][v]);
-        part[t][u] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-      }
+        for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(before[t][u][v]);
   };
 
+  // The next step's rows are requested before this step's arithmetic and go to the other
+  // LDS buffer after it (the last step asks for its own rows again, so that the requests
+  // and the staging are the same instructions in every step and the compiler keeps the
+  // rows in registers); the barriers for the instruction scheduler keep the requests ahead
+  // of the arithmetic and the staging behind it.
   fetch(0);
   stage(0);
   __syncthreads();
-  for (int s = 0; s < steps; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < steps) fetch((s + 1) * kTileStep);   // in flight during this step's arithmetic
-    compute(buf);
-    if ((s + 1) % kTiledChain == 0 || s + 1 == steps) flush();
-    if (s + 1 < steps) stage(buf ^ 1);               // the other buffer: nobody reads it during this step
+  for (int s = 0; s < steps; s += 2) {                // steps is even
+    fetch((s + 1) * kTileStep);
+    __builtin_amdgcn_sched_barrier(0);
+    step(0, part0, part1);
+    __builtin_amdgcn_sched_barrier(0);
+    stage(1);
+    __syncthreads();
+    fetch(min(s + 2, steps - 1) * kTileStep);
+    __builtin_amdgcn_sched_barrier(0);
+    step(1, part1, part0);
+    __builtin_amdgcn_sched_barrier(0);
+    stage(0);
     __syncthreads();
   }
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(part1[t][u][v]);
 
   // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile.
   // Reciprocal norms once per row and column; exp through the fp32 unit when K is
@@ -221,7 +250,7 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
 
 // One workgroup per (tile, image): for calls whose images are known to be large
 // (the hardware hands out workgroups as CUs come free, which balances best).
-__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(ScoresTiledArgs A, const int32_t* __restrict__ status) {
+__global__ __launch_bounds__(kTiledThreads, 2) void k_scores_tiled(ScoresTiledArgs A, const int32_t* __restrict__ status) {
   if (status[0]) return;
   scores_tile(A, blockIdx.y, blockIdx.x);
 }
@@ -230,7 +259,7 @@ __global__ __launch_bounds__(kTiledThreads) void k_scores_tiled(ScoresTiledArgs 
 // work list: for calls that may well have no such image (kept counts decided on
 // the device), where a grid sized for the worst case would cost more to launch
 // empty than the rest of the call's small kernels together.
-__global__ __launch_bounds__(kTiledThreads) void k_scores_tiled_list(ScoresTiledArgs A, int tiles,
+__global__ __launch_bounds__(kTiledThreads, 2) void k_scores_tiled_list(ScoresTiledArgs A, int tiles,
                                                                     const int32_t* __restrict__ work, int B,
                                                                     const int32_t* __restrict__ status) {
   if (status[0]) return;
