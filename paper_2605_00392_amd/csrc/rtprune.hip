@@ -410,7 +410,10 @@ int launch_scores_t(const rtprune_batch* in, const DevParams& p, const int32_t* 
       // the call can produce: the caller's bound, else what the retention clamp allows
       const int rmax = pruned_bound(in, p, max_pruned_hint);
       if (rmax > kTiledMinPruned) {
-        const int tiles_m = (in->max_tokens + kTileRows - 1) / kTileRows;
+        // kept rows an image can have: what the fixed retention leaves of the longest one when
+        // this call selected under it (then it also passed a bound), else all of its tokens
+        const int mmax = (max_pruned_hint >= 0 && !p.dynamic) ? kept_count(p.ratio, in->max_tokens) : in->max_tokens;
+        const int tiles_m = (std::max(mmax, 1) + kTileRows - 1) / kTileRows;
         const int tiles_n = (rmax + kTileCols - 1) / kTileCols;
         const int tiles = tiles_m * tiles_n;
         const ScoresTiledArgs TA{tok, in->offsets, in->D, sel, keep, plan_off, sq, p, kmat, L.plan_cap, scores_out,

@@ -82,9 +82,11 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
 
   __shared__ __attribute__((aligned(16))) unsigned char lds_a[2][kTileRows * kTilePitch];   // [buffer]
   __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kTileCols * kTilePitch];
+  __shared__ double rnorm[kTileRows + kTileCols];    // reciprocal norms of the tile's rows and columns
 
   // staging: thread t moves piece t % 8 (16 bytes) of rows t / 8 + 32 q of each operand
   constexpr int QA = kTileRows / 32, QB = kTileCols / 32;
+  static_assert(QA == 4 && QB == 2, "the staging below is written out for these counts");
   const int piece = tid & 7, srow = tid >> 3;
   const bf16_t* aptr[QA];
   const bf16_t* bptr[QB];
@@ -98,32 +100,41 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
     const int j = min(j0 + srow + 32 * q, r - 1);
     bptr[q] = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j], n)) * D + 8 * piece;
   }
-  // the next step's rows are requested from memory before this step's arithmetic
-  // and go to the other LDS buffer after it
+  // the reciprocal norms the last part needs, fetched now (two dependent loads) instead of
+  // when every wave waits for them
+  if (tid < kTileRows + kTileCols) {
+    const int at = tid < kTileRows ? min(i0 + tid, m - 1) : m + min(j0 + tid - kTileRows, r - 1);
+    rnorm[tid] = 1.0 / fmax(norm64[lo + clamp_index(sel[at], n)], kTinyNorm);
+  }
+
+  // Rows are requested two steps before their arithmetic (a step is shorter than a trip to
+  // memory that misses the L2) into one of two sets of registers, and go to the LDS buffer
+  // that the previous step has finished with.  Named registers, not arrays or structs: an
+  // array that lives across the step loop can end up in LDS, with a wait for the rows
+  // right behind their request.
   const int steps = D / kTileStep;                   // even: D is a multiple of 128 on this path
-  // (named registers, not arrays: an array that lives across the step loop can end up in
-  // LDS, with a wait for the rows right behind their request)
-  static_assert(QA == 4 && QB == 2, "the staging below is written out for these counts");
-  uint4 sa0, sa1, sa2, sa3, sb0, sb1;
-  auto fetch = [&](int k0) {
-    sa0 = *reinterpret_cast<const uint4*>(aptr[0] + k0);
-    sa1 = *reinterpret_cast<const uint4*>(aptr[1] + k0);
-    sa2 = *reinterpret_cast<const uint4*>(aptr[2] + k0);
-    sa3 = *reinterpret_cast<const uint4*>(aptr[3] + k0);
-    sb0 = *reinterpret_cast<const uint4*>(bptr[0] + k0);
-    sb1 = *reinterpret_cast<const uint4*>(bptr[1] + k0);
-  };
+  uint4 xa0, xa1, xa2, xa3, xb0, xb1, ya0, ya1, ya2, ya3, yb0, yb1;
   const int stage_off = srow * kTilePitch + 16 * piece;
-  auto stage = [&](int buf) {
-    unsigned char* a = &lds_a[buf][stage_off];
-    unsigned char* b = &lds_b[buf][stage_off];
-    *reinterpret_cast<uint4*>(a) = sa0;
-    *reinterpret_cast<uint4*>(a + 32 * kTilePitch) = sa1;
-    *reinterpret_cast<uint4*>(a + 64 * kTilePitch) = sa2;
-    *reinterpret_cast<uint4*>(a + 96 * kTilePitch) = sa3;
-    *reinterpret_cast<uint4*>(b) = sb0;
-    *reinterpret_cast<uint4*>(b + 32 * kTilePitch) = sb1;
-  };
+#define RTP_TILED_FETCH(w, k0)                                 \
+  do {                                                         \
+    w##a0 = *reinterpret_cast<const uint4*>(aptr[0] + (k0));   \
+    w##a1 = *reinterpret_cast<const uint4*>(aptr[1] + (k0));   \
+    w##a2 = *reinterpret_cast<const uint4*>(aptr[2] + (k0));   \
+    w##a3 = *reinterpret_cast<const uint4*>(aptr[3] + (k0));   \
+    w##b0 = *reinterpret_cast<const uint4*>(bptr[0] + (k0));   \
+    w##b1 = *reinterpret_cast<const uint4*>(bptr[1] + (k0));   \
+  } while (0)
+#define RTP_TILED_STAGE(buf, w)                                                 \
+  do {                                                                          \
+    unsigned char* sa_ = &lds_a[buf][stage_off];                                \
+    unsigned char* sb_ = &lds_b[buf][stage_off];                                \
+    *reinterpret_cast<uint4*>(sa_) = w##a0;                                     \
+    *reinterpret_cast<uint4*>(sa_ + 32 * kTilePitch) = w##a1;                   \
+    *reinterpret_cast<uint4*>(sa_ + 64 * kTilePitch) = w##a2;                   \
+    *reinterpret_cast<uint4*>(sa_ + 96 * kTilePitch) = w##a3;                   \
+    *reinterpret_cast<uint4*>(sb_) = w##b0;                                     \
+    *reinterpret_cast<uint4*>(sb_ + 32 * kTilePitch) = w##b1;                   \
+  } while (0)
 
   // fp64 sums of the flushed partials, and two sets of fp32 accumulators for the matrix
   // instructions: while a step's instructions fill one set, the previous step's partials
@@ -176,28 +187,29 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
         for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(before[t][u][v]);
   };
 
-  // The next step's rows are requested before this step's arithmetic and go to the other
-  // LDS buffer after it (the last step asks for its own rows again, so that the requests
-  // and the staging are the same instructions in every step and the compiler keeps the
-  // rows in registers); the barriers for the instruction scheduler keep the requests ahead
-  // of the arithmetic and the staging behind it.
-  fetch(0);
-  stage(0);
+  // The last steps ask for the last step's rows again, so that the requests and the staging
+  // are the same instructions in every step; the barriers for the instruction scheduler
+  // keep the requests ahead of the arithmetic and the staging behind it.
+  RTP_TILED_FETCH(x, 0);
+  RTP_TILED_STAGE(0, x);
+  RTP_TILED_FETCH(x, kTileStep);                      // step 1's
   __syncthreads();
   for (int s = 0; s < steps; s += 2) {                // steps is even
-    fetch((s + 1) * kTileStep);
+    RTP_TILED_FETCH(y, min(s + 2, steps - 1) * kTileStep);
     __builtin_amdgcn_sched_barrier(0);
     step(0, part0, part1);
     __builtin_amdgcn_sched_barrier(0);
-    stage(1);
+    RTP_TILED_STAGE(1, x);
     __syncthreads();
-    fetch(min(s + 2, steps - 1) * kTileStep);
+    RTP_TILED_FETCH(x, min(s + 3, steps - 1) * kTileStep);
     __builtin_amdgcn_sched_barrier(0);
     step(1, part1, part0);
     __builtin_amdgcn_sched_barrier(0);
-    stage(0);
+    RTP_TILED_STAGE(0, y);
     __syncthreads();
   }
+#undef RTP_TILED_FETCH
+#undef RTP_TILED_STAGE
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -206,42 +218,67 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
       for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(part1[t][u][v]);
 
   // accumulator element v of lane l is (kept row 4 (l / 16) + v, pruned row l % 16) of its tile.
-  // Reciprocal norms once per row and column; exp through the fp32 unit when K is
-  // stored in fp32 anyway: with y = x log2(e) = k + f, |f| <= 1/2 split in fp64,
-  // exp(x) = 2^k 2^f and v_exp_f32 gives 2^f to about 1e-7 relative, which on the
-  // score is eps * 1e-7.
-  double rni[4][4];
+  // exp through the fp32 unit when K is stored in fp32 for the sweep kernels: with
+  // y = x log2(e) = k + f, |f| <= 1/2 split in fp64, exp(x) = 2^k 2^f and v_exp_f32 gives
+  // 2^f to about 1e-7 relative, which on the score is eps * 1e-7.
+  const int il0 = 64 * wm + 4 * (lane >> 4), jl0 = 32 * wn + (lane & 15);
+  auto kernel_f32 = [&](double x) -> float {
+    if (!fast_exp) return static_cast<float>(exp_nonpositive(x));
+    const double y = x * 1.4426950408889634;
+    const double k = rint(y);
+    return ldexpf(__builtin_amdgcn_exp2f(static_cast<float>(y - k)), static_cast<int>(k));
+  };
+  if (k_f32 && !scores_out) {
+    // the tile's entries go through LDS (the staging buffers are free: every wave is past
+    // the loop's last barrier), so that they leave as whole 16-byte pieces of rows
+    constexpr int kOutPitch = kTileCols + 4;         // floats
+    static_assert(kTileRows * kOutPitch * 4 <= 2 * kTileRows * kTilePitch, "the output tile fits the staging buffers");
+    float* tile = reinterpret_cast<float*>(&lds_a[0][0]);
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+    for (int u = 0; u < 2; ++u) {
+      const int jl = jl0 + 16 * u;
+      const double rnj = rnorm[kTileRows + jl];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int i = min(i0 + 64 * wm + 16 * t + 4 * (lane >> 4) + v, m - 1);
-      rni[t][v] = 1.0 / fmax(norm64[lo + clamp_index(sel[i], n)], kTinyNorm);
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int il = il0 + 16 * t + v;
+          float kv = 0.f;
+          if (i0 + il < m && j0 + jl < r) {
+            kv = kernel_f32((acc[t][u][v] * rnorm[il] * rnj - p.shift) * inv_eps);
+          }
+          tile[il * kOutPitch + jl] = kv;
+        }
     }
+    __syncthreads();
+    float* kout = k32_base(kmat, po);
+    const int pitch = k32_pitch(r);                  // a multiple of 4: r > kTiledMinPruned
+    const int c4 = 4 * (tid & 15);
+#pragma unroll
+    for (int q = 0; q < kTileRows / 16; ++q) {
+      const int il = (tid >> 4) + 16 * q;
+      if (i0 + il < m && j0 + c4 < pitch)
+        *reinterpret_cast<float4*>(kout + static_cast<long long>(i0 + il) * pitch + j0 + c4) =
+            *reinterpret_cast<const float4*>(tile + il * kOutPitch + c4);
+    }
+    return;
+  }
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int j = j0 + 32 * wn + 16 * u + (lane & 15);
+    const int jl = jl0 + 16 * u, j = j0 + jl;
     if (j >= r) continue;
-    const double rnj = 1.0 / fmax(norm64[lo + clamp_index(sel[m + j], n)], kTinyNorm);
+    const double rnj = rnorm[kTileRows + jl];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int i = i0 + 64 * wm + 16 * t + 4 * (lane >> 4) + v;
+        const int il = il0 + 16 * t + v, i = i0 + il;
         if (i < m) {
-          const double sc = acc[t][u][v] * rni[t][v] * rnj;
+          const double sc = acc[t][u][v] * rnorm[il] * rnj;
           const long long at = static_cast<long long>(i) * r + j;
           const double x = (sc - p.shift) * inv_eps;
-          if (!fast_exp && k_f32) {
-            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = static_cast<float>(exp_nonpositive(x));
-          } else if (k_f32) {
-            const double y = x * 1.4426950408889634;
-            const double k = rint(y);
-            const float frac = __builtin_amdgcn_exp2f(static_cast<float>(y - k));
-            k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = ldexpf(frac, static_cast<int>(k));
-          } else {
-            kmat[po + at] = exp_nonpositive(x);
-          }
+          if (k_f32) k32_base(kmat, po)[static_cast<long long>(i) * k32_pitch(r) + j] = kernel_f32(x);
+          else kmat[po + at] = exp_nonpositive(x);
           if (scores_out) scores_out[po + at] = sc;
         }
       }
