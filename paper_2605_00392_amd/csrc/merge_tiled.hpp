@@ -12,7 +12,12 @@
 //
 // Workgroup = 4 waves as 2 x 2 on a tile of 128 kept rows x 128 features, 32
 // pruned rows per step, LDS double-buffered; a wave owns 64 x 64 = 4 x 4 matrix
-// tiles.  LDS rows are 64 bytes of payload on a pitch of 80.  The finished tile
+// tiles.  P's LDS rows are 64 bytes of payload on a pitch of 80.  A feature row of
+// the turned pruned rows has its four 16-byte pieces (eight pruned rows each) in
+// four of eight slots, slot = piece ^ (feature / 16 % 8), on a pitch of 144: the
+// 64 lanes of a turning 4-byte write (16 groups of eight features x 4 pairs of
+// pruned rows) then fall into 64 different banks (with the pieces in place they
+// fell into 8), and the fragment reads stay conflict-free.  The finished tile
 // goes through LDS once more so that the kept rows are read and the merged rows
 // written 16 bytes per lane.
 #pragma once
@@ -25,9 +30,10 @@ namespace rtp {
 constexpr int kMergeTileRows = 128;    // kept rows per workgroup tile
 constexpr int kMergeTileCols = 128;    // features per workgroup tile
 constexpr int kMergeTileStep = 32;     // pruned rows per step
-constexpr int kMergeTilePitch = 80;    // LDS bytes per staged row (32 bf16 + padding)
+constexpr int kMergeTilePitch = 80;    // LDS bytes per staged row of P (32 bf16 + padding)
+constexpr int kMergeTurnedPitch = 144; // LDS bytes per feature row of the turned pruned rows: eight 16-byte slots + padding
 constexpr int kMergeTiledThreads = 256;
-constexpr int kMergeTiledLdsBytes = 2 * 3 * 128 * 80;   // merge_tile's LDS buffer (its staging tiles; the output tile fits too)
+constexpr int kMergeTiledLdsBytes = 2 * 128 * (2 * kMergeTilePitch + kMergeTurnedPitch);   // merge_tile's LDS buffer (its staging tiles; the output tile fits too)
 constexpr int kMergeOutPitch = kMergeTileCols + 4;   // floats per row of the output staging tile
 
 // What both launch forms of the kernel pass on.
@@ -71,8 +77,9 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
 
-  constexpr int kOperand = kMergeTileRows * kMergeTilePitch;          // one staged operand
-  constexpr int kStageBytes = 2 * 3 * kOperand;                       // [buffer][P hi, P lo, T^T]
+  constexpr int kOperand = kMergeTileRows * kMergeTilePitch;          // P hi, P lo: one staged operand each
+  constexpr int kBuffer = 2 * kOperand + kMergeTileCols * kMergeTurnedPitch;   // [P hi, P lo, T^T]
+  constexpr int kStageBytes = 2 * kBuffer;
   constexpr int kOutBytes = 64 * kMergeOutPitch * 4;                  // half of the output tile, fp32
   static_assert(kMergeTiledLdsBytes >= kStageBytes && kMergeTiledLdsBytes >= kOutBytes, "the caller's LDS buffer");
 
@@ -101,13 +108,23 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
     }
   };
   auto stage = [&](int buf, int j0) {
-    unsigned char* base = lds + buf * 3 * kOperand;
+    unsigned char* base = lds + buf * kBuffer;
+    // only the last step can reach past the last pruned row: there, what lies past it is zero
+    if (j0 + kMergeTileStep > r) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j0 + pj + e >= r) pv[q][e] = 0.f;
+      if (j0 + 2 * tjp >= r) tv[0] = make_uint4(0u, 0u, 0u, 0u);
+      if (j0 + 2 * tjp + 1 >= r) tv[1] = make_uint4(0u, 0u, 0u, 0u);
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float hi[4], lo4[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float v = (j0 + pj + e < r) ? pv[q][e] : 0.f;          // past the last pruned row: no contribution
+        const float v = pv[q][e];
         hi[e] = bf16_to_f32(f32_to_bf16(v));
         lo4[e] = v - hi[e];
       }
@@ -120,14 +137,16 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
       *reinterpret_cast<uint2*>(base + off) = h2;
       *reinterpret_cast<uint2*>(base + kOperand + off) = l2;
     }
-    // transposed: feature row 8 tdg + e gets the pair (pruned row 2 tjp, 2 tjp + 1)
-    const bool in0 = j0 + 2 * tjp < r, in1 = j0 + 2 * tjp + 1 < r;
+    // turned: feature row 8 tdg + e gets the pair (pruned row 2 tjp, 2 tjp + 1)
     const uint32_t w0[4] = {tv[0].x, tv[0].y, tv[0].z, tv[0].w}, w1[4] = {tv[1].x, tv[1].y, tv[1].z, tv[1].w};
+    // features 8 tdg .. + 7 share feature / 16, hence the slot of this thread's piece tjp / 4
+    unsigned char* turned = base + 2 * kOperand + 8 * tdg * kMergeTurnedPitch +
+                            16 * ((tjp >> 2) ^ ((tdg >> 1) & 7)) + 4 * (tjp & 3);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const uint32_t a = in0 ? ((e & 1) ? w0[e >> 1] >> 16 : w0[e >> 1] & 0xffffu) : 0u;
-      const uint32_t c = in1 ? ((e & 1) ? w1[e >> 1] >> 16 : w1[e >> 1] & 0xffffu) : 0u;
-      *reinterpret_cast<uint32_t*>(base + 2 * kOperand + (8 * tdg + e) * kMergeTilePitch + 4 * tjp) = a | (c << 16);
+      const uint32_t a = (e & 1) ? w0[e >> 1] >> 16 : w0[e >> 1] & 0xffffu;
+      const uint32_t c = (e & 1) ? w1[e >> 1] & 0xffff0000u : w1[e >> 1] << 16;
+      *reinterpret_cast<uint32_t*>(turned + e * kMergeTurnedPitch) = a | c;
     }
   };
 
@@ -146,13 +165,14 @@ __device__ __forceinline__ void merge_tile(const MergeTiledArgs& A, int b, int t
   for (int s = 0; s < steps; ++s) {
     const int buf = s & 1;
     if (s + 1 < steps) fetch((s + 1) * kMergeTileStep);
-    const unsigned char* base = lds + buf * 3 * kOperand;
+    const unsigned char* base = lds + buf * kBuffer;
     uint4 fh[4], fl[4], fb[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       fh[t] = *reinterpret_cast<const uint4*>(base + (64 * wm + 16 * t) * kMergeTilePitch + frag_off);
       fl[t] = *reinterpret_cast<const uint4*>(base + kOperand + (64 * wm + 16 * t) * kMergeTilePitch + frag_off);
-      fb[t] = *reinterpret_cast<const uint4*>(base + 2 * kOperand + (64 * wn + 16 * t) * kMergeTilePitch + frag_off);
+      fb[t] = *reinterpret_cast<const uint4*>(base + 2 * kOperand + (64 * wn + 16 * t + (lane & 15)) * kMergeTurnedPitch +
+                                              16 * ((lane >> 4) ^ ((4 * wn + t) & 7)));
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t)
