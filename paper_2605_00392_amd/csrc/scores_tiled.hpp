@@ -16,8 +16,9 @@
 //
 // Workgroup = 4 waves as 2 x 2, a wave owns 64 x 32 = 4 x 2 matrix tiles; two
 // workgroups share a CU, so one's arithmetic hides the other's loads.  LDS
-// rows are padded by 16 bytes (pitch 144) so that the 16 lanes of a fragment
-// read, 144 bytes apart, fall into distinct banks.
+// rows are 128 bytes without padding; the 16-byte pieces of a row are permuted
+// by the row's number so that the 16 lanes of a fragment read fall into
+// distinct banks.
 #pragma once
 #include "common.hpp"
 #include "scores_mfma.hpp"
@@ -28,7 +29,7 @@ namespace rtp {
 constexpr int kTileRows = 128;         // kept rows per workgroup tile
 constexpr int kTileCols = 64;          // pruned rows per workgroup tile
 constexpr int kTileStep = 64;          // contraction elements per step (128 bytes per row)
-constexpr int kTilePitch = 144;        // LDS bytes per staged row
+constexpr int kTilePitch = 128;        // LDS bytes per staged row: eight 16-byte slots, no padding
 constexpr int kTiledThreads = 256;
 
 __host__ __device__ inline bool score_is_tiled(int r) { return r > kTiledMinPruned; }
@@ -80,8 +81,12 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   const int wm = wave >> 1, wn = wave & 1;          // the wave's 64 x 32 part of the tile
   const double inv_eps = 1.0 / p.eps;
 
-  __shared__ __attribute__((aligned(16))) unsigned char lds_a[2][kTileRows * kTilePitch];   // [buffer]
-  __shared__ __attribute__((aligned(16))) unsigned char lds_b[2][kTileCols * kTilePitch];
+  // [buffer][kept rows, pruned rows]; piece c (16 bytes) of row i sits in slot c ^ (i / 2 % 8), so
+  // that the 16 rows of a fragment read fall into different banks without padding
+  constexpr int kBufBytes = (kTileRows + kTileCols) * kTilePitch;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
+  unsigned char* const lds_a = lds;
+  unsigned char* const lds_b = lds + kTileRows * kTilePitch;
   __shared__ double rnorm[kTileRows + kTileCols];    // reciprocal norms of the tile's rows and columns
 
   // staging: thread t moves piece t % 8 (16 bytes) of rows t / 8 + 32 q of each operand
@@ -114,7 +119,7 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // right behind their request.
   const int steps = D / kTileStep;                   // even: D is a multiple of 128 on this path
   uint4 xa0, xa1, xa2, xa3, xb0, xb1, ya0, ya1, ya2, ya3, yb0, yb1;
-  const int stage_off = srow * kTilePitch + 16 * piece;
+  const int stage_off = srow * kTilePitch + 16 * (piece ^ ((srow >> 1) & 7));   // rows + 32 q: the same slot
 #define RTP_TILED_FETCH(w, k0)                                 \
   do {                                                         \
     w##a0 = *reinterpret_cast<const uint4*>(aptr[0] + (k0));   \
@@ -126,8 +131,8 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   } while (0)
 #define RTP_TILED_STAGE(buf, w)                                                 \
   do {                                                                          \
-    unsigned char* sa_ = &lds_a[buf][stage_off];                                \
-    unsigned char* sb_ = &lds_b[buf][stage_off];                                \
+    unsigned char* sa_ = lds_a + (buf) * kBufBytes + stage_off;                 \
+    unsigned char* sb_ = lds_b + (buf) * kBufBytes + stage_off;                 \
     *reinterpret_cast<uint4*>(sa_) = w##a0;                                     \
     *reinterpret_cast<uint4*>(sa_ + 32 * kTilePitch) = w##a1;                   \
     *reinterpret_cast<uint4*>(sa_ + 64 * kTilePitch) = w##a2;                   \
@@ -155,22 +160,23 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // fragment of a 16-row tile for half h of the step: lane l reads the 16 bytes
   // at row l % 16, elements 16 (l / 16) + 8 h .. + 7 of the step - the same
   // assignment of contraction elements to lanes for both operands
-  const int frag_off = (lane & 15) * kTilePitch + 32 * (lane >> 4);
-  const unsigned char* frag_a = &lds_a[0][wm * 64 * kTilePitch + frag_off];
-  const unsigned char* frag_b = &lds_b[0][wn * 32 * kTilePitch + frag_off];
+  const int frag_row = (lane & 15) * kTilePitch, frag_slot = (2 * (lane >> 4)) ^ ((lane & 15) >> 1);
+  const int frag_off[2] = {frag_row + 16 * frag_slot, frag_row + 16 * (frag_slot ^ 1)};   // halves 0 and 1
+  const unsigned char* frag_a = lds_a + wm * 64 * kTilePitch;
+  const unsigned char* frag_b = lds_b + wn * 32 * kTilePitch;
   // one step: the two matrix instructions per 16 x 16 tile of the wave, the first on a zero
   // accumulator, into `now`; and `before`, the previous step's partials, added to the sums
   auto step = [&](int buf, floatx4_t (&now)[4][2], const floatx4_t (&before)[4][2]) {
-    const unsigned char* A = frag_a + buf * (kTileRows * kTilePitch);
-    const unsigned char* B = frag_b + buf * (kTileCols * kTilePitch);
+    const unsigned char* A = frag_a + buf * kBufBytes;
+    const unsigned char* B = frag_b + buf * kBufBytes;
     const floatx4_t zero{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       uint4 fa[4], fb[2];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) fa[t] = *reinterpret_cast<const uint4*>(A + 16 * t * kTilePitch + 16 * h);
+      for (int t = 0; t < 4; ++t) fa[t] = *reinterpret_cast<const uint4*>(A + 16 * t * kTilePitch + frag_off[h]);
 #pragma unroll
-      for (int u = 0; u < 2; ++u) fb[u] = *reinterpret_cast<const uint4*>(B + 16 * u * kTilePitch + 16 * h);
+      for (int u = 0; u < 2; ++u) fb[u] = *reinterpret_cast<const uint4*>(B + 16 * u * kTilePitch + frag_off[h]);
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -232,8 +238,8 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
     // the tile's entries go through LDS (the staging buffers are free: every wave is past
     // the loop's last barrier), so that they leave as whole 16-byte pieces of rows
     constexpr int kOutPitch = kTileCols + 4;         // floats
-    static_assert(kTileRows * kOutPitch * 4 <= 2 * kTileRows * kTilePitch, "the output tile fits the staging buffers");
-    float* tile = reinterpret_cast<float*>(&lds_a[0][0]);
+    static_assert(kTileRows * kOutPitch * 4 <= 2 * kBufBytes, "the output tile fits the staging buffers");
+    float* tile = reinterpret_cast<float*>(lds);
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int jl = jl0 + 16 * u;
