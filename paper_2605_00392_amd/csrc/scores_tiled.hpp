@@ -50,6 +50,25 @@ struct ScoresTiledArgs {
   int tiles_n;
 };
 
+// Sixteen bytes per lane from memory straight into LDS: lane l's land at LDS byte address
+// `lds_base` + 16 l (`lds_base` the same in all lanes).  Written as assembly because the
+// compiler, for the builtin of the same instruction, makes LDS reads wait for every such load
+// in flight when it cannot tell their buffers apart, which would undo requesting rows two
+// steps ahead; the caller waits for them itself (they count in vmcnt, and are done when
+// their data is in LDS).  M0 holds the LDS base for the instruction and is put back.
+__device__ __forceinline__ void load_to_lds_16(const void* src, uint32_t lds_base) {
+  uint32_t m0_before;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(m0_before)
+      : "v"(src), "s"(lds_base)
+      : "memory");
+}
+
 // Tile `tile` (kept-row tile major) of image b.
 __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int tile) {
   const bf16_t* __restrict__ tokens = A.tokens;
@@ -81,18 +100,24 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   const int wm = wave >> 1, wn = wave & 1;          // the wave's 64 x 32 part of the tile
   const double inv_eps = 1.0 / p.eps;
 
-  // [buffer][kept rows, pruned rows]; piece c (16 bytes) of row i sits in slot c ^ (i / 2 % 8), so
-  // that the 16 rows of a fragment read fall into different banks without padding
+  // Three staging buffers, [kept rows, pruned rows] each, separate arrays so that the compiler
+  // can tell a buffer that loads are writing from the one being read.  Piece c (16 bytes) of
+  // row i sits in slot c ^ (i / 2 % 8), so that the 16 rows of a fragment read fall into
+  // different banks without padding.
   constexpr int kBufBytes = (kTileRows + kTileCols) * kTilePitch;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
-  unsigned char* const lds_a = lds;
-  unsigned char* const lds_b = lds + kTileRows * kTilePitch;
+  constexpr int kBufB = kTileRows * kTilePitch;      // where a buffer's pruned rows start
+  __shared__ __attribute__((aligned(16))) unsigned char lds0[kBufBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char lds1[kBufBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char lds2[kBufBytes];
   __shared__ double rnorm[kTileRows + kTileCols];    // reciprocal norms of the tile's rows and columns
 
-  // staging: thread t moves piece t % 8 (16 bytes) of rows t / 8 + 32 q of each operand
+  // Staging: the rows go from memory straight into LDS (global_load_lds_dwordx4: lane l's 16
+  // bytes land at the wave's LDS base + 16 l, so a wave's request fills eight rows): thread t
+  // fills slot t % 8 of rows t / 8 + 32 q of each operand, i.e. fetches piece
+  // (t % 8) ^ (row / 2 % 8) of that row.
   constexpr int QA = kTileRows / 32, QB = kTileCols / 32;
   static_assert(QA == 4 && QB == 2, "the staging below is written out for these counts");
-  const int piece = tid & 7, srow = tid >> 3;
+  const int srow = tid >> 3, piece = (tid & 7) ^ ((srow >> 1) & 7);   // rows + 32 q: the same piece
   const bf16_t* aptr[QA];
   const bf16_t* bptr[QB];
 #pragma unroll
@@ -113,32 +138,33 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   }
 
   // Rows are requested two steps before their arithmetic (a step is shorter than a trip to
-  // memory that misses the L2) into one of two sets of registers, and go to the LDS buffer
-  // that the previous step has finished with.  Named registers, not arrays or structs: an
-  // array that lives across the step loop can end up in LDS, with a wait for the rows
-  // right behind their request.
+  // memory that misses the L2), into the buffer that the previous step has finished with.
   const int steps = D / kTileStep;                   // even: D is a multiple of 128 on this path
-  uint4 xa0, xa1, xa2, xa3, xb0, xb1, ya0, ya1, ya2, ya3, yb0, yb1;
-  const int stage_off = srow * kTilePitch + 16 * (piece ^ ((srow >> 1) & 7));   // rows + 32 q: the same slot
-#define RTP_TILED_FETCH(w, k0)                                 \
-  do {                                                         \
-    w##a0 = *reinterpret_cast<const uint4*>(aptr[0] + (k0));   \
-    w##a1 = *reinterpret_cast<const uint4*>(aptr[1] + (k0));   \
-    w##a2 = *reinterpret_cast<const uint4*>(aptr[2] + (k0));   \
-    w##a3 = *reinterpret_cast<const uint4*>(aptr[3] + (k0));   \
-    w##b0 = *reinterpret_cast<const uint4*>(bptr[0] + (k0));   \
-    w##b1 = *reinterpret_cast<const uint4*>(bptr[1] + (k0));   \
+  // LDS byte addresses of the eight rows this wave's requests fill (+ 32 q rows), per buffer
+  typedef __attribute__((address_space(3))) unsigned char* lds_ptr_t;
+  const uint32_t wave_rows = 8 * wave * kTilePitch;
+  const uint32_t base0 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)lds0)) + wave_rows);
+  const uint32_t base1 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)lds1)) + wave_rows);
+  const uint32_t base2 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)lds2)) + wave_rows);
+#define RTP_TILED_REQUEST(base, k0)                                                            \
+  do {                                                                                         \
+    _Pragma("unroll") for (int q = 0; q < QA; ++q)                                             \
+      load_to_lds_16(aptr[q] + (k0), (base) + 32 * q * kTilePitch);                            \
+    _Pragma("unroll") for (int q = 0; q < QB; ++q)                                             \
+      load_to_lds_16(bptr[q] + (k0), (base) + kBufB + 32 * q * kTilePitch);                    \
   } while (0)
-#define RTP_TILED_STAGE(buf, w)                                                 \
-  do {                                                                          \
-    unsigned char* sa_ = lds_a + (buf) * kBufBytes + stage_off;                 \
-    unsigned char* sb_ = lds_b + (buf) * kBufBytes + stage_off;                 \
-    *reinterpret_cast<uint4*>(sa_) = w##a0;                                     \
-    *reinterpret_cast<uint4*>(sa_ + 32 * kTilePitch) = w##a1;                   \
-    *reinterpret_cast<uint4*>(sa_ + 64 * kTilePitch) = w##a2;                   \
-    *reinterpret_cast<uint4*>(sa_ + 96 * kTilePitch) = w##a3;                   \
-    *reinterpret_cast<uint4*>(sb_) = w##b0;                                     \
-    *reinterpret_cast<uint4*>(sb_ + 32 * kTilePitch) = w##b1;                   \
+  // Before the workgroup meets, a wave's requests but the latest six (one step's) have
+  // landed in LDS (vmcnt counts a request done when its data is written) and its LDS reads
+  // are over.  The wait is written out: a workgroup-scope fence would wait for every request,
+  // the latest too.  The wavefront-scope fences emit nothing; they keep the compiler from
+  // moving LDS accesses across the meeting.
+#define RTP_TILED_MEET(newest)                                                           \
+  do {                                                                                   \
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");                               \
+    if (newest) __builtin_amdgcn_s_waitcnt(0x0076); /* vmcnt(6) lgkmcnt(0) */            \
+    else __builtin_amdgcn_s_waitcnt(0x0070);        /* vmcnt(0) lgkmcnt(0) */            \
+    __builtin_amdgcn_s_barrier();                                                        \
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");                               \
   } while (0)
 
   // fp64 sums of the flushed partials, and two sets of fp32 accumulators for the matrix
@@ -162,13 +188,12 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // assignment of contraction elements to lanes for both operands
   const int frag_row = (lane & 15) * kTilePitch, frag_slot = (2 * (lane >> 4)) ^ ((lane & 15) >> 1);
   const int frag_off[2] = {frag_row + 16 * frag_slot, frag_row + 16 * (frag_slot ^ 1)};   // halves 0 and 1
-  const unsigned char* frag_a = lds_a + wm * 64 * kTilePitch;
-  const unsigned char* frag_b = lds_b + wn * 32 * kTilePitch;
+  const int frag_a = wm * 64 * kTilePitch, frag_b = kBufB + wn * 32 * kTilePitch;
   // one step: the two matrix instructions per 16 x 16 tile of the wave, the first on a zero
   // accumulator, into `now`; and `before`, the previous step's partials, added to the sums
-  auto step = [&](int buf, floatx4_t (&now)[4][2], const floatx4_t (&before)[4][2]) {
-    const unsigned char* A = frag_a + buf * kBufBytes;
-    const unsigned char* B = frag_b + buf * kBufBytes;
+  auto step = [&](const unsigned char* buf, floatx4_t (&now)[4][2], const floatx4_t (&before)[4][2]) {
+    const unsigned char* A = buf + frag_a;
+    const unsigned char* B = buf + frag_b;
     const floatx4_t zero{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -193,29 +218,33 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
         for (int v = 0; v < 4; ++v) acc[t][u][v] += static_cast<double>(before[t][u][v]);
   };
 
-  // The last steps ask for the last step's rows again, so that the requests and the staging
-  // are the same instructions in every step; the barriers for the instruction scheduler
-  // keep the requests ahead of the arithmetic and the staging behind it.
-  RTP_TILED_FETCH(x, 0);
-  RTP_TILED_STAGE(0, x);
-  RTP_TILED_FETCH(x, kTileStep);                      // step 1's
-  __syncthreads();
-  for (int s = 0; s < steps; s += 2) {                // steps is even
-    RTP_TILED_FETCH(y, min(s + 2, steps - 1) * kTileStep);
-    __builtin_amdgcn_sched_barrier(0);
-    step(0, part0, part1);
-    __builtin_amdgcn_sched_barrier(0);
-    RTP_TILED_STAGE(1, x);
-    __syncthreads();
-    RTP_TILED_FETCH(x, min(s + 3, steps - 1) * kTileStep);
-    __builtin_amdgcn_sched_barrier(0);
-    step(1, part1, part0);
-    __builtin_amdgcn_sched_barrier(0);
-    RTP_TILED_STAGE(0, y);
-    __syncthreads();
+  // Step s reads buffer s % 3 and accumulates in set s % 2, so the loop is written out for six
+  // steps; the last steps ask for the last step's rows again, so that every step issues the
+  // same requests.  The barriers for the instruction scheduler keep the requests ahead of
+  // the arithmetic.
+#define RTP_TILED_STEP(i, rd, wr, now, before)                             \
+  if (s + (i) < steps) {                                                   \
+    RTP_TILED_REQUEST(wr, min(s + (i) + 2, steps - 1) * kTileStep);        \
+    __builtin_amdgcn_sched_barrier(0);                                     \
+    step(rd, now, before);                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                     \
+    RTP_TILED_MEET(true);                                                  \
   }
-#undef RTP_TILED_FETCH
-#undef RTP_TILED_STAGE
+  RTP_TILED_REQUEST(base0, 0);
+  RTP_TILED_REQUEST(base1, kTileStep);
+  RTP_TILED_MEET(true);
+  for (int s = 0; s < steps; s += 6) {
+    RTP_TILED_STEP(0, lds0, base2, part0, part1)
+    RTP_TILED_STEP(1, lds1, base0, part1, part0)
+    RTP_TILED_STEP(2, lds2, base1, part0, part1)
+    RTP_TILED_STEP(3, lds0, base2, part1, part0)
+    RTP_TILED_STEP(4, lds1, base0, part0, part1)
+    RTP_TILED_STEP(5, lds2, base1, part1, part0)
+  }
+  RTP_TILED_MEET(false);                              // every request has landed: the buffers are free
+#undef RTP_TILED_STEP
+#undef RTP_TILED_REQUEST
+#undef RTP_TILED_MEET
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -238,8 +267,8 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
     // the tile's entries go through LDS (the staging buffers are free: every wave is past
     // the loop's last barrier), so that they leave as whole 16-byte pieces of rows
     constexpr int kOutPitch = kTileCols + 4;         // floats
-    static_assert(kTileRows * kOutPitch * 4 <= 2 * kBufBytes, "the output tile fits the staging buffers");
-    float* tile = reinterpret_cast<float*>(lds);
+    static_assert(kTileRows / 2 * kOutPitch * 4 <= kBufBytes, "half of the output tile fits a staging buffer");
+    float* tile = reinterpret_cast<float*>(wm ? lds1 : lds0) - (wm ? 64 * kOutPitch : 0);   // this wave's rows
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int jl = jl0 + 16 * u;
@@ -265,7 +294,8 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
       const int il = (tid >> 4) + 16 * q;
       if (i0 + il < m && j0 + c4 < pitch)
         *reinterpret_cast<float4*>(kout + static_cast<long long>(i0 + il) * pitch + j0 + c4) =
-            *reinterpret_cast<const float4*>(tile + il * kOutPitch + c4);
+            *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(q < kTileRows / 32 ? lds0 : lds1) +
+                                             (il & 63) * kOutPitch + c4);
     }
     return;
   }
