@@ -498,6 +498,22 @@ def test_matrix_core_tiles_at_their_edges(counts, ratio):
     np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
 
 
+@pytest.mark.parametrize("d", [128, 384, 512, 896])
+def test_tiled_scores_at_other_step_counts(d):
+    """The tiled score kernel walks the width 64 elements a step, with three staging buffers
+    and two accumulator sets in turn (a pattern of six steps): 2, 6, 8 and 14 steps, tiles cut
+    by both edges, the staged call (scores entry by entry) and the fused one."""
+    batch = _clustered([300, 457, 131], d, "bf16", 43, ratio=0.4, iters=10)
+    s = hz.run_staged(batch)
+    rep = hz.compare_batch(batch, s, staged=True)
+    _log(rep, f"tiled scores D={d}")
+    assert rep.max_score_abs <= hz.SCORE_ATOL
+    f = hz.run_prune(batch)
+    rows = int(s["out_offsets"][-1])
+    np.testing.assert_array_equal(f["out"][:rows], s["out"][:rows])
+    np.testing.assert_array_equal(f["pair"], s["pair"])
+
+
 @pytest.mark.parametrize("counts,ratio,d", [
     ([100, 116, 96], 0.83, 1024),      # 17, 19 and 16 pruned tokens: the last stays with the vector kernel
     ([160, 161], 0.8, 1280),           # 32 pruned tokens (one operand block), 128 and 129 kept rows
