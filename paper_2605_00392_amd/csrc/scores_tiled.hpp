@@ -27,10 +27,11 @@
 namespace rtp {
 
 constexpr int kTileRows = 128;         // kept rows per workgroup tile
-constexpr int kTileCols = 64;          // pruned rows per workgroup tile
+constexpr int kTileCols = 64;          // pruned rows per workgroup tile (128, eight waves: the same time)
 constexpr int kTileStep = 64;          // contraction elements per step (128 bytes per row)
 constexpr int kTilePitch = 128;        // LDS bytes per staged row: eight 16-byte slots, no padding
-constexpr int kTiledThreads = 256;
+constexpr int kTiledWavesN = kTileCols / 32;                   // waves side by side on the pruned rows
+constexpr int kTiledThreads = 64 * 2 * kTiledWavesN;          // 2 x kTiledWavesN waves of 64 x 32
 
 __host__ __device__ inline bool score_is_tiled(int r) { return r > kTiledMinPruned; }
 
@@ -97,7 +98,7 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   const bool fast_exp = k_f32 && sinkhorn_variant(m, r, p.mode) == kVariantSweep;
   const int32_t* sel = sel_idx + lo;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;          // the wave's 64 x 32 part of the tile
+  const int wm = wave / kTiledWavesN, wn = wave % kTiledWavesN;   // the wave's 64 x 32 part of the tile
   const double inv_eps = 1.0 / p.eps;
 
   // Three staging buffers, [kept rows, pruned rows] each, separate arrays so that the compiler
@@ -106,28 +107,29 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
   // different banks without padding.
   constexpr int kBufBytes = (kTileRows + kTileCols) * kTilePitch;
   constexpr int kBufB = kTileRows * kTilePitch;      // where a buffer's pruned rows start
-  __shared__ __attribute__((aligned(16))) unsigned char lds0[kBufBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds1[kBufBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char lds2[kBufBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[3 * kBufBytes];
+  unsigned char* const lds0 = lds;
+  unsigned char* const lds1 = lds + kBufBytes;
+  unsigned char* const lds2 = lds + 2 * kBufBytes;
   __shared__ double rnorm[kTileRows + kTileCols];    // reciprocal norms of the tile's rows and columns
 
   // Staging: the rows go from memory straight into LDS (global_load_lds_dwordx4: lane l's 16
   // bytes land at the wave's LDS base + 16 l, so a wave's request fills eight rows): thread t
   // fills slot t % 8 of rows t / 8 + 32 q of each operand, i.e. fetches piece
   // (t % 8) ^ (row / 2 % 8) of that row.
-  constexpr int QA = kTileRows / 32, QB = kTileCols / 32;
-  static_assert(QA == 4 && QB == 2, "the staging below is written out for these counts");
-  const int srow = tid >> 3, piece = (tid & 7) ^ ((srow >> 1) & 7);   // rows + 32 q: the same piece
+  constexpr int kPass = kTiledThreads / 8;           // rows the workgroup's requests fill at a time
+  constexpr int QA = kTileRows / kPass, QB = kTileCols / kPass;
+  const int srow = tid >> 3, piece = (tid & 7) ^ ((srow >> 1) & 7);   // rows + kPass q: the same piece
   const bf16_t* aptr[QA];
   const bf16_t* bptr[QB];
 #pragma unroll
   for (int q = 0; q < QA; ++q) {
-    const int i = min(i0 + srow + 32 * q, m - 1);
+    const int i = min(i0 + srow + kPass * q, m - 1);
     aptr[q] = tokens + static_cast<size_t>(lo + clamp_index(sel[i], n)) * D + 8 * piece;
   }
 #pragma unroll
   for (int q = 0; q < QB; ++q) {
-    const int j = min(j0 + srow + 32 * q, r - 1);
+    const int j = min(j0 + srow + kPass * q, r - 1);
     bptr[q] = tokens + static_cast<size_t>(lo + clamp_index(sel[m + j], n)) * D + 8 * piece;
   }
   // the reciprocal norms the last part needs, fetched now (two dependent loads) instead of
@@ -149,11 +151,11 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
 #define RTP_TILED_REQUEST(base, k0)                                                            \
   do {                                                                                         \
     _Pragma("unroll") for (int q = 0; q < QA; ++q)                                             \
-      load_to_lds_16(aptr[q] + (k0), (base) + 32 * q * kTilePitch);                            \
+      load_to_lds_16(aptr[q] + (k0), (base) + kPass * q * kTilePitch);                         \
     _Pragma("unroll") for (int q = 0; q < QB; ++q)                                             \
-      load_to_lds_16(bptr[q] + (k0), (base) + kBufB + 32 * q * kTilePitch);                    \
+      load_to_lds_16(bptr[q] + (k0), (base) + kBufB + kPass * q * kTilePitch);                    \
   } while (0)
-  // Before the workgroup meets, a wave's requests but the latest six (one step's) have
+  // Before the workgroup meets, a wave's requests but the latest QA + QB (one step's) have
   // landed in LDS (vmcnt counts a request done when its data is written) and its LDS reads
   // are over.  The wait is written out: a workgroup-scope fence would wait for every request,
   // the latest too.  The wavefront-scope fences emit nothing; they keep the compiler from
@@ -161,7 +163,7 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
 #define RTP_TILED_MEET(newest)                                                           \
   do {                                                                                   \
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");                               \
-    if (newest) __builtin_amdgcn_s_waitcnt(0x0076); /* vmcnt(6) lgkmcnt(0) */            \
+    if (newest) __builtin_amdgcn_s_waitcnt(0x0070 | (QA + QB)); /* vmcnt(one step's requests) lgkmcnt(0) */ \
     else __builtin_amdgcn_s_waitcnt(0x0070);        /* vmcnt(0) lgkmcnt(0) */            \
     __builtin_amdgcn_s_barrier();                                                        \
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");                               \
@@ -267,8 +269,8 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
     // the tile's entries go through LDS (the staging buffers are free: every wave is past
     // the loop's last barrier), so that they leave as whole 16-byte pieces of rows
     constexpr int kOutPitch = kTileCols + 4;         // floats
-    static_assert(kTileRows / 2 * kOutPitch * 4 <= kBufBytes, "half of the output tile fits a staging buffer");
-    float* tile = reinterpret_cast<float*>(wm ? lds1 : lds0) - (wm ? 64 * kOutPitch : 0);   // this wave's rows
+    static_assert(kTileRows * kOutPitch * 4 <= 3 * kBufBytes, "the output tile fits the staging buffers");
+    float* tile = reinterpret_cast<float*>(lds);
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int jl = jl0 + 16 * u;
@@ -279,23 +281,23 @@ __device__ __forceinline__ void scores_tile(const ScoresTiledArgs& A, int b, int
         for (int v = 0; v < 4; ++v) {
           const int il = il0 + 16 * t + v;
           float kv = 0.f;
-          if (i0 + il < m && j0 + jl < r) {
+          if (i0 + il < m && j0 + jl < r)
             kv = kernel_f32((acc[t][u][v] * rnorm[il] * rnj - p.shift) * inv_eps);
-          }
           tile[il * kOutPitch + jl] = kv;
         }
     }
     __syncthreads();
     float* kout = k32_base(kmat, po);
     const int pitch = k32_pitch(r);                  // a multiple of 4: r > kTiledMinPruned
-    const int c4 = 4 * (tid & 15);
+    constexpr int kRowLanes = kTileCols / 4;         // lanes that cover a row of the tile, 16 bytes each
+    constexpr int kRowsAtOnce = kTiledThreads / kRowLanes;
+    const int c4 = 4 * (tid % kRowLanes);
 #pragma unroll
-    for (int q = 0; q < kTileRows / 16; ++q) {
-      const int il = (tid >> 4) + 16 * q;
+    for (int q = 0; q < kTileRows / kRowsAtOnce; ++q) {
+      const int il = tid / kRowLanes + kRowsAtOnce * q;
       if (i0 + il < m && j0 + c4 < pitch)
         *reinterpret_cast<float4*>(kout + static_cast<long long>(i0 + il) * pitch + j0 + c4) =
-            *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(q < kTileRows / 32 ? lds0 : lds1) +
-                                             (il & 63) * kOutPitch + c4);
+            *reinterpret_cast<const float4*>(tile + il * kOutPitch + c4);
     }
     return;
   }
