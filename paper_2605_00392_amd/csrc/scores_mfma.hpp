@@ -72,6 +72,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_scores_mfma(
   const unsigned linear = blockIdx.x;
   if (job.on && linear == gridDim.x - 1) {
     static_assert(kClassifyLdsBytes <= sizeof(stage) && kScanLdsBytes <= sizeof(stage), "the job works in the stage buffer");
+    static_assert(kScoreThreads == 256, "scan_images and classify_images are written for workgroups of 256 threads");
     scan_images(offsets, keep, B, job.out_offsets, job.plan_offsets, stage, job.stride);
     __syncthreads();
     classify_images(offsets, keep, B, job.work, job.mode, stage);
